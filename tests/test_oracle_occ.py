@@ -1,0 +1,105 @@
+"""Pins for outlier clamping and compensation (Sec. 3.2)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import fp4_oracle as o
+
+F32 = np.float32
+
+
+def test_tail_count_and_printed_densities(golden):
+    g = dict((r[0], float(r[1])) for r in golden("appendix_b.txt"))
+    n = 16384 * 4096
+    for alpha in (0.999, 0.99, 0.97):
+        k = o.occ_tail_count(n, alpha)
+        assert abs(2 * k / n * 100 - g["density_%s" % alpha]) < 1e-3   # 0.2 %, 2 %, 6 %
+    assert o.occ_tail_count(131072, 0.99) == 1310
+    assert o.occ_tail_count(100, 1.0) == 0
+
+
+def test_thresholds_are_order_statistics_by_counting():
+    rng = np.random.default_rng(0)
+    for n, alpha in ((1000, 0.99), (4096, 0.97), (777, 0.999), (50, 0.9)):
+        x = rng.standard_t(3, size=n).astype(F32)
+        x[rng.integers(0, n, n // 10)] = F32(0.5)         # ties
+        lo, hi = o.occ_thresholds(x.reshape(-1, 1), alpha)
+        k = o.occ_tail_count(n, alpha)
+        # v[k] is the unique t with #(x < t) <= k < #(x <= t)
+        assert (x < lo).sum() <= k < (x <= lo).sum()
+        assert (x > hi).sum() <= k < (x >= hi).sum()
+        s = sorted(x.tolist())
+        assert float(lo) == s[k] and float(hi) == s[n - 1 - k]
+        assert lo <= hi
+
+
+def test_gaussian_closed_form():
+    x = np.random.default_rng(1).normal(size=(1000, 1000)).astype(F32)
+    lo, hi = o.occ_thresholds(x, 0.99)
+    assert abs(hi - 2.3263) < 0.02 and abs(lo + 2.3263) < 0.02      # Phi^-1(0.99)
+    lo, hi = o.occ_thresholds(x, 0.999)
+    assert abs(hi - 3.0902) < 0.05 and abs(lo + 3.0902) < 0.05      # Phi^-1(0.999)
+
+
+def test_hand_worked_clamp_and_residual():
+    x = np.array([[-9, 1, 2, 30], [0, 5, -7, 3]], F32)
+    xc, csr = o.occ_clamp_residual(x, F32(-7), F32(5))
+    assert xc.tolist() == [[-7, 1, 2, 5], [0, 5, -7, 3]]
+    assert csr.row_ptr.tolist() == [0, 2, 2]
+    assert csr.col_idx.tolist() == [0, 3] and csr.val.tolist() == [-2, 25]
+    assert csr.to_dense().tolist() == [[-2, 0, 0, 25], [0, 0, 0, 0]]
+
+
+def test_identity_density_and_structure():
+    rng = np.random.default_rng(2)
+    x = rng.normal(size=(128, 256)).astype(F32)
+    x[:, [7, 100]] *= 20
+    for alpha in (0.999, 0.99, 0.97):
+        lo, hi = o.occ_thresholds(x, alpha)
+        xc, csr = o.occ_clamp_residual(x, lo, hi)
+        k = o.occ_tail_count(x.size, alpha)
+        assert csr.val.size == 2 * k                       # continuous data: no ties
+        assert csr.row_ptr[0] == 0 and csr.row_ptr[-1] == csr.val.size
+        assert xc.min() == lo and xc.max() == hi
+        # clamped + residual == original (exact in fp64 up to the residual's rounding)
+        rec = xc.astype(np.float64) + csr.to_dense()
+        ulp = np.spacing(np.abs(csr.to_dense()).astype(F32)).astype(np.float64)
+        assert np.all(np.abs(rec - x) <= 0.5 * ulp + 0)
+        untouched = csr.to_dense() == 0
+        assert np.array_equal(xc[untouched], x[untouched])
+        for r in range(x.shape[0]):
+            c = csr.col_idx[csr.row_ptr[r]:csr.row_ptr[r + 1]]
+            assert np.all(np.diff(c) > 0)
+        assert np.all(csr.val != 0)
+    # alpha = 1: nothing is clamped
+    lo, hi = o.occ_thresholds(x, 1.0)
+    xc, csr = o.occ_clamp_residual(x, lo, hi)
+    assert np.array_equal(xc, x) and csr.val.size == 0
+    with pytest.raises(ValueError):
+        o.occ_thresholds(x, 0.4)
+
+
+def test_clamp_and_compensation_improve_fidelity_in_the_order_of_table_1():
+    # Table 1: no clamp < clamp < clamp+comp; lower alpha -> higher SNR.  Synthetic
+    # activations with a few outlier channels stand in for the paper's tensors.
+    rng = np.random.default_rng(3)
+    x = rng.normal(size=(256, 512)).astype(F32)
+    x[:, [5, 77, 300]] *= 30
+    snr = {}
+    snr["none"] = o.fidelity(x, o.dequantized_activation(x, None, False))[2]
+    snr["clamp999"] = o.fidelity(x, o.dequantized_activation(x, 0.999, False))[2]
+    snr["comp999"] = o.fidelity(x, o.dequantized_activation(x, 0.999, True))[2]
+    snr["comp99"] = o.fidelity(x, o.dequantized_activation(x, 0.99, True))[2]
+    snr["comp97"] = o.fidelity(x, o.dequantized_activation(x, 0.97, True))[2]
+    assert snr["comp999"] > snr["clamp999"]
+    assert snr["comp97"] > snr["comp99"] > snr["comp999"] > snr["none"]
+    cos_none = o.fidelity(x, o.dequantized_activation(x, None, False))[0]
+    cos_comp = o.fidelity(x, o.dequantized_activation(x, 0.99, True))[0]
+    assert cos_comp > cos_none
+    # without clamping most codes of a row holding an outlier underflow to zero
+    codes, _ = o.quantize_rows(x)
+    assert (codes == 0).mean() > 0.5
+    lo, hi = o.occ_thresholds(x, 0.99)
+    codes_c, _ = o.quantize_rows(o.occ_clamp_residual(x, lo, hi)[0])
+    assert (codes_c == 0).mean() < 0.3
