@@ -1,0 +1,184 @@
+/*
+ * fp4_linear.h -- C ABI of the FP4 (E2M1) quantized linear layer for MI355X (gfx950).
+ *
+ * The library implements the hot path of FP4 training as described in
+ * arXiv 2501.17116: for a linear layer Y = A W with A [M x K] (tokens x input
+ * channels) and W [K x N] (input x output channels), both operands are absmax-scaled
+ * along their non-contracted axis, rounded to the 16-value E2M1 grid, multiplied on
+ * the FP4 matrix cores and the two scale vectors divided back out (Sec. 2 Eq. 1;
+ * Fig. 2; Sec. 4.1; App. C.2).  Activations are first clamped at per-tensor quantile
+ * thresholds and the clamped-away part is added back through a sparse high-precision
+ * product (Sec. 3.2).  The weight gradient is multiplied element-wise by the capped
+ * derivative of the differentiable quantization surrogate (Sec. 3.1 Eq. 8).
+ *
+ * Conventions common to every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller unless a parameter
+ *     says "host".  Matrices are row-major.  The library allocates nothing, keeps no
+ *     state between calls and never synchronizes: every call only enqueues kernels on
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Return value: FP4_OK (0) or a negative fp4_status.  Arguments are validated on
+ *     the host before anything is enqueued; on error nothing has been enqueued, except
+ *     FP4_ERR_HIP which reports a failed launch of the call's own kernels.
+ *   - Inputs must be finite.  Tensor base pointers must be 16-byte aligned and leading
+ *     dimensions (in elements) multiples of 8.
+ *   - Packed FP4 tensors ("codes"): two 4-bit codes per byte along the contracted axis,
+ *     element 2t in bits 3:0 and element 2t+1 in bits 7:4, rows densely packed
+ *     (cols/2 bytes per row).  Code = sign, 2 exponent bits, 1 mantissa bit (App. A
+ *     table): 0..7 -> 0, .5, 1, 1.5, 2, 3, 4, 6; 8..15 the negatives; 1000 is never
+ *     produced.
+ *   - Rounding to the grid follows the comparison chain printed in App. A: nearest
+ *     value, a midpoint goes to its upper neighbour (towards +inf) for either sign,
+ *     magnitudes above 6 saturate.
+ *   - Scales are multiplicative, gamma = fl32(6 / absmax) (Eq. 1); gamma = 1 for an
+ *     all-zero vector or when 6/absmax is not finite.  The scaled value is the single
+ *     fp32 product x * gamma.
+ *   - Every GEMM contracts over an axis whose length is a multiple of 32.
+ *   - Workspaces: query with fp4_workspace_bytes(); contents on entry are ignored and
+ *     on exit undefined.  Two calls may share a workspace only if stream order
+ *     serializes them.
+ */
+#ifndef FP4_LINEAR_H
+#define FP4_LINEAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FP4_OK = 0,
+  FP4_ERR_NULL = -1,      /* a required pointer is NULL                                   */
+  FP4_ERR_SHAPE = -2,     /* a dimension <= 0 where not allowed, odd packed length,
+                             contraction length not a multiple of 32, ld too small        */
+  FP4_ERR_DTYPE = -3,     /* unknown fp4_dtype / fp4_axis / op                            */
+  FP4_ERR_ARG = -4,       /* alpha outside (0.5, 1], dge_cap <= 0, misaligned pointer     */
+  FP4_ERR_WORKSPACE = -5, /* workspace NULL or smaller than fp4_workspace_bytes()         */
+  FP4_ERR_CAPACITY = -6,  /* residual buffers smaller than 2*floor((1-alpha)*rows*cols)   */
+  FP4_ERR_HIP = -7        /* a kernel launch failed (hipGetLastError)                     */
+} fp4_status;
+
+typedef enum { FP4_F32 = 0, FP4_BF16 = 1 } fp4_dtype;
+
+typedef enum {
+  FP4_AXIS_ROW = 0, /* one scale per row;    codes [rows x cols/2], cols contiguous       */
+  FP4_AXIS_COL = 1  /* one scale per column; codes TRANSPOSED [cols x rows/2]             */
+} fp4_axis;
+
+typedef enum {
+  FP4_OP_QUANTIZE = 0, /* (M=rows, K=cols, N ignored)                                     */
+  FP4_OP_OCC = 1,      /* (M=rows, K=cols, N ignored)                                     */
+  FP4_OP_FWD = 2,
+  FP4_OP_DGRAD = 3,
+  FP4_OP_WGRAD = 4
+} fp4_op;
+
+/* What the forward pass leaves for the weight-gradient pass (Sec. 3.1 needs the
+ * forward's per-output-channel scales for f'(W_scaled); Sec. 3.2 needs the thresholds
+ * and the residual).  All members are caller-allocated device buffers. */
+typedef struct {
+  float*   gamma_W;    /* [N]   forward scales of W, one per output channel               */
+  float*   thresholds; /* [2]   {lo, hi}; {-inf, +inf} when alpha == 1                    */
+  int64_t* row_ptr;    /* [M+1] CSR of Delta_A = A - clamp(A): row starts                 */
+  int32_t* col_idx;    /* [capacity] column of each entry, ascending inside a row         */
+  float*   val;        /* [capacity] fl32(A[i,c] - threshold)                             */
+  int64_t  capacity;   /* entries available; >= 2*floor((1-alpha)*M*K)                    */
+  int64_t* nnz;        /* [1]   number of entries                                         */
+} fp4_fwd_ctx;
+
+const char* fp4_status_string(int status);
+
+/* Bytes of device workspace an operation needs for the given problem. 0 for a bad op. */
+size_t fp4_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, fp4_dtype dt);
+
+/* Entries the residual buffers must hold: 2*floor((1-alpha)*rows*cols) (Sec. 3.2; the
+ * density 2(1-alpha) is stated in App. B). */
+int64_t fp4_occ_capacity(int64_t rows, int64_t cols, double alpha);
+
+/* Vector-wise absmax quantization (Sec. 2 Eq. 1; Sec. 4.1: token-wise for A,
+ * channel-wise for W).
+ *   x      [rows x cols] of dtype dt, leading dimension ld (elements)
+ *   axis   ROW: gamma[rows], codes [rows x cols/2]   (cols must be even)
+ *          COL: gamma[cols], codes [cols x rows/2]   (rows must be even)
+ *   rows or cols == 0 is allowed and does nothing. */
+int fp4_quantize(const void* x, fp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                 fp4_axis axis, uint8_t* codes, float* gamma,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Outlier clamping and compensation on one tensor (Sec. 3.2).
+ *   thresholds (out, [2]): lo = v[k], hi = v[n-1-k] of the ascending-sorted values,
+ *       k = floor((1-alpha)*rows*cols) evaluated in double, no interpolation.
+ *   x_clamped (optional out, dtype dt, leading dimension ld): clamp(x, lo, hi).
+ *   codes/gamma (optional out, both or neither): row-wise quantization of the clamped
+ *       tensor, as fp4_quantize(axis = ROW) would produce from x_clamped.
+ *   row_ptr/col_idx/val/nnz (out): CSR of x - x_clamped; an entry exists exactly where
+ *       x < lo or x > hi, val = fl32(x - threshold).  capacity as in fp4_occ_capacity. */
+int occ_clamp_residual(const void* x, fp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                       double alpha, float* thresholds, uint8_t* codes, float* gamma,
+                       void* x_clamped, int64_t* row_ptr, int32_t* col_idx, float* val,
+                       int64_t capacity, int64_t* nnz,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Forward: Y = dequant(Q(A_c) Q(W)) + Delta_A W   (Fig. 2; Sec. 3.2; App. C.2).
+ *   A [M x K], W [K x N], Y [M x N], all dtype dt, dense (ld = row length).
+ *   A_c = A clamped at the alpha / 1-alpha order statistics of the whole tensor and
+ *   quantized per token; W quantized per output channel; the residual product uses the
+ *   unquantized W with fp32 accumulation and is added before the single rounding of Y.
+ *   alpha == 1 switches OCC off.  `saved` is filled for fp4_linear_bwd_wgrad. */
+int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
+                   double alpha, void* Y, const fp4_fwd_ctx* saved,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* Activation gradient: dA = dY W^T as an FP4 GEMM contracting over output channels,
+ * dY scaled per token and W per input channel (scales on the non-contracted axes,
+ * Sec. 4.1).  dY [M x N], W [K x N], dA [M x K], dtype dt.  No DGE term (Sec. 3). */
+int fp4_linear_bwd_dgrad(const void* dY, const void* W, fp4_dtype dt,
+                         int64_t M, int64_t K, int64_t N, void* dA,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Weight gradient: dW = (A^T dY) (.) min(dge_cap, f'(W gamma_W))
+ * (Sec. 3.1 Eq. 3-6 and 8; App. C.2 Eq. 22).  A^T dY is an FP4 GEMM contracting over
+ * tokens: A clamped at saved->thresholds and scaled per input channel, dY scaled per
+ * output channel, plus Delta_A^T dY from the saved residual in fp32.  f' uses the
+ * forward's saved->gamma_W.  dge_k <= 0 selects the straight-through estimator (f' = 1).
+ * dW is fp32 [K x N], overwritten. */
+int fp4_linear_bwd_wgrad(const void* A, const void* dY, const void* W, fp4_dtype dt,
+                         int64_t M, int64_t K, int64_t N, const fp4_fwd_ctx* saved,
+                         float dge_k, float dge_cap, float* dW,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- building blocks, exported for parity tests and per-kernel measurement ---- */
+
+/* out[P x Q] = (codes_l[P x Kc/2] . codes_rt[Q x Kc/2]^T) / (gamma_l[p] gamma_r[q]) (+ addend),
+ * the FP4 GEMM with scale dequantization (Fig. 2).  gamma_l / gamma_r NULL = raw fp32
+ * accumulator (then out must be fp32).  addend: optional fp32 [P x Q] (same ld as out)
+ * added before rounding; may alias out when out is fp32. */
+int fp4_gemm(const uint8_t* codes_l, const float* gamma_l, const uint8_t* codes_rt,
+             const float* gamma_r, int64_t P, int64_t Q, int64_t Kc,
+             const float* addend, void* out, fp4_dtype out_dt, int64_t ldo, void* stream);
+
+/* One 4-bit code per output byte (for inspecting packed tensors). */
+int fp4_unpack(const uint8_t* codes, int64_t rows, int64_t cols, uint8_t* one_per_byte,
+               void* stream);
+
+/* dW[k, n] = G[k, n] * min(cap, f'(W[k, n] * gamma_W[n])): the DGE factor as a
+ * stand-alone pass (Sec. 3.1 Eq. 8).  G and dW fp32 [K x N] (may alias), W dtype dt. */
+int fp4_dge_apply(const float* G, const void* W, fp4_dtype dt, const float* gamma_W,
+                  int64_t K, int64_t N, float dge_k, float dge_cap, float* dW, void* stream);
+
+/* R[P x N] (fp32, overwritten) = S D with S a P x Q CSR matrix (fp32 values) and D
+ * [Q x N] dense of dtype dt: the high-precision sparse product of Sec. 3.2. */
+int fp4_residual_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val,
+                      int64_t P, int64_t Q, const void* D, fp4_dtype dt, int64_t N,
+                      float* R, void* stream);
+
+/* Host-side evaluation of the library's own rounding routine: codes[i] = Q(x[i]) for
+ * n fp32 values in HOST memory (the same inline function the kernels use, compiled for
+ * the CPU; lets the rounding be checked exhaustively without a GPU). */
+int fp4_host_round_codes(const float* x_host, int64_t n, uint8_t* codes_host);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FP4_LINEAR_H */

@@ -1,0 +1,299 @@
+// Host side of the C ABI: argument validation, workspace carving and the kernel sequences of
+// the three layer passes (Fig. 2; Sec. 3.1; Sec. 3.2; Sec. 4.1).  Nothing here allocates,
+// synchronizes or keeps state; every buffer is the caller's.
+#include "fp4_common.h"
+
+#include <cmath>
+#include <limits>
+
+// launchers defined next to their kernels
+int fp4_launch_gemm(const uint8_t* L, const float* gl, const uint8_t* Rt, const float* gr, int64_t P,
+                    int64_t Q, int64_t Kc, const float* addend, void* out, int out_bf16, int64_t ldo,
+                    const void* W, int w_bf16, int64_t ldw, const float* gamma_w, float dge_k,
+                    float dge_cap, hipStream_t stream);
+int fp4_launch_quantize_rows(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
+                             uint8_t* codes, float* gamma, hipStream_t s);
+int fp4_launch_occ_rows(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, const float* thr,
+                        uint8_t* codes, float* gamma, void* x_clamped, int32_t* tmp_col, float* tmp_val,
+                        int64_t* row_start, int32_t* row_cnt, unsigned long long* total, int64_t capacity,
+                        hipStream_t s);
+int fp4_launch_quantize_cols(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
+                             const float* clamp_thr, uint8_t* codes_t, float* gamma, uint32_t* amax_scratch,
+                             hipStream_t s);
+size_t fp4_select_scratch_bytes();
+int fp4_launch_thresholds(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, int64_t k,
+                          float* thresholds, void* scratch, unsigned long long* total, hipStream_t s);
+int fp4_launch_csr_finalize(const int32_t* tmp_col, const float* tmp_val, const int64_t* row_start,
+                            const int32_t* row_cnt, int64_t rows, int64_t capacity, int64_t* row_ptr,
+                            int32_t* col_idx, float* val, int64_t* nnz, hipStream_t s);
+int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, const float* val,
+                             const int64_t* nnz, int64_t P, int64_t Q, int64_t capacity, int64_t* t_ptr,
+                             int32_t* t_idx, float* t_val, int32_t* scratch, hipStream_t s);
+int fp4_launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val, int64_t capacity,
+                    int64_t P, const void* D, int bf16, int64_t N, float* R, hipStream_t s);
+
+namespace {
+
+__global__ void init_no_occ_kernel(float* thr, int64_t* row_ptr, int64_t rows, int64_t* nnz) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (row_ptr && i <= rows) row_ptr[i] = 0;
+  if (i == 0) {
+    if (thr) { thr[0] = -INFINITY; thr[1] = INFINITY; }
+    if (nnz) *nnz = 0;
+  }
+}
+
+// Bump allocator over the caller's workspace; every block 256-byte aligned.
+struct Carver {
+  uint8_t* base;
+  size_t off = 0;
+  explicit Carver(void* p) : base(reinterpret_cast<uint8_t*>(p)) {}
+  template <class T>
+  T* take(size_t count) {
+    T* r = reinterpret_cast<T*>(base ? base + off : nullptr);
+    off += align_up(count * sizeof(T), 256);
+    return r;
+  }
+};
+
+inline bool dtype_ok(fp4_dtype dt) { return dt == FP4_F32 || dt == FP4_BF16; }
+inline size_t esize(fp4_dtype dt) { return dt == FP4_BF16 ? 2 : 4; }
+
+int64_t tail_count(int64_t n, double alpha) { return (int64_t)std::floor((1.0 - alpha) * (double)n); }
+
+struct OccTemps {
+  void* select;
+  int32_t* tmp_col;
+  float* tmp_val;
+  int64_t* row_start;
+  int32_t* row_cnt;
+  unsigned long long* total;
+};
+OccTemps carve_occ(Carver& c, int64_t rows, int64_t capacity) {
+  OccTemps t;
+  t.select = c.take<uint8_t>(fp4_select_scratch_bytes());
+  t.tmp_col = c.take<int32_t>((size_t)capacity);
+  t.tmp_val = c.take<float>((size_t)capacity);
+  t.row_start = c.take<int64_t>((size_t)rows);
+  t.row_cnt = c.take<int32_t>((size_t)rows);
+  t.total = c.take<unsigned long long>(1);
+  return t;
+}
+
+struct FwdWs {
+  uint8_t* qA; float* gA; uint8_t* qWt; uint32_t* amax; OccTemps occ; float* R;
+};
+FwdWs carve_fwd(Carver& c, int64_t M, int64_t K, int64_t N, fp4_dtype dt) {
+  FwdWs w;
+  w.qA = c.take<uint8_t>((size_t)(M * K / 2));
+  w.gA = c.take<float>((size_t)M);
+  w.qWt = c.take<uint8_t>((size_t)(N * K / 2));
+  w.amax = c.take<uint32_t>((size_t)N);
+  // sized for the densest residual the entry points accept (alpha > 0.5 -> fewer than M*K entries);
+  // the workspace query does not know alpha, so it provides for alpha >= 0.9
+  w.occ = carve_occ(c, M, 2 * tail_count(M * K, 0.9));
+  w.R = dt == FP4_BF16 ? c.take<float>((size_t)(M * N)) : nullptr;
+  return w;
+}
+
+struct DgradWs { uint8_t* qdY; float* gdY; uint8_t* qW; float* gWk; };
+DgradWs carve_dgrad(Carver& c, int64_t M, int64_t K, int64_t N) {
+  DgradWs w;
+  w.qdY = c.take<uint8_t>((size_t)(M * N / 2));
+  w.gdY = c.take<float>((size_t)M);
+  w.qW = c.take<uint8_t>((size_t)(K * N / 2));
+  w.gWk = c.take<float>((size_t)K);
+  return w;
+}
+
+struct WgradWs {
+  uint8_t* qAt; float* gAk; uint8_t* qdYt; float* gdYn; uint32_t* amax;
+  int64_t* t_ptr; int32_t* t_idx; float* t_val; int32_t* t_scratch;
+};
+WgradWs carve_wgrad(Carver& c, int64_t M, int64_t K, int64_t N) {
+  WgradWs w;
+  w.qAt = c.take<uint8_t>((size_t)(K * M / 2));
+  w.gAk = c.take<float>((size_t)K);
+  w.qdYt = c.take<uint8_t>((size_t)(N * M / 2));
+  w.gdYn = c.take<float>((size_t)N);
+  w.amax = c.take<uint32_t>((size_t)std::max(K, N));
+  const int64_t cap = 2 * tail_count(M * K, 0.9);
+  w.t_ptr = c.take<int64_t>((size_t)(K + 1));
+  w.t_idx = c.take<int32_t>((size_t)cap);
+  w.t_val = c.take<float>((size_t)cap);
+  w.t_scratch = c.take<int32_t>((size_t)(2 * K));
+  return w;
+}
+
+}  // namespace
+
+extern "C" const char* fp4_status_string(int status) {
+  switch (status) {
+    case FP4_OK: return "ok";
+    case FP4_ERR_NULL: return "null pointer";
+    case FP4_ERR_SHAPE: return "bad shape";
+    case FP4_ERR_DTYPE: return "bad dtype, axis or op";
+    case FP4_ERR_ARG: return "bad argument";
+    case FP4_ERR_WORKSPACE: return "workspace too small";
+    case FP4_ERR_CAPACITY: return "residual capacity too small";
+    case FP4_ERR_HIP: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int64_t fp4_occ_capacity(int64_t rows, int64_t cols, double alpha) {
+  if (rows < 0 || cols < 0 || !(alpha > 0.5) || !(alpha <= 1.0)) return -1;
+  return 2 * tail_count(rows * cols, alpha);
+}
+
+extern "C" size_t fp4_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, fp4_dtype dt) {
+  if (M < 0 || K < 0 || N < 0 || !dtype_ok(dt)) return 0;
+  Carver c(nullptr);
+  switch (op) {
+    case FP4_OP_QUANTIZE: c.take<uint32_t>((size_t)K); break;  // column absmax
+    case FP4_OP_OCC: carve_occ(c, M, 2 * tail_count(M * K, 0.9)); break;
+    case FP4_OP_FWD: carve_fwd(c, M, K, N, dt); break;
+    case FP4_OP_DGRAD: carve_dgrad(c, M, K, N); break;
+    case FP4_OP_WGRAD: carve_wgrad(c, M, K, N); break;
+    default: return 0;
+  }
+  return c.off + 256;
+}
+
+extern "C" int occ_clamp_residual(const void* x, fp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                                  double alpha, float* thresholds, uint8_t* codes, float* gamma,
+                                  void* x_clamped, int64_t* row_ptr, int32_t* col_idx, float* val,
+                                  int64_t capacity, int64_t* nnz, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+  if (!dtype_ok(dt)) return FP4_ERR_DTYPE;
+  if (rows <= 0 || cols <= 0 || ld < cols || (cols & 1)) return FP4_ERR_SHAPE;
+  if (!(alpha > 0.5) || !(alpha <= 1.0)) return FP4_ERR_ARG;
+  if (!x || !thresholds || !row_ptr || !nnz) return FP4_ERR_NULL;
+  if ((codes == nullptr) != (gamma == nullptr)) return FP4_ERR_NULL;
+  const int64_t k = tail_count(rows * cols, alpha);
+  if (capacity < 2 * k) return FP4_ERR_CAPACITY;
+  if (capacity > 0 && (!col_idx || !val)) return FP4_ERR_NULL;
+  if (!aligned16(x) || (ld % 8) != 0 || (codes && !aligned16(codes)) || (x_clamped && !aligned16(x_clamped)))
+    return FP4_ERR_ARG;
+  if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_OCC, rows, cols, 0, dt)) return FP4_ERR_WORKSPACE;
+  if (2 * k > 2 * tail_count(rows * cols, 0.9)) return FP4_ERR_WORKSPACE;  // alpha below 0.9 not provisioned
+  hipStream_t s = (hipStream_t)stream;
+  Carver c(reinterpret_cast<void*>(align_up((size_t)(uintptr_t)workspace, 256)));
+  OccTemps t = carve_occ(c, rows, 2 * tail_count(rows * cols, 0.9));
+  int rc = fp4_launch_thresholds(x, dt == FP4_BF16, rows, cols, ld, k, thresholds, t.select, t.total, s);
+  if (rc) return rc;
+  rc = fp4_launch_occ_rows(x, dt == FP4_BF16, rows, cols, ld, thresholds, codes, gamma, x_clamped, t.tmp_col,
+                           t.tmp_val, t.row_start, t.row_cnt, t.total, capacity, s);
+  if (rc) return rc;
+  return fp4_launch_csr_finalize(t.tmp_col, t.tmp_val, t.row_start, t.row_cnt, rows, capacity, row_ptr,
+                                 col_idx, val, nnz, s);
+}
+
+extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
+                              double alpha, void* Y, const fp4_fwd_ctx* saved, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  if (!dtype_ok(dt)) return FP4_ERR_DTYPE;
+  if (M <= 0 || K <= 0 || N <= 0 || (K % 32) != 0 || (N % 8) != 0) return FP4_ERR_SHAPE;
+  if (!(alpha > 0.5) || !(alpha <= 1.0)) return FP4_ERR_ARG;
+  if (!A || !W || !Y || !saved || !saved->gamma_W) return FP4_ERR_NULL;
+  if (!aligned16(A) || !aligned16(W) || !aligned16(Y)) return FP4_ERR_ARG;
+  const bool occ = alpha < 1.0;
+  const int64_t k = tail_count(M * K, alpha);
+  if (occ) {
+    if (!saved->thresholds || !saved->row_ptr || !saved->nnz) return FP4_ERR_NULL;
+    if (saved->capacity < 2 * k) return FP4_ERR_CAPACITY;
+    if (saved->capacity > 0 && (!saved->col_idx || !saved->val)) return FP4_ERR_NULL;
+    if (2 * k > 2 * tail_count(M * K, 0.9)) return FP4_ERR_WORKSPACE;
+  }
+  if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_FWD, M, K, N, dt)) return FP4_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const int bf16 = dt == FP4_BF16;
+  Carver c(reinterpret_cast<void*>(align_up((size_t)(uintptr_t)workspace, 256)));
+  FwdWs w = carve_fwd(c, M, K, N, dt);
+
+  // W per output channel -> codes [N x K/2], scales kept for the DGE term of the backward pass
+  int rc = fp4_launch_quantize_cols(W, bf16, K, N, N, nullptr, w.qWt, saved->gamma_W, w.amax, s);
+  if (rc) return rc;
+  const float* addend = nullptr;
+  if (occ) {
+    rc = fp4_launch_thresholds(A, bf16, M, K, K, k, saved->thresholds, w.occ.select, w.occ.total, s);
+    if (rc) return rc;
+    rc = fp4_launch_occ_rows(A, bf16, M, K, K, saved->thresholds, w.qA, w.gA, nullptr, w.occ.tmp_col,
+                             w.occ.tmp_val, w.occ.row_start, w.occ.row_cnt, w.occ.total, saved->capacity, s);
+    if (rc) return rc;
+    rc = fp4_launch_csr_finalize(w.occ.tmp_col, w.occ.tmp_val, w.occ.row_start, w.occ.row_cnt, M,
+                                 saved->capacity, saved->row_ptr, saved->col_idx, saved->val, saved->nnz, s);
+    if (rc) return rc;
+    // Delta_A W with the unquantized W, fp32; lands where the GEMM epilogue picks it up
+    float* R = bf16 ? w.R : reinterpret_cast<float*>(Y);
+    rc = fp4_launch_spmm(saved->row_ptr, saved->col_idx, saved->val, saved->capacity, M, W, bf16, N, R, s);
+    if (rc) return rc;
+    addend = R;
+  } else {
+    rc = fp4_launch_quantize_rows(A, bf16, M, K, K, w.qA, w.gA, s);
+    if (rc) return rc;
+    if (saved->thresholds || saved->row_ptr || saved->nnz) {
+      hipLaunchKernelGGL(init_no_occ_kernel, dim3((unsigned)((M + 1 + 255) / 256)), dim3(256), 0, s,
+                         saved->thresholds, saved->row_ptr, M, saved->nnz);
+      FP4_CHECK_LAUNCH();
+    }
+  }
+  return fp4_launch_gemm(w.qA, w.gA, w.qWt, saved->gamma_W, M, N, K, addend, Y, bf16, N, nullptr, 0, 0,
+                         nullptr, 0.0f, 0.0f, s);
+}
+
+extern "C" int fp4_linear_bwd_dgrad(const void* dY, const void* W, fp4_dtype dt, int64_t M, int64_t K,
+                                    int64_t N, void* dA, void* workspace, size_t workspace_bytes,
+                                    void* stream) {
+  if (!dtype_ok(dt)) return FP4_ERR_DTYPE;
+  if (M <= 0 || K <= 0 || N <= 0 || (N % 32) != 0 || (K % 8) != 0) return FP4_ERR_SHAPE;
+  if (!dY || !W || !dA) return FP4_ERR_NULL;
+  if (!aligned16(dY) || !aligned16(W) || !aligned16(dA)) return FP4_ERR_ARG;
+  if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_DGRAD, M, K, N, dt)) return FP4_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const int bf16 = dt == FP4_BF16;
+  Carver c(reinterpret_cast<void*>(align_up((size_t)(uintptr_t)workspace, 256)));
+  DgradWs w = carve_dgrad(c, M, K, N);
+  int rc = fp4_launch_quantize_rows(dY, bf16, M, N, N, w.qdY, w.gdY, s);   // per token
+  if (rc) return rc;
+  rc = fp4_launch_quantize_rows(W, bf16, K, N, N, w.qW, w.gWk, s);         // per input channel
+  if (rc) return rc;
+  return fp4_launch_gemm(w.qdY, w.gdY, w.qW, w.gWk, M, K, N, nullptr, dA, bf16, K, nullptr, 0, 0, nullptr,
+                         0.0f, 0.0f, s);
+}
+
+extern "C" int fp4_linear_bwd_wgrad(const void* A, const void* dY, const void* W, fp4_dtype dt, int64_t M,
+                                    int64_t K, int64_t N, const fp4_fwd_ctx* saved, float dge_k,
+                                    float dge_cap, float* dW, void* workspace, size_t workspace_bytes,
+                                    void* stream) {
+  if (!dtype_ok(dt)) return FP4_ERR_DTYPE;
+  if (M <= 0 || K <= 0 || N <= 0 || (M % 32) != 0 || (K % 8) != 0 || (N % 8) != 0) return FP4_ERR_SHAPE;
+  if (!A || !dY || !W || !dW || !saved || !saved->gamma_W) return FP4_ERR_NULL;
+  if (dge_k > 0.0f && !(dge_cap > 0.0f)) return FP4_ERR_ARG;
+  if (!aligned16(A) || !aligned16(dY) || !aligned16(W) || !aligned16(dW)) return FP4_ERR_ARG;
+  // The residual is in play when the forward pass saved one (capacity > 0 with its arrays).
+  const bool occ = saved->capacity > 0 && saved->row_ptr && saved->col_idx && saved->val && saved->nnz &&
+                   saved->thresholds;
+  if (occ && saved->capacity > 2 * tail_count(M * K, 0.9)) return FP4_ERR_WORKSPACE;
+  if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_WGRAD, M, K, N, dt)) return FP4_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const int bf16 = dt == FP4_BF16;
+  Carver c(reinterpret_cast<void*>(align_up((size_t)(uintptr_t)workspace, 256)));
+  WgradWs w = carve_wgrad(c, M, K, N);
+  // A_c per input channel (codes [K x M/2]); dY per output channel (codes [N x M/2])
+  int rc = fp4_launch_quantize_cols(A, bf16, M, K, K, occ ? saved->thresholds : nullptr, w.qAt, w.gAk, w.amax, s);
+  if (rc) return rc;
+  rc = fp4_launch_quantize_cols(dY, bf16, M, N, N, nullptr, w.qdYt, w.gdYn, w.amax, s);
+  if (rc) return rc;
+  const float* addend = nullptr;
+  if (occ) {
+    rc = fp4_launch_csr_transpose(saved->row_ptr, saved->col_idx, saved->val, saved->nnz, M, K,
+                                  saved->capacity, w.t_ptr, w.t_idx, w.t_val, w.t_scratch, s);
+    if (rc) return rc;
+    rc = fp4_launch_spmm(w.t_ptr, w.t_idx, w.t_val, saved->capacity, K, dY, bf16, N, dW, s);
+    if (rc) return rc;
+    addend = dW;
+  }
+  return fp4_launch_gemm(w.qAt, w.gAk, w.qdYt, w.gdYn, K, N, M, addend, dW, 0, N, W, bf16, N, saved->gamma_W,
+                         dge_k, dge_cap, s);
+}

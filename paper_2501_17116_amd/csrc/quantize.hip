@@ -1,0 +1,547 @@
+// Vector-wise absmax quantization to packed E2M1 (Sec. 2 Eq. 1; Sec. 4.1), row-wise and
+// column-wise (transposing), with the OCC clamp (Sec. 3.2) optionally fused in front of it,
+// and the stand-alone DGE pass (Sec. 3.1 Eq. 8).
+//
+// Work unit: 8 consecutive elements of a row = one 16-byte load of bf16 (two of fp32) and one
+// 4-byte store of codes, so a wave reads 1 KiB (bf16) contiguous and writes 256 B contiguous.
+#include "fp4_common.h"
+
+namespace {
+
+struct BF16 {};
+struct F32 {};
+
+template <class DT>
+FP4_D void load8(const void* base, int64_t off, int valid, float (&v)[8]) {
+  if (valid >= 8) {
+    if constexpr (__is_same(DT, BF16)) {
+      u32x4 r = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(base) + off);
+      v[0] = u2f(r.x << 16); v[1] = u2f(r.x & 0xffff0000u);
+      v[2] = u2f(r.y << 16); v[3] = u2f(r.y & 0xffff0000u);
+      v[4] = u2f(r.z << 16); v[5] = u2f(r.z & 0xffff0000u);
+      v[6] = u2f(r.w << 16); v[7] = u2f(r.w & 0xffff0000u);
+    } else {
+      const f32x4* p = reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(base) + off);
+      f32x4 a = p[0], b = p[1];
+      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+      v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float f = 0.0f;
+      if (e < valid) {
+        if constexpr (__is_same(DT, BF16))
+          f = bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(base)[off + e]);
+        else
+          f = reinterpret_cast<const float*>(base)[off + e];
+      }
+      v[e] = f;
+    }
+  }
+}
+
+template <class DT>
+FP4_D void store8(void* base, int64_t off, int valid, const float (&v)[8]) {
+  if (valid >= 8) {
+    if constexpr (__is_same(DT, BF16)) {
+      u32x4 r;
+      r.x = (f2u(v[0]) >> 16) | (f2u(v[1]) & 0xffff0000u);
+      r.y = (f2u(v[2]) >> 16) | (f2u(v[3]) & 0xffff0000u);
+      r.z = (f2u(v[4]) >> 16) | (f2u(v[5]) & 0xffff0000u);
+      r.w = (f2u(v[6]) >> 16) | (f2u(v[7]) & 0xffff0000u);
+      *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(base) + off) = r;
+    } else {
+      f32x4* p = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(base) + off);
+      f32x4 a = {v[0], v[1], v[2], v[3]}, b = {v[4], v[5], v[6], v[7]};
+      p[0] = a; p[1] = b;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (e < valid) {
+        if constexpr (__is_same(DT, BF16))
+          reinterpret_cast<uint16_t*>(base)[off + e] = (uint16_t)(f2u(v[e]) >> 16);
+        else
+          reinterpret_cast<float*>(base)[off + e] = v[e];
+      }
+  }
+}
+
+FP4_D float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+FP4_D uint32_t pack8(const float (&v)[8], float gamma) {
+  uint32_t w = 0;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) w |= q_e2m1_code(__fmul_rn(v[e], gamma)) << (4 * e);
+  return w;
+}
+
+FP4_D void store_codes(uint8_t* dst, uint32_t w, int valid, bool word_ok) {
+  if (valid >= 8 && word_ok) {
+    *reinterpret_cast<uint32_t*>(dst) = w;
+  } else {
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+      if (2 * b < valid) dst[b] = (uint8_t)(w >> (8 * b));
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Row-wise: one scale per row.  TPR threads share a row (64: one wave, 256: the workgroup).
+// With NV > 0 a thread keeps its NV units in registers between the absmax pass and the
+// quantize pass (row read once); NV == 0 streams the row twice (second read served by L2).
+// With OCC the values are clamped to [lo, hi] first and the clamped-away part is appended,
+// in a deterministic but not column-sorted order, to a per-row segment of a temporary
+// entry list whose start and length are recorded per row.
+// ------------------------------------------------------------------------------------------
+struct RowArgs {
+  const void* x;
+  uint8_t* codes;        // may be null (OCC only)
+  float* gamma;          // may be null (OCC only)
+  void* x_clamped;       // may be null
+  const float* thr;      // {lo, hi} (OCC)
+  int32_t* tmp_col;      // OCC: temporary entries
+  float* tmp_val;
+  int64_t* row_start;    // OCC: [rows]
+  int32_t* row_cnt;      // OCC: [rows]
+  unsigned long long* total;  // OCC: running entry count
+  int64_t rows, cols, ld, capacity;
+};
+
+template <class DT, bool OCC, int TPR, int NV>
+__global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
+  constexpr int RPB = 256 / TPR;
+  constexpr bool CACHED = NV > 0;
+  __shared__ float s_max[4];
+  __shared__ int s_cnt[4];
+  __shared__ long long s_base;
+
+  const int tid = threadIdx.x;
+  const int t = tid % TPR;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int64_t row = (int64_t)blockIdx.x * RPB + tid / TPR;
+  const bool row_ok = row < a.rows;
+  const int64_t nunits = (a.cols + 7) / 8;
+  const int nloop = CACHED ? NV : (int)((nunits + TPR - 1) / TPR);
+  const int64_t xoff = row * a.ld;
+
+  float lo = 0.0f, hi = 0.0f;
+  if (OCC) { lo = a.thr[0]; hi = a.thr[1]; }
+
+  float cache[CACHED ? NV : 1][8];
+  float amax = 0.0f;
+  int cnt = 0;
+
+  auto visit = [&](int u, float (&v)[8], int& valid) {
+    const int64_t unit = (int64_t)u * TPR + t;
+    valid = (row_ok && unit < nunits) ? (int)min((int64_t)8, a.cols - unit * 8) : 0;
+    if (valid > 0) load8<DT>(a.x, xoff + unit * 8, valid, v);
+    else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = 0.0f;
+    }
+  };
+
+  // ---- pass 1: absmax of the (clamped) row, outlier count
+  if constexpr (CACHED) {
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+      int valid;
+      visit(u, cache[u], valid);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float x = cache[u][e];
+        if (OCC) {
+          bool out = (x < lo) | (x > hi);
+          cnt += (out && e < valid) ? 1 : 0;
+          x = x < lo ? lo : (x > hi ? hi : x);
+          if (e >= valid) x = 0.0f;
+        }
+        amax = fmaxf(amax, fabsf(x));
+      }
+    }
+  } else {
+    for (int u = 0; u < nloop; ++u) {
+      float v[8];
+      int valid;
+      visit(u, v, valid);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float x = v[e];
+        if (OCC) {
+          bool out = (x < lo) | (x > hi);
+          cnt += (out && e < valid) ? 1 : 0;
+          x = x < lo ? lo : (x > hi ? hi : x);
+          if (e >= valid) x = 0.0f;
+        }
+        amax = fmaxf(amax, fabsf(x));
+      }
+    }
+  }
+
+  amax = wave_max(amax);
+  if (TPR == 256) {
+    if (lane == 0) s_max[wave] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+  }
+  const float gamma = absmax_to_gamma(amax);
+  if (row_ok && t == 0 && a.gamma) a.gamma[row] = gamma;
+
+  // ---- OCC: reserve a segment of the entry list for this row
+  int64_t wr = 0;       // this thread's first entry slot
+  bool emit = false;
+  if (OCC) {
+    int incl = cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      int n = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += n;
+    }
+    int wave_total = __shfl(incl, 63, 64);
+    int excl = incl - cnt;
+    int row_total = wave_total;
+    if (TPR == 256) {
+      if (lane == 0) s_cnt[wave] = wave_total;
+      __syncthreads();
+      row_total = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+      for (int w = 0; w < wave; ++w) excl += s_cnt[w];
+    }
+    long long base = 0;
+    if (TPR == 256) {
+      if (tid == 0) {
+        s_base = row_total ? (long long)atomicAdd(a.total, (unsigned long long)row_total) : 0;
+      }
+      __syncthreads();
+      base = s_base;
+    } else {
+      if (lane == 0 && row_ok)
+        base = row_total ? (long long)atomicAdd(a.total, (unsigned long long)row_total) : 0;
+      base = __shfl(base, 0, 64);
+    }
+    if (row_ok && t == 0) {
+      a.row_start[row] = base;
+      a.row_cnt[row] = row_total;
+    }
+    emit = row_ok && (base + row_total <= a.capacity);
+    wr = base + excl;
+  }
+
+  // ---- pass 2: clamp again, emit residual entries, quantize, pack, store
+  const bool word_ok = (a.cols % 8) == 0;
+  auto finish = [&](int u, float (&v)[8], int valid) {
+    if (valid <= 0) return;
+    const int64_t unit = (int64_t)u * TPR + t;
+    if (OCC) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float x = v[e];
+        bool below = x < lo, above = x > hi;
+        if ((below | above) && e < valid) {
+          if (emit) {
+            a.tmp_col[wr] = (int32_t)(unit * 8 + e);
+            a.tmp_val[wr] = __fsub_rn(x, below ? lo : hi);
+          }
+          ++wr;
+        }
+        v[e] = below ? lo : (above ? hi : x);
+      }
+      if (a.x_clamped) store8<DT>(a.x_clamped, xoff + unit * 8, valid, v);
+    }
+    if (a.codes) {
+      uint32_t w = pack8(v, gamma);
+      store_codes(a.codes + row * (a.cols / 2) + unit * 4, w, valid, word_ok);
+    }
+  };
+  if constexpr (CACHED) {
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+      const int64_t unit = (int64_t)u * TPR + t;
+      int valid = (row_ok && unit < nunits) ? (int)min((int64_t)8, a.cols - unit * 8) : 0;
+      finish(u, cache[u], valid);
+    }
+  } else {
+    for (int u = 0; u < nloop; ++u) {
+      float v[8];
+      int valid;
+      visit(u, v, valid);
+      finish(u, v, valid);
+    }
+  }
+}
+
+template <class DT, bool OCC>
+int launch_rows(const RowArgs& a, hipStream_t s) {
+  const int64_t nunits = (a.cols + 7) / 8;
+  // one wave per row while the row fits 64 lanes x 8 units, else the whole workgroup
+  if (nunits <= 64 * 2) {
+    hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 64, 2>), dim3((unsigned)((a.rows + 3) / 4)), dim3(256), 0, s, a);
+  } else if (nunits <= 64 * 8) {
+    hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 64, 8>), dim3((unsigned)((a.rows + 3) / 4)), dim3(256), 0, s, a);
+  } else if (nunits <= 256 * 4) {
+    hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 256, 4>), dim3((unsigned)a.rows), dim3(256), 0, s, a);
+  } else if (nunits <= 256 * 8) {
+    hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 256, 8>), dim3((unsigned)a.rows), dim3(256), 0, s, a);
+  } else {
+    hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 256, 0>), dim3((unsigned)a.rows), dim3(256), 0, s, a);
+  }
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Column-wise: one scale per column, codes transposed [cols x rows/2].
+// Pass A: column absmax of the (clamped) tensor, atomically maxed as uint bits (non-negative
+// floats order like unsigned integers).  Pass B: 256-row x 64-column tiles; a thread takes
+// 8 consecutive rows of 8 consecutive columns, packs each column's 8 codes into one word,
+// and the tile is transposed through LDS so every column leaves as one 128-byte run.
+// ------------------------------------------------------------------------------------------
+struct ColArgs {
+  const void* x;
+  uint8_t* codes_t;
+  float* gamma;          // out [cols]
+  uint32_t* amax_bits;   // scratch [cols]
+  const float* thr;      // clamp thresholds or null
+  int64_t rows, cols, ld;
+};
+
+__global__ void fill_u32_kernel(uint32_t* p, int64_t n, uint32_t v) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+constexpr int CA_ROWS = 128;  // rows per workgroup in the absmax pass
+
+template <class DT, bool CLAMP>
+__global__ __launch_bounds__(256) void col_absmax_kernel(ColArgs a) {
+  __shared__ float s_m[4][64][8];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t unit = (int64_t)blockIdx.x * 64 + lane;   // 8 columns
+  const int64_t nunits = (a.cols + 7) / 8;
+  const int64_t r0 = (int64_t)blockIdx.y * CA_ROWS;
+  const int64_t r1 = min(r0 + CA_ROWS, a.rows);
+  float lo = 0, hi = 0;
+  if (CLAMP) { lo = a.thr[0]; hi = a.thr[1]; }
+  float m[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) m[e] = 0.0f;
+  const int valid = unit < nunits ? (int)min((int64_t)8, a.cols - unit * 8) : 0;
+  if (valid > 0) {
+    for (int64_t r = r0 + wave; r < r1; r += 4) {
+      float v[8];
+      load8<DT>(a.x, r * a.ld + unit * 8, valid, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float x = v[e];
+        if (CLAMP) x = x < lo ? lo : (x > hi ? hi : x);
+        m[e] = fmaxf(m[e], fabsf(x));
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) s_m[wave][lane][e] = m[e];
+  __syncthreads();
+  if (wave == 0 && valid > 0) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float mm = fmaxf(fmaxf(s_m[0][lane][e], s_m[1][lane][e]), fmaxf(s_m[2][lane][e], s_m[3][lane][e]));
+      if (e < valid && mm > 0.0f) atomicMax(&a.amax_bits[unit * 8 + e], f2u(mm));
+    }
+  }
+}
+
+__global__ void amax_to_gamma_kernel(const uint32_t* amax_bits, float* gamma, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) gamma[i] = absmax_to_gamma(u2f(amax_bits[i]));
+}
+
+constexpr int CT_ROWS = 256;
+constexpr int CT_COLS = 64;
+
+template <class DT, bool CLAMP>
+__global__ __launch_bounds__(256) void quantize_cols_kernel(ColArgs a) {
+  // s_w[col][rowgroup]: the 8 codes of rows 8*rowgroup..+7 of one column; +1 word of padding
+  __shared__ uint32_t s_w[CT_COLS][CT_ROWS / 8 + 1];
+  const int tid = threadIdx.x;
+  const int chunk = tid & 7;      // 8 columns
+  const int rg = tid >> 3;        // row group 0..31 (8 rows each)
+  const int64_t c0 = (int64_t)blockIdx.x * CT_COLS;
+  const int64_t r0 = (int64_t)blockIdx.y * CT_ROWS;
+  const int64_t col = c0 + chunk * 8;
+  const int valid = col < a.cols ? (int)min((int64_t)8, a.cols - col) : 0;
+  float lo = 0, hi = 0;
+  if (CLAMP) { lo = a.thr[0]; hi = a.thr[1]; }
+  float g[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) g[e] = (e < valid) ? a.gamma[col + e] : 1.0f;
+  uint32_t w[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) w[e] = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int64_t r = r0 + rg * 8 + i;
+    if (r < a.rows && valid > 0) {
+      float v[8];
+      load8<DT>(a.x, r * a.ld + col, valid, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float x = v[e];
+        if (CLAMP) x = x < lo ? lo : (x > hi ? hi : x);
+        w[e] |= q_e2m1_code(__fmul_rn(x, g[e])) << (4 * i);
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) s_w[chunk * 8 + e][rg] = w[e];
+  __syncthreads();
+  // write-out: 4 threads per column, 8 words (32 bytes, 64 rows) each
+  const int oc = tid >> 2;
+  const int part = tid & 3;
+  const int64_t ocol = c0 + oc;
+  if (ocol >= a.cols) return;
+  const int64_t row_bytes = a.rows / 2;
+  const int64_t b0 = r0 / 2 + part * 32;      // byte offset inside the column's row of codes
+  if (b0 >= row_bytes) return;
+  uint8_t* dst = a.codes_t + ocol * row_bytes + b0;
+  const int nbytes = (int)min((int64_t)32, row_bytes - b0);
+  if (nbytes == 32 && (row_bytes % 16) == 0) {
+    u32x4 o0 = {s_w[oc][part * 8 + 0], s_w[oc][part * 8 + 1], s_w[oc][part * 8 + 2], s_w[oc][part * 8 + 3]};
+    u32x4 o1 = {s_w[oc][part * 8 + 4], s_w[oc][part * 8 + 5], s_w[oc][part * 8 + 6], s_w[oc][part * 8 + 7]};
+    reinterpret_cast<u32x4*>(dst)[0] = o0;
+    reinterpret_cast<u32x4*>(dst)[1] = o1;
+  } else {
+    for (int b = 0; b < nbytes; ++b) dst[b] = (uint8_t)(s_w[oc][part * 8 + b / 4] >> (8 * (b & 3)));
+  }
+}
+
+template <class DT, bool CLAMP>
+int launch_cols(const ColArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((a.cols + 255) / 256)), dim3(256), 0, s, a.amax_bits, a.cols, 0u);
+  const int64_t nunits = (a.cols + 7) / 8;
+  hipLaunchKernelGGL((col_absmax_kernel<DT, CLAMP>),
+                     dim3((unsigned)((nunits + 63) / 64), (unsigned)((a.rows + CA_ROWS - 1) / CA_ROWS)),
+                     dim3(256), 0, s, a);
+  hipLaunchKernelGGL(amax_to_gamma_kernel, dim3((unsigned)((a.cols + 255) / 256)), dim3(256), 0, s,
+                     a.amax_bits, a.gamma, a.cols);
+  hipLaunchKernelGGL((quantize_cols_kernel<DT, CLAMP>),
+                     dim3((unsigned)((a.cols + CT_COLS - 1) / CT_COLS), (unsigned)((a.rows + CT_ROWS - 1) / CT_ROWS)),
+                     dim3(256), 0, s, a);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Stand-alone DGE pass: dW = G * min(cap, f'(W gamma_W))   (Sec. 3.1 Eq. 8; App. C.2 Eq. 22)
+// ------------------------------------------------------------------------------------------
+template <class DT>
+__global__ void dge_apply_kernel(const float* G, const void* W, const float* gamma_w, int64_t K,
+                                 int64_t N, float inv_k, float cap, int ste, float* dW) {
+  const int64_t nunits = N / 8;  // N % 8 == 0 checked by the caller
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= K * nunits) return;
+  const int64_t r = i / nunits, u = i % nunits;
+  float w[8], gq[8];
+  load8<DT>(W, r * N + u * 8, 8, w);
+  load8<F32>(G, r * N + u * 8, 8, gq);
+  const float pw = inv_k - 1.0f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    float a = fabsf(__fmul_rn(w[e], gamma_w[u * 8 + e]));
+    float l, s;
+    if (a < 2.0f) { l = 0.5f * floorf(a + a); s = 4.0f; }
+    else if (a < 4.0f) { l = floorf(a); s = 2.0f; }
+    else { l = 4.0f; s = 1.0f; }
+    float t = fabsf(s * (a - l) - 1.0f);
+    float f = fminf(inv_k * __builtin_amdgcn_exp2f(pw * __builtin_amdgcn_logf(t)), cap);
+    gq[e] *= ste ? 1.0f : f;
+  }
+  store8<F32>(dW, r * N + u * 8, 8, gq);
+}
+
+}  // namespace
+
+// ---- internal launchers used by the layer entry points --------------------------------------
+int fp4_launch_quantize_rows(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
+                             uint8_t* codes, float* gamma, hipStream_t s) {
+  if (rows == 0 || cols == 0) return FP4_OK;
+  RowArgs a = {};
+  a.x = x; a.codes = codes; a.gamma = gamma; a.rows = rows; a.cols = cols; a.ld = ld;
+  return bf16 ? launch_rows<BF16, false>(a, s) : launch_rows<F32, false>(a, s);
+}
+
+int fp4_launch_occ_rows(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
+                        const float* thr, uint8_t* codes, float* gamma, void* x_clamped,
+                        int32_t* tmp_col, float* tmp_val, int64_t* row_start, int32_t* row_cnt,
+                        unsigned long long* total, int64_t capacity, hipStream_t s) {
+  if (rows == 0 || cols == 0) return FP4_OK;
+  RowArgs a = {};
+  a.x = x; a.codes = codes; a.gamma = gamma; a.x_clamped = x_clamped; a.thr = thr;
+  a.tmp_col = tmp_col; a.tmp_val = tmp_val; a.row_start = row_start; a.row_cnt = row_cnt;
+  a.total = total; a.rows = rows; a.cols = cols; a.ld = ld; a.capacity = capacity;
+  return bf16 ? launch_rows<BF16, true>(a, s) : launch_rows<F32, true>(a, s);
+}
+
+int fp4_launch_quantize_cols(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
+                             const float* clamp_thr, uint8_t* codes_t, float* gamma,
+                             uint32_t* amax_scratch, hipStream_t s) {
+  if (rows == 0 || cols == 0) return FP4_OK;
+  ColArgs a = {};
+  a.x = x; a.codes_t = codes_t; a.gamma = gamma; a.amax_bits = amax_scratch; a.thr = clamp_thr;
+  a.rows = rows; a.cols = cols; a.ld = ld;
+  if (clamp_thr) return bf16 ? launch_cols<BF16, true>(a, s) : launch_cols<F32, true>(a, s);
+  return bf16 ? launch_cols<BF16, false>(a, s) : launch_cols<F32, false>(a, s);
+}
+
+extern "C" int fp4_quantize(const void* x, fp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                            fp4_axis axis, uint8_t* codes, float* gamma, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  if (dt != FP4_F32 && dt != FP4_BF16) return FP4_ERR_DTYPE;
+  if (axis != FP4_AXIS_ROW && axis != FP4_AXIS_COL) return FP4_ERR_DTYPE;
+  if (rows < 0 || cols < 0 || ld < cols) return FP4_ERR_SHAPE;
+  if (axis == FP4_AXIS_ROW ? (cols & 1) : (rows & 1)) return FP4_ERR_SHAPE;
+  if (rows == 0 || cols == 0) return FP4_OK;
+  if (!x || !codes || !gamma) return FP4_ERR_NULL;
+  if (!aligned16(x) || !aligned16(codes) || (ld % 8) != 0) return FP4_ERR_ARG;
+  if (axis == FP4_AXIS_ROW)
+    return fp4_launch_quantize_rows(x, dt == FP4_BF16, rows, cols, ld, codes, gamma, (hipStream_t)stream);
+  const size_t need = fp4_workspace_bytes(FP4_OP_QUANTIZE, rows, cols, 0, dt);
+  if (!workspace || workspace_bytes < need) return FP4_ERR_WORKSPACE;
+  return fp4_launch_quantize_cols(x, dt == FP4_BF16, rows, cols, ld, nullptr, codes, gamma,
+                                  reinterpret_cast<uint32_t*>(workspace), (hipStream_t)stream);
+}
+
+extern "C" int fp4_dge_apply(const float* G, const void* W, fp4_dtype dt, const float* gamma_W,
+                             int64_t K, int64_t N, float dge_k, float dge_cap, float* dW,
+                             void* stream) {
+  if (dt != FP4_F32 && dt != FP4_BF16) return FP4_ERR_DTYPE;
+  if (K < 0 || N < 0 || (N % 8) != 0) return FP4_ERR_SHAPE;
+  if (K == 0 || N == 0) return FP4_OK;
+  if (!G || !W || !gamma_W || !dW) return FP4_ERR_NULL;
+  if (dge_cap <= 0.0f) return FP4_ERR_ARG;
+  if (!aligned16(G) || !aligned16(W) || !aligned16(dW)) return FP4_ERR_ARG;
+  const int64_t n = K * (N / 8);
+  const float inv_k = dge_k > 0.0f ? 1.0f / dge_k : 1.0f;
+  const int ste = dge_k > 0.0f ? 0 : 1;  // k <= 0: straight-through estimator, f' = 1
+  const float cap = dge_cap;
+  if (dt == FP4_BF16)
+    hipLaunchKernelGGL((dge_apply_kernel<BF16>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)stream, G, W, gamma_W, K, N, inv_k, cap, ste, dW);
+  else
+    hipLaunchKernelGGL((dge_apply_kernel<F32>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)stream, G, W, gamma_W, K, N, inv_k, cap, ste, dW);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
+
+extern "C" int fp4_host_round_codes(const float* x_host, int64_t n, uint8_t* codes_host) {
+  if (n < 0) return FP4_ERR_SHAPE;
+  if (n && (!x_host || !codes_host)) return FP4_ERR_NULL;
+  for (int64_t i = 0; i < n; ++i) codes_host[i] = (uint8_t)q_e2m1_code(x_host[i]);
+  return FP4_OK;
+}

@@ -1,0 +1,104 @@
+"""No-GPU checks of the boundary: the library loads, exports every declared symbol, validates
+arguments before launching anything, and its rounding routine (run on the host) agrees with
+the oracle bit for bit."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import fp4_oracle as o
+from paper_2501_17116_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(b.LIB_PATH):
+        pytest.fail("libfp4mi.so is not built; run __graft_entry__.build() first")
+    return b.lib()
+
+
+def _declared_symbols():
+    src = open(os.path.join(ROOT, "include", "fp4_linear.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = re.findall(r"\b(?:int|size_t|int64_t|const char\*)\s+(\w+)\s*\(", src)
+    return sorted(set(names))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = _declared_symbols()
+    for must in ("fp4_quantize", "occ_clamp_residual", "fp4_linear_fwd", "fp4_linear_bwd_dgrad",
+                 "fp4_linear_bwd_wgrad"):
+        assert must in names
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings_and_queries(L):
+    assert b.status_string(0) == "ok"
+    assert "shape" in b.status_string(-2)
+    assert b.occ_capacity(256, 512, 0.99) == 2 * o.occ_tail_count(256 * 512, 0.99) == 2620
+    assert b.occ_capacity(16384, 4096, 0.999) == 2 * o.occ_tail_count(16384 * 4096, 0.999)
+    assert b.occ_capacity(4, 4, 1.0) == 0
+    assert b.occ_capacity(4, 4, 0.3) == -1
+    for op in range(5):
+        assert b.workspace_bytes(op, 256, 512, 512, b.FP4_F32) > 0
+    assert b.workspace_bytes(99, 256, 512, 512, b.FP4_F32) == 0
+    # forward workspace holds at least both packed operands and the fp32 residual product
+    M, K, N = 16384, 4096, 12288
+    assert b.workspace_bytes(b.FP4_OP_FWD, M, K, N, b.FP4_BF16) >= M * K // 2 + N * K // 2 + 4 * M * N
+
+
+def test_argument_validation_happens_on_the_host(L):
+    one = C.c_void_p(16)   # non-null, aligned, never dereferenced: every call below must fail first
+    assert L.fp4_quantize(None, 0, 4, 8, 8, 0, one, one, one, 1 << 20, None) == -1
+    assert L.fp4_quantize(one, 0, 4, 7, 8, 0, one, one, one, 1 << 20, None) == -2      # odd cols
+    assert L.fp4_quantize(one, 7, 4, 8, 8, 0, one, one, one, 1 << 20, None) == -3
+    assert L.fp4_quantize(one, 0, 4, 8, 4, 0, one, one, one, 1 << 20, None) == -2      # ld < cols
+    assert L.fp4_quantize(C.c_void_p(20), 0, 4, 8, 8, 0, one, one, one, 1 << 20, None) == -4
+    assert L.fp4_quantize(one, 0, 4, 8, 8, 1, one, one, None, 0, None) == -5            # col needs ws
+    assert L.fp4_quantize(one, 0, 0, 8, 8, 0, one, one, one, 0, None) == 0              # empty: no-op
+    assert L.fp4_gemm(one, one, one, one, 4, 4, 48, None, one, 0, 8, None) == -2        # K % 32
+    assert L.fp4_gemm(one, None, one, None, 4, 4, 64, None, one, 1, 8, None) == -3      # raw needs fp32
+    assert L.fp4_gemm(one, one, one, one, 0, 4, 64, None, one, 0, 8, None) == 0
+    ctx = b.fp4_fwd_ctx(16, 16, 16, 16, 16, 0, 16)
+    big = 1 << 40
+    assert L.fp4_linear_fwd(one, one, 0, 8, 48, 8, 0.99, one, C.byref(ctx), one, big, None) == -2
+    assert L.fp4_linear_fwd(one, one, 0, 8, 64, 8, 0.2, one, C.byref(ctx), one, big, None) == -4
+    assert L.fp4_linear_fwd(one, one, 0, 8, 64, 8, 0.99, one, C.byref(ctx), one, big, None) == -6  # capacity 0 < 2k
+    assert L.fp4_linear_fwd(one, one, 0, 8, 64, 8, 1.0, one, C.byref(ctx), one, 8, None) == -5
+    assert L.fp4_linear_bwd_dgrad(one, one, 0, 8, 8, 48, one, one, big, None) == -2
+    assert L.fp4_linear_bwd_wgrad(one, one, one, 0, 48, 8, 8, C.byref(ctx), 5.0, 3.0, one, one, big, None) == -2
+    assert L.fp4_linear_bwd_wgrad(one, one, one, 0, 64, 8, 8, C.byref(ctx), 5.0, -1.0, one, one, big, None) == -4
+    assert L.occ_clamp_residual(one, 0, 8, 8, 8, 0.9, one, None, None, None, one, one, one, 0, one, one, big,
+                                None) == -6
+    assert L.fp4_dge_apply(one, one, 0, one, 8, 12, 5.0, 3.0, one, None) == -2
+
+
+def test_library_rounding_equals_the_oracle_bit_for_bit(L):
+    rng = np.random.default_rng(0)
+    # every threshold and grid point with its fp32 neighbours, both signs, specials
+    pts = [0.25, 0.5, 0.75, 1, 1.25, 1.5, 1.75, 2, 2.5, 3, 3.5, 4, 5, 6, 7, 0.0]
+    edge = []
+    for p in pts:
+        for s in (1, -1):
+            v = np.float32(s * p)
+            edge += [v, np.nextafter(v, np.float32(np.inf)), np.nextafter(v, np.float32(-np.inf))]
+    edge += [np.float32(x) for x in (np.inf, -np.inf, np.nan, 1e-45, -1e-45, 1e38, -1e38, -0.0)]
+    edge = np.array(edge, np.float32)
+    assert np.array_equal(b.fp4_host_round_codes(edge), o.q_e2m1(edge))
+    # random bit patterns (all exponents) and a dense sweep of the interesting range
+    bits = rng.integers(0, 2 ** 32, 4_000_000, dtype=np.uint64).astype(np.uint32)
+    x = bits.view(np.float32)
+    assert np.array_equal(b.fp4_host_round_codes(x), o.q_e2m1(x))
+    x = rng.uniform(-7, 7, 4_000_000).astype(np.float32)
+    assert np.array_equal(b.fp4_host_round_codes(x), o.q_e2m1(x))
+    # the mantissa patterns around every tie, in every binade the grid spans
+    base = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0], np.float32).view(np.uint32)
+    near = (base[:, None].astype(np.int64) + np.arange(-2000, 2001)[None, :]).astype(np.uint32).ravel()
+    for sign in (0, 0x80000000):
+        x = (near | np.uint32(sign)).view(np.float32)
+        assert np.array_equal(b.fp4_host_round_codes(x), o.q_e2m1(x))

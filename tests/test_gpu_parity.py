@@ -1,0 +1,301 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle on the same seeded inputs.
+
+Bars: 4-bit codes, scales, thresholds, residual triplets and raw accumulators bit-exact;
+scaled outputs and gradients within  1e-3 * |ref| + 2e-6 * max|ref|  of the oracle's fp64
+value (fp32 outputs), plus half a bf16 ulp (2^-8 |ref|) when the output is bf16.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fp4_oracle as o
+from paper_2501_17116_amd import binding as b
+from paper_2501_17116_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-3
+FLOOR = 2e-6
+
+
+def dev(x: torch.Tensor, dtype: str) -> torch.Tensor:
+    t = x.to(torch.bfloat16) if dtype == "bf16" else x.to(torch.float32)
+    return t.contiguous().cuda()
+
+
+def host_codes(packed: torch.Tensor) -> np.ndarray:
+    return o.unpack_codes(packed.cpu().numpy())
+
+
+def assert_close(got: torch.Tensor, ref: np.ndarray, out_dtype: str, what: str):
+    g = got.float().cpu().numpy().astype(np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    tol = RTOL * np.abs(ref) + FLOOR * np.abs(ref).max()
+    if out_dtype == "bf16":
+        tol = tol + 2.0 ** -8 * np.abs(ref) + 2.0 ** -133
+    bad = np.abs(g - ref) > tol
+    assert not bad.any(), "%s: %d of %d outside tolerance, worst %g vs %g" % (
+        what, bad.sum(), bad.size, g[bad][0], ref[bad][0])
+    if out_dtype == "f32":
+        rel = np.abs(g - ref) / (np.abs(ref) + 1e-30)
+        assert np.median(rel) < 1e-5, what
+
+
+# ------------------------------------------------------------------------------------------
+# quantization
+# ------------------------------------------------------------------------------------------
+ROW_SHAPES = [(7, 64), (16, 10), (33, 520), (64, 4096), (5, 9000), (3, 20000), (1, 2), (130, 1024)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", ROW_SHAPES)
+def test_quantize_rows_bit_exact(shape, dtype):
+    R, Cc = shape
+    ldpad = (Cc + 7) // 8 * 8
+    g = torch.Generator().manual_seed(R * 1000 + Cc)
+    x = torch.randn(R, ldpad, generator=g) * torch.exp(torch.randn(R, 1, generator=g) * 2)
+    x[:, : min(4, Cc)] *= 30
+    if R > 2:
+        x[2] = 0.0                                    # all-zero row -> gamma 1, codes 0
+    x = synth._finish(x, dtype)
+    xd = dev(x, dtype)
+    if ldpad != Cc:
+        # exercise ld > cols through the raw ABI
+        import ctypes as C
+        codes = torch.empty((R, Cc // 2), dtype=torch.uint8, device="cuda")
+        gamma = torch.empty(R, dtype=torch.float32, device="cuda")
+        st = b.lib().fp4_quantize(C.c_void_p(xd.data_ptr()), b._dt(xd), R, Cc, ldpad, b.FP4_AXIS_ROW,
+                                  C.c_void_p(codes.data_ptr()), C.c_void_p(gamma.data_ptr()), None, 0,
+                                  b._stream())
+        assert st == 0
+    else:
+        codes, gamma = b.fp4_quantize(xd, b.FP4_AXIS_ROW)
+    torch.cuda.synchronize()
+    rc, rg = o.quantize_rows(x[:, :Cc].numpy())
+    assert np.array_equal(gamma.cpu().numpy().view(np.uint32), rg.view(np.uint32))
+    assert np.array_equal(host_codes(codes), rc)
+
+
+def test_quantize_ties_and_tiny_values_bit_exact():
+    # rows whose absmax is 6 (gamma = 1) so scaled values hit the midpoints exactly
+    ties = torch.tensor([6, .25, -.25, .75, -.75, 1.25, -1.25, 1.75, -1.75, 2.5, -2.5, 3.5, -3.5, 5, -5, 0.,
+                         -0., 6, -6, 5.9999995, 0.24999999, -0.25000003, 1e-30, -1e-30], dtype=torch.float32)
+    x = torch.zeros(4, 32)
+    x[0, :ties.numel()] = ties
+    x[1, :ties.numel()] = ties * 2 ** -100            # same pattern, gamma = 2^100
+    x[2, 0] = 1e-44                                   # subnormal absmax: 6/amax overflows -> gamma 1
+    x[3, :ties.numel()] = ties.flip(0)
+    codes, gamma = b.fp4_quantize(x.cuda(), b.FP4_AXIS_ROW)
+    rc, rg = o.quantize_rows(x.numpy())
+    assert np.array_equal(gamma.cpu().numpy().view(np.uint32), rg.view(np.uint32))
+    assert np.array_equal(host_codes(codes), rc)
+
+
+COL_SHAPES = [(256, 64), (300, 136), (1024, 512), (34, 8), (2, 2048), (514, 72)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", COL_SHAPES)
+def test_quantize_cols_bit_exact(shape, dtype):
+    R, Cc = shape
+    g = torch.Generator().manual_seed(7 * R + Cc)
+    x = torch.randn(R, Cc, generator=g) * 0.02 * torch.exp(torch.randn(1, Cc, generator=g))
+    x[:, 1] = 0.0
+    x = synth._finish(x, dtype)
+    codes, gamma = b.fp4_quantize(dev(x, dtype), b.FP4_AXIS_COL)
+    rc, rg = o.quantize_cols(x.numpy())
+    assert codes.shape == (Cc, R // 2)
+    assert np.array_equal(gamma.cpu().numpy().view(np.uint32), rg.view(np.uint32))
+    assert np.array_equal(host_codes(codes), rc)
+
+
+def test_unpack():
+    p = torch.randint(0, 256, (37, 24), dtype=torch.uint8)
+    assert np.array_equal(b.fp4_unpack(p.cuda()).cpu().numpy(), o.unpack_codes(p.numpy()))
+
+
+# ------------------------------------------------------------------------------------------
+# GEMM
+# ------------------------------------------------------------------------------------------
+GEMM_SHAPES = [(256, 256, 256), (64, 48, 32), (300, 200, 128), (513, 257, 1056), (1, 8, 64), (700, 1030, 512)]
+
+
+@pytest.mark.parametrize("shape", GEMM_SHAPES)
+def test_gemm_raw_accumulator_bit_exact(shape):
+    P, Q, K = shape
+    g = torch.Generator().manual_seed(P + Q + K)
+    ca = torch.randint(0, 16, (P, K), generator=g, dtype=torch.uint8)
+    cb = torch.randint(0, 16, (Q, K), generator=g, dtype=torch.uint8)
+    pa = torch.from_numpy(o.pack_codes(ca.numpy())).cuda()
+    pb = torch.from_numpy(o.pack_codes(cb.numpy())).cuda()
+    acc = b.fp4_gemm(pa, None, pb, None)
+    ref = o.gemm_acc(ca.numpy(), cb.numpy())
+    assert np.array_equal(acc.cpu().numpy().astype(np.float64), ref)
+
+
+def test_gemm_extreme_codes_long_k_exact():
+    # all +-6 over K = 16384: |acc| = 36 K, the largest accumulator any config produces
+    K = 16384
+    ca = torch.full((40, K), 7, dtype=torch.uint8)
+    cb = torch.full((24, K), 15, dtype=torch.uint8)
+    cb[::2] = 7
+    acc = b.fp4_gemm(torch.from_numpy(o.pack_codes(ca.numpy())).cuda(), None,
+                     torch.from_numpy(o.pack_codes(cb.numpy())).cuda(), None)
+    assert np.array_equal(acc.cpu().numpy().astype(np.float64), o.gemm_acc(ca.numpy(), cb.numpy()))
+
+
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
+def test_gemm_scaled_and_addend(out_dtype):
+    P, Q, K = 300, 264, 384
+    g = torch.Generator().manual_seed(5)
+    A = torch.randn(P, K, generator=g)
+    W = torch.randn(K, Q, generator=g) * 0.02
+    ca, ga = o.quantize_rows(A.numpy())
+    cw, gw = o.quantize_cols(W.numpy())
+    add = torch.randn(P, Q, generator=g)
+    tdt = torch.bfloat16 if out_dtype == "bf16" else torch.float32
+    y = b.fp4_gemm(torch.from_numpy(o.pack_codes(ca)).cuda(), torch.from_numpy(ga).cuda(),
+                   torch.from_numpy(o.pack_codes(cw)).cuda(), torch.from_numpy(gw).cuda(), out_dtype=tdt)
+    assert_close(y, o.dequant_gemm(ca, ga, cw, gw), out_dtype, "scaled gemm")
+    y2 = b.fp4_gemm(torch.from_numpy(o.pack_codes(ca)).cuda(), torch.from_numpy(ga).cuda(),
+                    torch.from_numpy(o.pack_codes(cw)).cuda(), torch.from_numpy(gw).cuda(), out_dtype=tdt,
+                    addend=add.cuda())
+    assert_close(y2, o.dequant_gemm(ca, ga, cw, gw) + add.numpy().astype(np.float64), out_dtype, "gemm+addend")
+
+
+# ------------------------------------------------------------------------------------------
+# OCC
+# ------------------------------------------------------------------------------------------
+def _check_occ(x: torch.Tensor, dtype: str, alpha: float):
+    out = b.occ_clamp_residual(dev(x, dtype), alpha, want_codes=True, want_clamped=True)
+    torch.cuda.synchronize()
+    xn = x.numpy()
+    lo, hi = o.occ_thresholds(xn, alpha)
+    thr = out["thresholds"].cpu().numpy()
+    assert thr[0] == lo and thr[1] == hi, (thr, lo, hi)
+    xc, csr = o.occ_clamp_residual(xn, lo, hi)
+    nnz = int(out["nnz"].item())
+    assert nnz == csr.val.size <= b.occ_capacity(x.shape[0], x.shape[1], alpha)
+    assert np.array_equal(out["row_ptr"].cpu().numpy(), csr.row_ptr)
+    assert np.array_equal(out["col_idx"].cpu().numpy()[:nnz], csr.col_idx)
+    assert np.array_equal(out["val"].cpu().numpy()[:nnz].view(np.uint32), csr.val.view(np.uint32))
+    assert np.array_equal(out["x_clamped"].float().cpu().numpy(), xc)
+    rc, rg = o.quantize_rows(xc)
+    assert np.array_equal(out["gamma"].cpu().numpy().view(np.uint32), rg.view(np.uint32))
+    assert np.array_equal(host_codes(out["codes"]), rc)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape,alpha", [((256, 512), 0.99), ((100, 72), 0.97), ((64, 4096), 0.999),
+                                          ((9, 2056), 0.99), ((300, 640), 1.0), ((2, 20000), 0.95)])
+def test_occ_clamp_residual_bit_exact(shape, alpha, dtype):
+    cfg = synth.CONFIGS["c1"]
+    x = synth.make_activation(cfg, shape[0], shape[1], salt=shape[0])
+    _check_occ(synth._finish(x, dtype), dtype, alpha)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_occ_with_ties_one_sided_and_constant(dtype):
+    g = torch.Generator().manual_seed(3)
+    x = torch.randint(0, 5, (64, 128), generator=g).float()          # heavy ties, all non-negative
+    _check_occ(synth._finish(x, dtype), dtype, 0.97)
+    _check_occ(torch.full((16, 64), 1.5), dtype, 0.99)                # constant tensor: nothing clamped
+    x = torch.randn(32, 64, generator=g).abs() + 1.0                  # one-sided
+    _check_occ(synth._finish(x, dtype), dtype, 0.9)
+    x = torch.randn(32, 64, generator=g)
+    x[0, 0] = -0.0
+    _check_occ(synth._finish(-x.abs(), dtype), dtype, 0.95)
+
+
+def test_residual_spmm():
+    g = torch.Generator().manual_seed(11)
+    x = torch.randn(70, 96, generator=g)
+    lo, hi = o.occ_thresholds(x.numpy(), 0.95)
+    _, csr = o.occ_clamp_residual(x.numpy(), lo, hi)
+    for dtype in ("f32", "bf16"):
+        D = synth._finish(torch.randn(96, 2056, generator=g), dtype)
+        R = b.fp4_residual_spmm(torch.from_numpy(csr.row_ptr).cuda(), torch.from_numpy(csr.col_idx).cuda(),
+                                torch.from_numpy(csr.val).cuda(), 96, dev(D, dtype))
+        assert_close(R, csr.to_dense() @ D.numpy().astype(np.float64), "f32", "spmm")
+
+
+# ------------------------------------------------------------------------------------------
+# DGE
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_dge_apply(dtype):
+    g = torch.Generator().manual_seed(13)
+    K, N = 200, 264
+    W = synth._finish(torch.randn(K, N, generator=g) * 0.02, dtype)
+    # plant scaled weights on grid points, midpoints and the cap boundary (gamma = 1 column)
+    W[:16, 0] = torch.tensor([6, .25, .5, .75, 1, 1.25, 2.5, 3, 3.5, 5, 0, 2.516, 2.484, -5, -0.25, 4.99])
+    G = torch.randn(K, N, generator=g)
+    _, gw = o.quantize_cols(W.numpy())
+    ref = G.numpy().astype(np.float64) * o.dge_fprime(o.scaled_weights(W.numpy(), gw), 5.0, 3.0)
+    got = b.fp4_dge_apply(G.cuda(), dev(W, dtype), torch.from_numpy(gw).cuda(), 5.0, 3.0)
+    g64 = got.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(g64 - ref) <= 1e-5 * np.abs(ref) + 1e-12)
+    ste = b.fp4_dge_apply(G.cuda(), dev(W, dtype), torch.from_numpy(gw).cuda(), 0.0, 3.0)
+    assert torch.equal(ste.cpu(), G)
+
+
+# ------------------------------------------------------------------------------------------
+# the layer: forward, dgrad, wgrad
+# ------------------------------------------------------------------------------------------
+LAYER_CASES = [
+    ("c1", 256, 512, 512, "f32", 0.99),
+    ("rag", 160, 288, 224, "f32", 0.97),
+    ("rag", 288, 544, 1056, "bf16", 0.99),
+    ("off", 96, 128, 96, "bf16", 1.0),
+    ("tiny", 32, 32, 32, "f32", 0.9),
+]
+
+
+def _layer_inputs(name, M, K, N, dtype):
+    if name == "c1":
+        cfg = synth.CONFIGS["c1"]
+        return synth.make_layer(cfg, cfg.layers[0])
+    return synth.small_case(M, K, N, dtype, seed=M + K + N)
+
+
+@pytest.mark.parametrize("name,M,K,N,dtype,alpha", LAYER_CASES)
+def test_layer_forward_backward(name, M, K, N, dtype, alpha):
+    A, W, dY = _layer_inputs(name, M, K, N, dtype)
+    Ad, Wd, dYd = dev(A, dtype), dev(W, dtype), dev(dY, dtype)
+    Y, ctx = b.fp4_linear_fwd(Ad, Wd, alpha)
+    torch.cuda.synchronize()
+    Yref, st = o.fp4_linear_fwd(A.numpy(), W.numpy(), alpha, "f32")
+    # saved state: scales, thresholds, residual -- bit exact
+    assert np.array_equal(ctx.gamma_W.cpu().numpy().view(np.uint32), st.gamma_w.view(np.uint32))
+    if alpha < 1.0:
+        thr = ctx.thresholds.cpu().numpy()
+        assert thr[0] == st.lo and thr[1] == st.hi
+        nnz = int(ctx.nnz.item())
+        assert nnz == st.csr.val.size
+        assert np.array_equal(ctx.row_ptr.cpu().numpy(), st.csr.row_ptr)
+        assert np.array_equal(ctx.col_idx.cpu().numpy()[:nnz], st.csr.col_idx)
+        assert np.array_equal(ctx.val.cpu().numpy()[:nnz].view(np.uint32), st.csr.val.view(np.uint32))
+    else:
+        assert int(ctx.nnz.item()) == 0
+    assert_close(Y, Yref, dtype, "Y")
+
+    dA = b.fp4_linear_bwd_dgrad(dYd, Wd)
+    assert_close(dA, o.fp4_linear_bwd_dgrad(dY.numpy(), W.numpy(), "f32"), dtype, "dA")
+
+    if M % 32 == 0:
+        dW = b.fp4_linear_bwd_wgrad(Ad, dYd, Wd, ctx, 5.0, 3.0)
+        assert dW.dtype == torch.float32
+        assert_close(dW, o.fp4_linear_bwd_wgrad(A.numpy(), dY.numpy(), W.numpy(), alpha, 5.0, 3.0), "f32", "dW")
+        G = b.fp4_linear_bwd_wgrad(Ad, dYd, Wd, ctx, 0.0, 3.0)
+        assert_close(G, o.fp4_linear_bwd_wgrad(A.numpy(), dY.numpy(), W.numpy(), alpha, 0.0, 3.0), "f32", "G (STE)")
+
+
+def test_forward_is_deterministic_and_keeps_guard_bands():
+    A, W, _ = synth.small_case(256, 512, 520, "bf16", seed=1)
+    Ad, Wd = dev(A, "bf16"), dev(W, "bf16")
+    buf = torch.full((256 + 2, 520), 7.0, dtype=torch.bfloat16, device="cuda")
+    Y1, _ = b.fp4_linear_fwd(Ad, Wd, 0.99, Y=buf[1:-1])
+    Y1 = Y1.clone()
+    Y2, _ = b.fp4_linear_fwd(Ad, Wd, 0.99)
+    assert torch.equal(Y1, Y2)
+    assert torch.all(buf[0] == 7.0) and torch.all(buf[-1] == 7.0)
