@@ -3,6 +3,7 @@
 // synchronizes or keeps state; every buffer is the caller's.
 #include "fp4_common.h"
 
+#include <algorithm>
 #include <cmath>
 #include <limits>
 
@@ -180,6 +181,7 @@ extern "C" int occ_clamp_residual(const void* x, fp4_dtype dt, int64_t rows, int
   hipStream_t s = (hipStream_t)stream;
   Carver c(reinterpret_cast<void*>(align_up((size_t)(uintptr_t)workspace, 256)));
   OccTemps t = carve_occ(c, rows, 2 * tail_count(rows * cols, 0.9));
+  capacity = std::min(capacity, 2 * tail_count(rows * cols, 0.9));  // never beyond the temporaries
   int rc = fp4_launch_thresholds(x, dt == FP4_BF16, rows, cols, ld, k, thresholds, t.select, t.total, s);
   if (rc) return rc;
   rc = fp4_launch_occ_rows(x, dt == FP4_BF16, rows, cols, ld, thresholds, codes, gamma, x_clamped, t.tmp_col,
@@ -216,17 +218,18 @@ extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_
   if (rc) return rc;
   const float* addend = nullptr;
   if (occ) {
+    const int64_t cap = std::min(saved->capacity, 2 * tail_count(M * K, 0.9));  // never beyond the temporaries
     rc = fp4_launch_thresholds(A, bf16, M, K, K, k, saved->thresholds, w.occ.select, w.occ.total, s);
     if (rc) return rc;
     rc = fp4_launch_occ_rows(A, bf16, M, K, K, saved->thresholds, w.qA, w.gA, nullptr, w.occ.tmp_col,
-                             w.occ.tmp_val, w.occ.row_start, w.occ.row_cnt, w.occ.total, saved->capacity, s);
+                             w.occ.tmp_val, w.occ.row_start, w.occ.row_cnt, w.occ.total, cap, s);
     if (rc) return rc;
-    rc = fp4_launch_csr_finalize(w.occ.tmp_col, w.occ.tmp_val, w.occ.row_start, w.occ.row_cnt, M,
-                                 saved->capacity, saved->row_ptr, saved->col_idx, saved->val, saved->nnz, s);
+    rc = fp4_launch_csr_finalize(w.occ.tmp_col, w.occ.tmp_val, w.occ.row_start, w.occ.row_cnt, M, cap,
+                                 saved->row_ptr, saved->col_idx, saved->val, saved->nnz, s);
     if (rc) return rc;
     // Delta_A W with the unquantized W, fp32; lands where the GEMM epilogue picks it up
     float* R = bf16 ? w.R : reinterpret_cast<float*>(Y);
-    rc = fp4_launch_spmm(saved->row_ptr, saved->col_idx, saved->val, saved->capacity, M, W, bf16, N, R, s);
+    rc = fp4_launch_spmm(saved->row_ptr, saved->col_idx, saved->val, cap, M, W, bf16, N, R, s);
     if (rc) return rc;
     addend = R;
   } else {

@@ -101,8 +101,14 @@ __global__ __launch_bounds__(256) void sel_pick_kernel(SelState* st, unsigned lo
       st->prefix[s] = (st->prefix[s] << bits) | (uint32_t)b;
       if (last) {
         uint32_t key = st->prefix[s];
-        if (key_bits == 16) key <<= 16;
-        thresholds[s] = u2f(f32_from_order_key(key));
+        if (key_bits == 16) {
+          // 16-bit keys are the top half of the fp32 key of a bf16 value; undo the map on
+          // 16 bits so the low half of the fp32 pattern stays zero
+          const uint32_t h = (key & 0x8000u) ? (key & 0x7fffu) : (~key & 0xffffu);
+          thresholds[s] = u2f(h << 16);
+        } else {
+          thresholds[s] = u2f(f32_from_order_key(key));
+        }
       }
     }
     __syncthreads();
