@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the FP4 linear hot path on one MI355X.
+
+A step is one pass of the whole path -- forward (OCC + quantize + FP4 GEMM + residual),
+activation gradient and weight gradient (with DGE) -- over every linear layer of the
+workload, on synthetic inputs already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c4|c5|c1]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP4_MFMA_PEAK_TFLOPS = 10100.0   # MI355X dense FP4 (published)
+
+
+def build_layers(cfg, torch, b):
+    """Per-layer device tensors, drawn on the GPU with the workload's recipe."""
+    layers = []
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    for li, l in enumerate(cfg.layers):
+        g = torch.Generator(device="cuda")
+        g.manual_seed(20250117 + 1000 * cfg.idx + 10 * li)
+        A = torch.randn(l.M, l.K, generator=g, device="cuda", dtype=torch.float32)
+        if cfg.act == "gauss_outlier":
+            n_out = max(1, int(round(cfg.outlier_frac * l.K)))
+            ch = torch.randperm(l.K, generator=g, device="cuda")[:n_out]
+            A[:, ch] *= cfg.outlier_scale
+        else:  # student-t, nu = 3
+            chi = torch.zeros_like(A)
+            for _ in range(3):
+                chi += torch.randn(l.M, l.K, generator=g, device="cuda", dtype=torch.float32) ** 2
+            A = A / torch.sqrt(chi / 3.0)
+            del chi
+        A = A.to(tdt)
+        W = (torch.randn(l.K, l.N, generator=g, device="cuda", dtype=torch.float32) * 0.02).to(tdt)
+        dY = (torch.randn(l.M, l.N, generator=g, device="cuda", dtype=torch.float32) * 1e-2).to(tdt)
+        layers.append(dict(shape=l, A=A, W=W, dY=dY,
+                           Y=torch.empty(l.M, l.N, device="cuda", dtype=tdt),
+                           dA=torch.empty(l.M, l.K, device="cuda", dtype=tdt),
+                           dW=torch.empty(l.K, l.N, device="cuda", dtype=torch.float32),
+                           ctx=b.FwdCtx(l.M, l.K, l.N, cfg.alpha)))
+    return layers
+
+
+def run_step(cfg, layers, b, ws):
+    for L in layers:
+        b.fp4_linear_fwd(L["A"], L["W"], cfg.alpha, ctx=L["ctx"], Y=L["Y"], ws=ws)
+        b.fp4_linear_bwd_dgrad(L["dY"], L["W"], dA=L["dA"], ws=ws)
+        b.fp4_linear_bwd_wgrad(L["A"], L["dY"], L["W"], L["ctx"], cfg.dge_k, cfg.dge_cap, dW=L["dW"], ws=ws)
+
+
+def cpu_baseline(cfg):
+    """The oracle, as it stands, on a bounded slice of the same workload."""
+    import numpy as np
+    from oracle import fp4_oracle as o
+    from paper_2501_17116_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = 1
+    l = min(cfg.layers, key=lambda s: s.K * s.N)
+    Ms = min(l.M, 256)
+    A, W, dY = synth.make_layer(cfg, l, M=Ms)
+    A, W, dY = A.numpy(), W.numpy(), dY.numpy()
+    t0 = time.perf_counter()
+    o.fp4_linear_fwd(A, W, cfg.alpha, cfg.dtype)
+    o.fp4_linear_bwd_dgrad(dY, W, cfg.dtype)
+    o.fp4_linear_bwd_wgrad(A, dY, W, cfg.alpha, cfg.dge_k, cfg.dge_cap)
+    dt = time.perf_counter() - t0
+    flops = 3 * 2.0 * Ms * l.K * l.N
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": "layer %s (K=%d, N=%d) with %d of its %d tokens, fwd+dgrad+wgrad, %.1f s" %
+                      (l.name, l.K, l.N, Ms, l.M, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.stderr.write("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+                         "--gpus %d is not supported\n" % args.gpus)
+        sys.exit(2)
+
+    import torch
+    from paper_2501_17116_amd import binding as b
+    from paper_2501_17116_amd import synth
+
+    b.lib()   # fail loudly if the HIP library is missing
+    cfg = synth.CONFIGS[args.workload]
+    torch.cuda.set_device(0)
+    layers = build_layers(cfg, torch, b)
+    ws = b.Workspace()
+    n_gemm = 3 * len(layers)
+    gemm_flops = []
+    for L in layers:
+        l = L["shape"]
+        gemm_flops += [2.0 * l.M * l.K * l.N] * 3
+    step_flops = sum(gemm_flops)
+
+    for _ in range(args.warmup):
+        run_step(cfg, layers, b, ws)
+    torch.cuda.synchronize()
+
+    b.fp4_trace_gemm_begin(n_gemm * args.steps)
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t_wall0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        run_step(cfg, layers, b, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    t_wall = time.perf_counter() - t_wall0
+    ms_total = e0.elapsed_time(e1)
+    gemm_ms = b.fp4_trace_gemm_end(n_gemm * args.steps)
+    ms_per_step = ms_total / args.steps
+    value = step_flops / (ms_per_step * 1e-3) / 1e12
+
+    avg_gemm_ms = sum(gemm_ms) / max(len(gemm_ms), 1)
+    avg_gemm_flops = step_flops / n_gemm
+    achieved = avg_gemm_flops / (avg_gemm_ms * 1e-3) / 1e12 if gemm_ms else 0.0
+    out = {
+        "metric": "FP4 linear fwd+bwd TFLOP/s and % of FP4 MFMA peak; quantize GB/s",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp4-e2m1 x fp4-e2m1 -> f32", "data": "synthetic",
+        "config": {"workload": "%s (%s): %s; M=%d tokens, %s masters, OCC alpha=%g, DGE k=%g; "
+                               "fwd+dgrad+wgrad per layer" %
+                               (args.workload, cfg.name,
+                                ", ".join("%s %dx%d" % (l.name, l.K, l.N) for l in cfg.layers),
+                                cfg.layers[0].M, cfg.dtype, cfg.alpha, cfg.dge_k),
+                   "gemm_flop_per_step": step_flops, "wall_ms_per_step": t_wall / args.steps * 1e3},
+        "roofline": {"bound": "mfma", "kernel": "fp4_gemm_nt_kernel", "achieved": achieved,
+                     "peak": FP4_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / FP4_MFMA_PEAK_TFLOPS,
+                     "traffic": None, "avg_launch_ms": avg_gemm_ms, "launches": len(gemm_ms),
+                     "gemm_share_of_step": sum(gemm_ms) / ms_total if ms_total else None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

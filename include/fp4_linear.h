@@ -178,6 +178,16 @@ int fp4_residual_spmm(const int64_t* row_ptr, const int32_t* col_idx, const floa
  * the CPU; lets the rounding be checked exhaustively without a GPU). */
 int fp4_host_round_codes(const float* x_host, int64_t n, uint8_t* codes_host);
 
+/* ---- measurement helper (host-side state, off by default; not thread-safe) ----
+ * Between fp4_trace_gemm_begin(n) and fp4_trace_gemm_end() every launch of the FP4 GEMM
+ * kernel, from any entry point, is bracketed by a pair of HIP events recorded on the
+ * launch's own stream (at most n launches; later ones are not recorded).
+ * fp4_trace_gemm_end waits for the recorded launches, writes their durations in
+ * milliseconds, in launch order, to ms_host[0..capacity) (HOST memory) and returns the
+ * number of launches recorded (>= 0) or a negative fp4_status. */
+int fp4_trace_gemm_begin(int max_launches);
+int fp4_trace_gemm_end(float* ms_host, int capacity);
+
 #ifdef __cplusplus
 }
 #endif

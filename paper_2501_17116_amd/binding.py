@@ -62,6 +62,10 @@ def lib() -> C.CDLL:
         L.fp4_dge_apply.argtypes = [vp, vp, i32, vp, i64, i64, f32, f32, vp, vp]
         L.fp4_residual_spmm.argtypes = [vp, vp, vp, i64, i64, vp, i32, i64, vp, vp]
         L.fp4_host_round_codes.argtypes = [vp, i64, vp]
+        L.fp4_trace_gemm_begin.argtypes = [i32]
+        L.fp4_trace_gemm_begin.restype = i32
+        L.fp4_trace_gemm_end.argtypes = [vp, i32]
+        L.fp4_trace_gemm_end.restype = i32
         for name in ("fp4_quantize", "occ_clamp_residual", "fp4_linear_fwd", "fp4_linear_bwd_dgrad",
                      "fp4_linear_bwd_wgrad", "fp4_gemm", "fp4_unpack", "fp4_dge_apply", "fp4_residual_spmm",
                      "fp4_host_round_codes"):
@@ -308,3 +312,16 @@ def fp4_host_round_codes(x_host):
     _check(lib().fp4_host_round_codes(x.ctypes.data_as(C.c_void_p), x.size, out.ctypes.data_as(C.c_void_p)),
            "fp4_host_round_codes")
     return out
+
+
+def fp4_trace_gemm_begin(max_launches: int) -> None:
+    _check(lib().fp4_trace_gemm_begin(int(max_launches)), "fp4_trace_gemm_begin")
+
+
+def fp4_trace_gemm_end(max_launches: int):
+    """Durations (ms) of the GEMM launches recorded since fp4_trace_gemm_begin, in order."""
+    buf = (C.c_float * max_launches)()
+    n = lib().fp4_trace_gemm_end(C.cast(buf, C.c_void_p), max_launches)
+    if n < 0:
+        raise Fp4Error(n, "fp4_trace_gemm_end")
+    return [float(buf[i]) for i in range(min(n, max_launches))]
