@@ -24,13 +24,22 @@ namespace {
 constexpr int BM = 256;          // rows of L per tile  (output rows)
 constexpr int BN = 256;          // rows of Rt per tile (output columns)
 constexpr int BKB = 128;         // bytes of K per step (256 codes)
-constexpr int LDS_ROW = BKB + 16;  // padded row: 16-byte reads of 32 consecutive rows hit distinct banks
-constexpr int NTHREADS = 256;
+constexpr int WQ = 4;            // waves along the output-column axis (x 2 along rows)
+constexpr int NTHREADS = 2 * WQ * 64;
+constexpr int NWAVES = NTHREADS / 64;
+constexpr int QI = BN / WQ / 32;  // 32-column MFMA blocks per wave
+constexpr int NLD = BM * 8 / NTHREADS;  // 16-byte chunks per thread, per operand, per K step
 constexpr int GROUP_P = 8;       // tile-rows per L2 reuse group
-constexpr int TILE_BYTES = BM * LDS_ROW;          // one operand, one stage
-constexpr int SMEM_BYTES = 4 * TILE_BYTES;        // 2 operands x 2 stages = 147456
-constexpr int EPI_LD = 132;                       // floats per row of the epilogue staging tile
-static_assert(4 * 64 * EPI_LD * 4 <= SMEM_BYTES, "epilogue staging must fit the operand buffers");
+constexpr int TILE_BYTES = BM * BKB;              // one operand, one stage (rows unpadded)
+constexpr int EPI_LD = QI * 32 + 4;               // floats per row of the epilogue staging tile
+constexpr int EPI_BYTES = NWAVES * 64 * EPI_LD * 4;
+constexpr int SMEM_BYTES = 4 * TILE_BYTES > EPI_BYTES ? 4 * TILE_BYTES : EPI_BYTES;
+static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
+
+// LDS layout of an operand stage: row r occupies bytes [128 r, 128 r + 128); its 16-byte
+// chunk c sits in slot c ^ ((r >> 1) & 7).  Sixteen consecutive rows reading the same logical
+// chunk then touch sixteen different 16-byte bank groups of the 256-byte bank period, and a
+// wave's direct-to-LDS load (64 lanes x 16 B = 8 whole rows) stays one contiguous KiB.
 
 struct GemmShape {
   int64_t P, Q, Kb, ldo, ldw;
@@ -45,6 +54,17 @@ FP4_D void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
 template <int N, class F>
 FP4_D void static_for(F&& f) {
   static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// two fp32 -> packed bf16 pair, round to nearest even (hardware conversion on gfx950)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+FP4_D uint32_t pack_bf16x2(float a, float b) {
+  f32x2_t f = {a, b};
+  bf16x2_t h = __builtin_convertvector(f, bf16x2_t);
+  union { bf16x2_t h; uint32_t u; } c;
+  c.h = h;
+  return c.u;
 }
 
 FP4_D float dge_factor(float w, float gamma, float inv_k_minus_1, float inv_k, float cap) {
@@ -85,129 +105,179 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept scalar
   const int wave_p = wave & 1;
-  const int wave_q = wave >> 1;
+  const int wave_q = wave >> 1;   // 0 .. WQ-1
   const int l32 = lane & 31;
   const int lhi = lane >> 5;
 
   const int64_t P0 = (int64_t)tp * BM;
   const int64_t Q0 = (int64_t)tq * BN;
 
-  // global -> register staging: 8 threads cover one 128-byte row segment
-  const int ld_chunk = tid & 7;
-  const int ld_row = tid >> 3;  // 0..31, rows ld_row + 32*i
-  const uint8_t* gL[8];
-  const uint8_t* gR[8];
+  // Operand staging.  Load instruction j of wave w fills the KiB [(w*NLD + j) * 1024, +1024) of a
+  // stage = tile rows 8*(w*NLD+j) .. +7; lane i owns slot i & 7 of row (i >> 3) of that group and
+  // therefore fetches logical chunk (i & 7) ^ ((row >> 1) & 7) of its row.
+  uint32_t goffL[NLD], goffR[NLD];   // byte offset of this lane's chunk from the tile's first row
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    int64_t rp = min(P0 + ld_row + 32 * i, g.P - 1);
-    int64_t rq = min(Q0 + ld_row + 32 * i, g.Q - 1);
-    gL[i] = Lp + rp * g.Kb;
-    gR[i] = Rp + rq * g.Kb;
+  for (int j = 0; j < NLD; ++j) {
+    const int row = 8 * (wave * NLD + j) + (lane >> 3);
+    const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+    const int64_t rp = min(P0 + row, g.P - 1) - P0;   // rows past the edge re-read the last row
+    const int64_t rq = min(Q0 + row, g.Q - 1) - Q0;
+    goffL[j] = (uint32_t)(rp * g.Kb + chunk * 16);
+    goffR[j] = (uint32_t)(rq * g.Kb + chunk * 16);
   }
-  const int st_off = ld_row * LDS_ROW + ld_chunk * 16;
+  // tile base pointers are workgroup-uniform; say so, so descriptors and offsets stay scalar
+  auto uniform_ptr = [](const uint8_t* p) {
+    const uint64_t v = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const uint8_t*)(((uint64_t)hi << 32) | lo);
+  };
+  const uint8_t* const tileL = uniform_ptr(Lp + P0 * g.Kb);
+  const uint8_t* const tileR = uniform_ptr(Rp + Q0 * g.Kb);
+  const int lds_lane = (wave * NLD) * 1024 + lane * 16;
+  // buffer descriptors over the tile's rows: loads past the end of the matrix return zero
+  const uint64_t bytesL = (uint64_t)(g.P - P0) * (uint64_t)g.Kb, bytesR = (uint64_t)(g.Q - Q0) * (uint64_t)g.Kb;
+  const __amdgpu_buffer_rsrc_t rsrcL = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(tileL), 0,
+      __builtin_amdgcn_readfirstlane((int)(bytesL > 0xffffffffull ? 0xffffffffu : (uint32_t)bytesL)), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrcR = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint8_t*>(tileR), 0,
+      __builtin_amdgcn_readfirstlane((int)(bytesR > 0xffffffffull ? 0xffffffffu : (uint32_t)bytesR)), 0x00020000);
 
-  f32x16 acc[4][4];
+  f32x16 acc[QI][4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < QI; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
   const int KT = (int)((g.Kb + BKB - 1) / BKB);
-  u32x4 rl[8], rr[8];
 
-  // Loads never branch: a chunk past K reads chunk 0 of its row instead and is zeroed when
-  // it is written to LDS.
-  bool ld_ok = true;
-  auto load_tile = [&](int kt) {
-    const int64_t kb = (int64_t)kt * BKB + ld_chunk * 16;
-    ld_ok = kb < g.Kb;
-    const int64_t kc = ld_ok ? kb : 0;
+  // Fast path: global -> LDS without passing through registers.  Ragged K (K step overhanging
+  // the row): through registers, blanking the overhang.
+  auto load_tile = [&](int kt, int buf, int jb, int je) {
+    const uint8_t* bL = tileL + (int64_t)kt * BKB;
+    const uint8_t* bR = tileR + (int64_t)kt * BKB;
+    if constexpr (!KRAGGED) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      rl[i] = *reinterpret_cast<const u32x4*>(gL[i] + kc);
-      rr[i] = *reinterpret_cast<const u32x4*>(gR[i] + kc);
-      if constexpr (KRAGGED) {   // K not a multiple of the K step: blank the overhang
+      for (int j = jb; j < je; ++j) {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rsrcL, (__attribute__((address_space(3))) void*)(sL + buf * TILE_BYTES + (wave * NLD + j) * 1024), 16,
+            goffL[j], kt * BKB, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rsrcR, (__attribute__((address_space(3))) void*)(sR + buf * TILE_BYTES + (wave * NLD + j) * 1024), 16,
+            goffR[j], kt * BKB, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int j = jb; j < je; ++j) {
+        const int row = 8 * (wave * NLD + j) + (lane >> 3);
+        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+        const bool ok = (int64_t)kt * BKB + chunk * 16 < g.Kb;
         const u32x4 z = {0u, 0u, 0u, 0u};
-        rl[i] = ld_ok ? rl[i] : z;
-        rr[i] = ld_ok ? rr[i] : z;
+        u32x4 a = z, b = z;
+        if (ok) {
+          a = *reinterpret_cast<const u32x4*>(bL + goffL[j]);
+          b = *reinterpret_cast<const u32x4*>(bR + goffR[j]);
+        }
+        *reinterpret_cast<u32x4*>(sL + buf * TILE_BYTES + lds_lane + j * 1024) = a;
+        *reinterpret_cast<u32x4*>(sR + buf * TILE_BYTES + lds_lane + j * 1024) = b;
       }
     }
   };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      *reinterpret_cast<u32x4*>(sL + buf * TILE_BYTES + st_off + 32 * i * LDS_ROW) = rl[i];
-      *reinterpret_cast<u32x4*>(sR + buf * TILE_BYTES + st_off + 32 * i * LDS_ROW) = rr[i];
-    }
-  };
 
-  const int frag_off_l = (wave_p * 128 + l32) * LDS_ROW + lhi * 16;
-  const int frag_off_r = (wave_q * 128 + l32) * LDS_ROW + lhi * 16;
-  u32x4 fl[2][4], fr[2][4];
-  auto read_frags = [&](int buf, int ks, int set) {
+  // MFMA fragments: lane (l32, lhi) needs, for k-slice ks of a stage, logical chunk 2 ks + lhi
+  // of rows l32 + 32 j.  (row >> 1) & 7 only depends on l32 because the row bases are
+  // multiples of 32.
+  const int key = (l32 >> 1) & 7;
+  int frag_l[4], frag_r[4];   // per k-slice byte offsets inside a stage
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      fl[set][j] = *reinterpret_cast<const u32x4*>(sL + buf * TILE_BYTES + frag_off_l + j * 32 * LDS_ROW + ks * 32);
-      fr[set][j] = *reinterpret_cast<const u32x4*>(sR + buf * TILE_BYTES + frag_off_r + j * 32 * LDS_ROW + ks * 32);
-    }
+  for (int ks = 0; ks < 4; ++ks) {
+    const int slot = (2 * ks + lhi) ^ key;
+    frag_l[ks] = (wave_p * 128 + l32) * BKB + slot * 16;
+    frag_r[ks] = (wave_q * (QI * 32) + l32) * BKB + slot * 16;
+  }
+  u32x4 fl[4], fr[QI];
+  auto read_frags = [&](int buf, int ks) {
+#pragma unroll
+    for (int j = 0; j < QI; ++j)
+      fr[j] = *reinterpret_cast<const u32x4*>(sR + buf * TILE_BYTES + frag_r[ks] + j * 32 * BKB);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      fl[j] = *reinterpret_cast<const u32x4*>(sL + buf * TILE_BYTES + frag_l[ks] + j * 32 * BKB);
   };
   const int one = 0x7f7f7f7f;  // E8M0 127 = 2^0 in every byte: hardware block scale off
   // MFMA "A" operand = Rt rows (output columns, indexed by the accumulator registers),
   // "B" operand = L rows (output rows, indexed by lane % 32): a lane ends up holding runs of
   // 4 consecutive output columns of one output row.
-  auto mfma_rows = [&](int set, int qi_begin, int qi_end) {
+  auto mfma_slice = [&]() {
 #pragma unroll
-    for (int qi = qi_begin; qi < qi_end; ++qi) {
-      i32x8 a = {(int)fr[set][qi].x, (int)fr[set][qi].y, (int)fr[set][qi].z, (int)fr[set][qi].w, 0, 0, 0, 0};
+    for (int qi = 0; qi < QI; ++qi) {
+      i32x8 a = {(int)fr[qi].x, (int)fr[qi].y, (int)fr[qi].z, (int)fr[qi].w, 0, 0, 0, 0};
 #pragma unroll
       for (int pj = 0; pj < 4; ++pj) {
-        i32x8 b = {(int)fl[set][pj].x, (int)fl[set][pj].y, (int)fl[set][pj].z, (int)fl[set][pj].w, 0, 0, 0, 0};
+        i32x8 b = {(int)fl[pj].x, (int)fl[pj].y, (int)fl[pj].z, (int)fl[pj].w, 0, 0, 0, 0};
         acc[qi][pj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[qi][pj], 4, 4, 0, one, 0, one);
       }
     }
   };
 
-  load_tile(0);
-  store_tile(0);
+  load_tile(0, 0, 0, NLD);
+  __builtin_amdgcn_s_waitcnt(0);   // direct loads are tracked by vmcnt: all of this wave's have landed
   __syncthreads();
-  read_frags(0, 0, 0);
+  read_frags(0, 0);
 
+  // Ping-pong: the two waves of a SIMD (wave w and w + 4) alternate between a compute phase
+  // (the MFMAs of one k-slice, back to back) and a memory phase (fragment reads of the next
+  // k-slice and this wave's share of the next tile's global -> LDS loads), half a period apart,
+  // so one wave's MFMAs cover the other's memory instructions.  Every phase ends in a
+  // workgroup barrier; the second group takes one extra barrier first, the first group one
+  // extra at the end.  The order inside a phase is pinned with scheduling barriers.
+  const bool second_group = wave >= NWAVES / 2;
+  if (second_group) __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
   for (int kt = 0; kt < KT; ++kt) {
     const int cur = kt & 1;
-    load_tile(min(kt + 1, KT - 1));   // last iteration reloads its own tile: harmless, branch-free
+    const int ktn = min(kt + 1, KT - 1);   // last iteration refetches its own tile: harmless, branch-free
+    static_for<4>([&](auto ksc) {
+      constexpr int ks = decltype(ksc)::value;
+      // ---- compute phase
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_setprio(1);
+      mfma_slice();
+      // pin the MFMAs to this phase: the accumulators pass through an (empty) volatile asm
+      // that the optimizer must keep in order with the barriers
 #pragma unroll
-    for (int ks = 0; ks < 3; ++ks) {
-      read_frags(cur, ks + 1, (ks + 1) & 1);
-      mfma_rows(ks & 1, 0, 4);
-      // interleave: the 8 LDS reads of the next k-slice (and, in the first slice, the 16
-      // global loads of the next tile) ride under the 16 MFMAs of this one
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // 2 MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 DS read
-        if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);  // 2 VMEM read
+      for (int qi = 0; qi < QI; ++qi)
+        asm volatile("" : "+v"(acc[qi][0]), "+v"(acc[qi][1]), "+v"(acc[qi][2]), "+v"(acc[qi][3]));
+      __builtin_amdgcn_s_setprio(0);
+      __builtin_amdgcn_sched_barrier(0);
+      // before anyone reads the next tile (memory phase of k-slice 3) every wave's loads of
+      // it must have landed: each wave drains its own before the barrier that precedes the
+      // first such read (the first group's barrier after compute 3, the second group's
+      // barrier after memory 2)
+      if constexpr (ks == 3) {
+        if (!second_group) __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
       }
-    }
-    mfma_rows(1, 0, 2);
-    store_tile(cur ^ 1);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
-      __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);  // 2 DS write
-    }
-    __syncthreads();
-    read_frags(cur ^ 1, 0, 0);
-    mfma_rows(1, 2, 4);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    }
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");   // LDS is filled by direct loads the compiler does not see as stores
+      __builtin_amdgcn_sched_barrier(0);
+      // ---- memory phase
+      if constexpr (ks < 3) read_frags(cur, ks + 1);
+      else read_frags(cur ^ 1, 0);
+      if constexpr (ks < 2) load_tile(ktn, cur ^ 1, ks * (NLD / 2), (ks + 1) * (NLD / 2));
+      if constexpr (ks == 2) {
+        if (second_group) __builtin_amdgcn_s_waitcnt(0x0f70);    // vmcnt(0)
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+    });
   }
+  if (!second_group) __builtin_amdgcn_s_barrier();
   __syncthreads();   // every wave is done with the operand buffers
 
   // ---- epilogue --------------------------------------------------------------------------
@@ -216,28 +286,31 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
   // consecutive columns of a row, adds the addend, applies the DGE factor, converts and
   // stores 16 / 32 contiguous bytes, 16 lanes per row.
   float* const stage = reinterpret_cast<float*>(smem) + wave * 64 * EPI_LD;
+  constexpr int WCOLS = QI * 32;        // columns per wave
+  constexpr int LPR = WCOLS / 8;        // lanes per row in phase B (8 columns each)
+  constexpr int RPP = 64 / LPR;         // rows per pass
   const bool scaled = gl != nullptr;
-  float ir[4][4][4];
+  float ir[QI][4][4];
   if (scaled) {
 #pragma unroll
-    for (int qi = 0; qi < 4; ++qi)
+    for (int qi = 0; qi < QI; ++qi)
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int64_t q = min(Q0 + wave_q * 128 + qi * 32 + g4 * 8 + lhi * 4 + e, g.Q - 1);
+          const int64_t q = min(Q0 + wave_q * WCOLS + qi * 32 + g4 * 8 + lhi * 4 + e, g.Q - 1);
           ir[qi][g4][e] = __builtin_amdgcn_rcpf(gr[q]);
         }
   } else {
 #pragma unroll
-    for (int qi = 0; qi < 4; ++qi)
+    for (int qi = 0; qi < QI; ++qi)
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4)
 #pragma unroll
         for (int e = 0; e < 4; ++e) ir[qi][g4][e] = 1.0f;
   }
-  const int bcol = (lane & 15) * 8;                     // phase B: this lane's 8 columns
-  const int64_t q0 = Q0 + wave_q * 128 + bcol;
+  const int bcol = (lane % LPR) * 8;                    // phase B: this lane's 8 columns
+  const int64_t q0 = Q0 + wave_q * WCOLS + bcol;
   const bool q_full = q0 + 7 < g.Q;
   float gw[8];
   const float inv_k = DGE ? 1.0f / g.dge_k : 1.0f;
@@ -254,7 +327,7 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
       const int64_t p = min(P0 + wave_p * 128 + pj * 32 + l32, g.P - 1);
       float il = 1.0f;
       if (scaled) il = __builtin_amdgcn_rcpf(gl[p]);
-      static_for<16>([&](auto ic) {
+      static_for<4 * QI>([&](auto ic) {
         constexpr int qi = decltype(ic)::value / 4, g4 = decltype(ic)::value % 4;
         f32x4 y;
         const f32x16& a16 = half == 0 ? acc[qi][pjl] : acc[qi][2 + pjl];
@@ -268,8 +341,8 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 #pragma unroll 4
-    for (int pass = 0; pass < 16; ++pass) {
-      const int rloc = pass * 4 + (lane >> 4);
+    for (int pass = 0; pass < 64 / RPP; ++pass) {
+      const int rloc = pass * RPP + lane / LPR;
       const int64_t p = P0 + wave_p * 128 + half * 64 + rloc;
       const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + rloc * EPI_LD + bcol);
       const f32x4 v1 = *reinterpret_cast<const f32x4*>(stage + rloc * EPI_LD + bcol + 4);
@@ -311,10 +384,10 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
           uint16_t* o = reinterpret_cast<uint16_t*>(outp) + p * g.ldo + q0;
           if (q_full) {
             u32x4 pk;
-            pk.x = f32_to_bf16_bits(y[0]) | (f32_to_bf16_bits(y[1]) << 16);
-            pk.y = f32_to_bf16_bits(y[2]) | (f32_to_bf16_bits(y[3]) << 16);
-            pk.z = f32_to_bf16_bits(y[4]) | (f32_to_bf16_bits(y[5]) << 16);
-            pk.w = f32_to_bf16_bits(y[6]) | (f32_to_bf16_bits(y[7]) << 16);
+            pk.x = pack_bf16x2(y[0], y[1]);
+            pk.y = pack_bf16x2(y[2], y[3]);
+            pk.z = pack_bf16x2(y[4], y[5]);
+            pk.w = pack_bf16x2(y[6], y[7]);
             *reinterpret_cast<u32x4*>(o) = pk;
           } else {
 #pragma unroll
