@@ -71,7 +71,8 @@ typedef enum {
   FP4_OP_OCC = 1,      /* (M=rows, K=cols, N ignored)                                     */
   FP4_OP_FWD = 2,
   FP4_OP_DGRAD = 3,
-  FP4_OP_WGRAD = 4
+  FP4_OP_WGRAD = 4,
+  FP4_OP_SPMM = 5      /* (M=P rows of S, K=Q, N)                                        */
 } fp4_op;
 
 /* What the forward pass leaves for the weight-gradient pass (Sec. 3.1 needs the
@@ -168,10 +169,11 @@ int fp4_dge_apply(const float* G, const void* W, fp4_dtype dt, const float* gamm
                   int64_t K, int64_t N, float dge_k, float dge_cap, float* dW, void* stream);
 
 /* R[P x N] (fp32, overwritten) = S D with S a P x Q CSR matrix (fp32 values) and D
- * [Q x N] dense of dtype dt: the high-precision sparse product of Sec. 3.2. */
+ * [Q x N] dense of dtype dt: the high-precision sparse product of Sec. 3.2.  Column indices
+ * must ascend inside a row.  Workspace: fp4_workspace_bytes(FP4_OP_SPMM, P, Q, N, dt). */
 int fp4_residual_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val,
                       int64_t P, int64_t Q, const void* D, fp4_dtype dt, int64_t N,
-                      float* R, void* stream);
+                      float* R, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Host-side evaluation of the library's own rounding routine: codes[i] = Q(x[i]) for
  * n fp32 values in HOST memory (the same inline function the kernels use, compiled for

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libfp4mi.so")
 
 FP4_F32, FP4_BF16 = 0, 1
 FP4_AXIS_ROW, FP4_AXIS_COL = 0, 1
-FP4_OP_QUANTIZE, FP4_OP_OCC, FP4_OP_FWD, FP4_OP_DGRAD, FP4_OP_WGRAD = range(5)
+FP4_OP_QUANTIZE, FP4_OP_OCC, FP4_OP_FWD, FP4_OP_DGRAD, FP4_OP_WGRAD, FP4_OP_SPMM = range(6)
 
 _lib = None
 
@@ -60,7 +60,7 @@ def lib() -> C.CDLL:
         L.fp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, i32, i64, vp]
         L.fp4_unpack.argtypes = [vp, i64, i64, vp, vp]
         L.fp4_dge_apply.argtypes = [vp, vp, i32, vp, i64, i64, f32, f32, vp, vp]
-        L.fp4_residual_spmm.argtypes = [vp, vp, vp, i64, i64, vp, i32, i64, vp, vp]
+        L.fp4_residual_spmm.argtypes = [vp, vp, vp, i64, i64, vp, i32, i64, vp, vp, sz, vp]
         L.fp4_host_round_codes.argtypes = [vp, i64, vp]
         L.fp4_trace_gemm_begin.argtypes = [i32]
         L.fp4_trace_gemm_begin.restype = i32
@@ -293,14 +293,15 @@ def fp4_dge_apply(G: torch.Tensor, W: torch.Tensor, gamma_W: torch.Tensor, dge_k
 
 
 def fp4_residual_spmm(row_ptr: torch.Tensor, col_idx: torch.Tensor, val: torch.Tensor, Q: int,
-                      D: torch.Tensor, R: Optional[torch.Tensor] = None) -> torch.Tensor:
+                      D: torch.Tensor, R: Optional[torch.Tensor] = None, ws: Optional[Workspace] = None) -> torch.Tensor:
     _dev_check(row_ptr, col_idx, val, D, R)
     P = row_ptr.numel() - 1
     N = D.shape[1]
     if R is None:
         R = torch.empty((P, N), dtype=torch.float32, device=D.device)
+    w = _ws(workspace_bytes(FP4_OP_SPMM, P, Q, N, _dt(D)), ws)
     _check(lib().fp4_residual_spmm(_ptr(row_ptr), _ptr(col_idx), _ptr(val), P, Q, _ptr(D), _dt(D), N,
-                                   _ptr(R), _stream()), "fp4_residual_spmm")
+                                   _ptr(R), _ptr(w), w.numel(), _stream()), "fp4_residual_spmm")
     return R
 
 

@@ -29,9 +29,12 @@ int fp4_launch_csr_finalize(const int32_t* tmp_col, const float* tmp_val, const 
                             int32_t* col_idx, float* val, int64_t* nnz, hipStream_t s);
 int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, const float* val,
                              const int64_t* nnz, int64_t P, int64_t Q, int64_t capacity, int64_t* t_ptr,
-                             int32_t* t_idx, float* t_val, int32_t* scratch, hipStream_t s);
+                             int32_t* t_idx, float* t_val, int32_t* u_idx, float* u_val, int32_t* scratch,
+                             hipStream_t s);
+int64_t fp4_spmm_long_list_cap(int64_t capacity);
 int fp4_launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val, int64_t capacity,
-                    int64_t P, const void* D, int bf16, int64_t N, float* R, hipStream_t s);
+                    int64_t P, int64_t Q, const void* D, int bf16, int64_t N, float* R, int32_t* scratch,
+                    hipStream_t s);
 
 namespace {
 
@@ -82,7 +85,7 @@ OccTemps carve_occ(Carver& c, int64_t rows, int64_t capacity) {
 }
 
 struct FwdWs {
-  uint8_t* qA; float* gA; uint8_t* qWt; uint32_t* amax; OccTemps occ; float* R;
+  uint8_t* qA; float* gA; uint8_t* qWt; uint32_t* amax; OccTemps occ; float* R; int32_t* sp_scratch;
 };
 FwdWs carve_fwd(Carver& c, int64_t M, int64_t K, int64_t N, fp4_dtype dt) {
   FwdWs w;
@@ -94,6 +97,7 @@ FwdWs carve_fwd(Carver& c, int64_t M, int64_t K, int64_t N, fp4_dtype dt) {
   // the workspace query does not know alpha, so it provides for alpha >= 0.9
   w.occ = carve_occ(c, M, 2 * tail_count(M * K, 0.9));
   w.R = dt == FP4_BF16 ? c.take<float>((size_t)(M * N)) : nullptr;
+  w.sp_scratch = c.take<int32_t>((size_t)(64 + fp4_spmm_long_list_cap(2 * tail_count(M * K, 0.9))));
   return w;
 }
 
@@ -109,7 +113,8 @@ DgradWs carve_dgrad(Carver& c, int64_t M, int64_t K, int64_t N) {
 
 struct WgradWs {
   uint8_t* qAt; float* gAk; uint8_t* qdYt; float* gdYn; uint32_t* amax;
-  int64_t* t_ptr; int32_t* t_idx; float* t_val; int32_t* t_scratch;
+  int64_t* t_ptr; int32_t* t_idx; float* t_val; int32_t* u_idx; float* u_val; int32_t* t_scratch;
+  int32_t* sp_scratch;
 };
 WgradWs carve_wgrad(Carver& c, int64_t M, int64_t K, int64_t N) {
   WgradWs w;
@@ -122,7 +127,10 @@ WgradWs carve_wgrad(Carver& c, int64_t M, int64_t K, int64_t N) {
   w.t_ptr = c.take<int64_t>((size_t)(K + 1));
   w.t_idx = c.take<int32_t>((size_t)cap);
   w.t_val = c.take<float>((size_t)cap);
+  w.u_idx = c.take<int32_t>((size_t)cap);
+  w.u_val = c.take<float>((size_t)cap);
   w.t_scratch = c.take<int32_t>((size_t)(2 * K));
+  w.sp_scratch = c.take<int32_t>((size_t)(64 + fp4_spmm_long_list_cap(cap)));
   return w;
 }
 
@@ -156,6 +164,7 @@ extern "C" size_t fp4_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, f
     case FP4_OP_FWD: carve_fwd(c, M, K, N, dt); break;
     case FP4_OP_DGRAD: carve_dgrad(c, M, K, N); break;
     case FP4_OP_WGRAD: carve_wgrad(c, M, K, N); break;
+    case FP4_OP_SPMM: c.take<int32_t>((size_t)(64 + M + 2)); break;   // long-row list, at most M rows
     default: return 0;
   }
   return c.off + 256;
@@ -229,7 +238,7 @@ extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_
     if (rc) return rc;
     // Delta_A W with the unquantized W, fp32; lands where the GEMM epilogue picks it up
     float* R = bf16 ? w.R : reinterpret_cast<float*>(Y);
-    rc = fp4_launch_spmm(saved->row_ptr, saved->col_idx, saved->val, cap, M, W, bf16, N, R, s);
+    rc = fp4_launch_spmm(saved->row_ptr, saved->col_idx, saved->val, cap, M, K, W, bf16, N, R, w.sp_scratch, s);
     if (rc) return rc;
     addend = R;
   } else {
@@ -291,12 +300,27 @@ extern "C" int fp4_linear_bwd_wgrad(const void* A, const void* dY, const void* W
   const float* addend = nullptr;
   if (occ) {
     rc = fp4_launch_csr_transpose(saved->row_ptr, saved->col_idx, saved->val, saved->nnz, M, K,
-                                  saved->capacity, w.t_ptr, w.t_idx, w.t_val, w.t_scratch, s);
+                                  saved->capacity, w.t_ptr, w.t_idx, w.t_val, w.u_idx, w.u_val, w.t_scratch, s);
     if (rc) return rc;
-    rc = fp4_launch_spmm(w.t_ptr, w.t_idx, w.t_val, saved->capacity, K, dY, bf16, N, dW, s);
+    rc = fp4_launch_spmm(w.t_ptr, w.t_idx, w.t_val, saved->capacity, K, M, dY, bf16, N, dW, w.sp_scratch, s);
     if (rc) return rc;
     addend = dW;
   }
   return fp4_launch_gemm(w.qAt, w.gAk, w.qdYt, w.gdYn, K, N, M, addend, dW, 0, N, W, bf16, N, saved->gamma_W,
                          dge_k, dge_cap, s);
+}
+
+extern "C" int fp4_residual_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val,
+                                 int64_t P, int64_t Q, const void* D, fp4_dtype dt, int64_t N, float* R,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  if (!dtype_ok(dt)) return FP4_ERR_DTYPE;
+  if (P < 0 || Q < 0 || N < 0 || (N % 8) != 0) return FP4_ERR_SHAPE;
+  if (P == 0 || N == 0) return FP4_OK;
+  if (!row_ptr || !D || !R) return FP4_ERR_NULL;
+  if (!aligned16(D) || !aligned16(R)) return FP4_ERR_ARG;
+  if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_SPMM, P, Q, N, dt)) return FP4_ERR_WORKSPACE;
+  int32_t* scratch = reinterpret_cast<int32_t*>(align_up((size_t)(uintptr_t)workspace, 256));
+  // the long-row list is sized by P here, so any capacity is safe
+  return fp4_launch_spmm(row_ptr, col_idx, val, (int64_t)P * 2048, P, Q, D, dt == FP4_BF16, N, R, scratch,
+                         (hipStream_t)stream);
 }

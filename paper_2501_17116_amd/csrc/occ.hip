@@ -164,133 +164,6 @@ __global__ __launch_bounds__(256) void csr_gather_kernel(const int32_t* tmp_col,
   }
 }
 
-// ---- CSR transpose (P x Q -> Q x P) -----------------------------------------------------------
-__global__ void fill_i32_kernel(int32_t* p, int64_t n, int32_t v) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = v;
-}
-
-__global__ void csr_count_cols_kernel(const int32_t* col_idx, const int64_t* nnz, int64_t capacity,
-                                      int32_t* cnt) {
-  const int64_t n = min((int64_t)*nnz, capacity);
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
-    atomicAdd(&cnt[col_idx[i]], 1);
-}
-
-__global__ __launch_bounds__(256) void csr_transpose_fill_kernel(const int64_t* row_ptr, const int32_t* col_idx,
-                                                                 const float* val, int64_t rows, int64_t capacity,
-                                                                 const int64_t* t_ptr, int32_t* cursor,
-                                                                 int32_t* t_idx, float* t_val) {
-  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
-  if (row >= rows) return;
-  const int64_t b = row_ptr[row], e = min(row_ptr[row + 1], capacity);
-  for (int64_t i = b + lane; i < e; i += 64) {
-    const int32_t c = col_idx[i];
-    const int64_t pos = t_ptr[c] + atomicAdd(&cursor[c], 1);
-    t_idx[pos] = (int32_t)row;
-    t_val[pos] = val[i];
-  }
-}
-
-// Order each transposed row by index so the product below sums in a fixed order.  One
-// workgroup per row; rows up to SORT_MAX entries are sorted in LDS (bitonic), longer rows
-// are left in arrival order.
-constexpr int SORT_MAX = 16384;
-__global__ __launch_bounds__(256) void csr_sort_rows_kernel(const int64_t* ptr, int64_t rows, int32_t* idx,
-                                                            float* val) {
-  __shared__ unsigned long long s_kv[SORT_MAX];
-  const int64_t row = blockIdx.x;
-  const int64_t b = ptr[row];
-  const int L = (int)(ptr[row + 1] - b);
-  if (L < 2 || L > SORT_MAX) return;
-  int n = 1;
-  while (n < L) n <<= 1;
-  for (int i = threadIdx.x; i < n; i += 256)
-    s_kv[i] = i < L ? (((unsigned long long)(uint32_t)idx[b + i] << 32) | f2u(val[b + i])) : ~0ull;
-  __syncthreads();
-  for (int k = 2; k <= n; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int i = threadIdx.x; i < n; i += 256) {
-        const int p = i ^ j;
-        if (p > i) {
-          const bool up = (i & k) == 0;
-          unsigned long long a = s_kv[i], c = s_kv[p];
-          if ((a > c) == up) { s_kv[i] = c; s_kv[p] = a; }
-        }
-      }
-      __syncthreads();
-    }
-  }
-  for (int i = threadIdx.x; i < L; i += 256) {
-    idx[b + i] = (int32_t)(s_kv[i] >> 32);
-    val[b + i] = u2f((uint32_t)s_kv[i]);
-  }
-}
-
-// ---- sparse x dense: R[p, :] = sum_e val[e] * D[col[e], :] ------------------------------------
-template <class DT>
-FP4_D void load8d(const void* base, int64_t off, int valid, float (&v)[8]) {
-  if (valid >= 8) {
-    if constexpr (__is_same(DT, BF16)) {
-      u32x4 r = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(base) + off);
-      v[0] = u2f(r.x << 16); v[1] = u2f(r.x & 0xffff0000u);
-      v[2] = u2f(r.y << 16); v[3] = u2f(r.y & 0xffff0000u);
-      v[4] = u2f(r.z << 16); v[5] = u2f(r.z & 0xffff0000u);
-      v[6] = u2f(r.w << 16); v[7] = u2f(r.w & 0xffff0000u);
-    } else {
-      const f32x4* p = reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(base) + off);
-      f32x4 a = p[0], b = p[1];
-      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
-      v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-    }
-  } else {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float f = 0.0f;
-      if (e < valid) {
-        if constexpr (__is_same(DT, BF16))
-          f = bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(base)[off + e]);
-        else
-          f = reinterpret_cast<const float*>(base)[off + e];
-      }
-      v[e] = f;
-    }
-  }
-}
-
-template <class DT>
-__global__ __launch_bounds__(256) void spmm_rows_kernel(const int64_t* row_ptr, const int32_t* col_idx,
-                                                        const float* val, int64_t capacity, const void* D,
-                                                        int64_t N, float* R) {
-  const int64_t row = blockIdx.x;
-  const int64_t col = ((int64_t)blockIdx.y * 256 + threadIdx.x) * 8;
-  if (col >= N) return;
-  const int valid = (int)min((int64_t)8, N - col);
-  float acc[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
-  const int64_t b = row_ptr[row], en = min(row_ptr[row + 1], capacity);
-  for (int64_t i = b; i < en; ++i) {
-    const int32_t c = col_idx[i];
-    const float s = val[i];
-    float d[8];
-    load8d<DT>(D, (int64_t)c * N + col, valid, d);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = fmaf(s, d[e], acc[e]);
-  }
-  float* o = R + row * N + col;
-  if (valid >= 8 && (N % 4) == 0) {
-    f32x4 a = {acc[0], acc[1], acc[2], acc[3]}, c4 = {acc[4], acc[5], acc[6], acc[7]};
-    reinterpret_cast<f32x4*>(o)[0] = a;
-    reinterpret_cast<f32x4*>(o)[1] = c4;
-  } else {
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-      if (e < valid) o[e] = acc[e];
-  }
-}
-
 }  // namespace
 
 // ---- internal launchers -----------------------------------------------------------------------
@@ -340,43 +213,3 @@ int fp4_launch_csr_finalize(const int32_t* tmp_col, const float* tmp_val, const 
   return FP4_OK;
 }
 
-// scratch: cnt[Q] + cursor[Q] int32
-int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, const float* val,
-                             const int64_t* nnz, int64_t P, int64_t Q, int64_t capacity, int64_t* t_ptr,
-                             int32_t* t_idx, float* t_val, int32_t* scratch, hipStream_t s) {
-  int32_t* cnt = scratch;
-  int32_t* cursor = scratch + Q;
-  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((2 * Q + 255) / 256)), dim3(256), 0, s, scratch, 2 * Q, 0);
-  const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((capacity + 255) / 256, 4096));
-  hipLaunchKernelGGL(csr_count_cols_kernel, dim3(grid), dim3(256), 0, s, col_idx, nnz, capacity, cnt);
-  hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(1024), 0, s, cnt, Q, t_ptr, (int64_t*)nullptr);
-  hipLaunchKernelGGL(csr_transpose_fill_kernel, dim3((unsigned)((P + 3) / 4)), dim3(256), 0, s, row_ptr,
-                     col_idx, val, P, capacity, t_ptr, cursor, t_idx, t_val);
-  hipLaunchKernelGGL(csr_sort_rows_kernel, dim3((unsigned)Q), dim3(256), 0, s,
-                     t_ptr, Q, t_idx, t_val);
-  FP4_CHECK_LAUNCH();
-  return FP4_OK;
-}
-
-int fp4_launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val, int64_t capacity,
-                    int64_t P, const void* D, int bf16, int64_t N, float* R, hipStream_t s) {
-  if (P == 0 || N == 0) return FP4_OK;
-  dim3 grid((unsigned)P, (unsigned)((N + 2047) / 2048));
-  if (bf16)
-    hipLaunchKernelGGL((spmm_rows_kernel<BF16>), grid, dim3(256), 0, s, row_ptr, col_idx, val, capacity, D, N, R);
-  else
-    hipLaunchKernelGGL((spmm_rows_kernel<F32>), grid, dim3(256), 0, s, row_ptr, col_idx, val, capacity, D, N, R);
-  FP4_CHECK_LAUNCH();
-  return FP4_OK;
-}
-
-extern "C" int fp4_residual_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val,
-                                 int64_t P, int64_t Q, const void* D, fp4_dtype dt, int64_t N, float* R,
-                                 void* stream) {
-  if (dt != FP4_F32 && dt != FP4_BF16) return FP4_ERR_DTYPE;
-  if (P < 0 || Q < 0 || N < 0 || (N % 8) != 0) return FP4_ERR_SHAPE;
-  if (P == 0 || N == 0) return FP4_OK;
-  if (!row_ptr || !D || !R) return FP4_ERR_NULL;
-  if (!aligned16(D) || !aligned16(R)) return FP4_ERR_ARG;
-  return fp4_launch_spmm(row_ptr, col_idx, val, INT64_MAX, P, D, dt == FP4_BF16, N, R, (hipStream_t)stream);
-}

@@ -1,0 +1,339 @@
+// The high-precision sparse product of outlier compensation (Sec. 3.2):
+//   R[P x N] = S D,  S a P x Q CSR matrix with fp32 values (the clamped-away residual or its
+//   transpose), D [Q x N] dense in the master dtype, fp32 accumulation.
+// and the CSR transpose the weight-gradient pass needs (Delta_A^T dY).
+//
+// S has density 2(1 - alpha) (about 2 %), scattered, plus a few nearly dense outlier channels.
+// At that density neither a dense matrix-core product (50x wasted work) nor a row gather
+// (every non-zero re-reads a row of D from L2) is acceptable, so the product is tiled the way
+// a dense GEMM is, with plain fp32 FMAs:
+//   * a workgroup of 1024 threads owns 1024 rows of R x 64 columns, one row per thread, the
+//     64 accumulators in registers;
+//   * D is staged through LDS in slabs of 512 rows x 64 columns, widened to fp32 once per slab,
+//     so a D element is fetched from L2 once per 1024 output rows;
+//   * a thread walks its row's entries (ascending columns) slab by slab: per non-zero 64 FMAs
+//     against one LDS row.
+// Rows much longer than the rest (the outlier channels of the transposed residual) would
+// stall their workgroup; they are left out of the tiled kernel and handled by a kernel that
+// spreads one row's entries over a workgroup and reduces.
+#include "fp4_common.h"
+
+#include <algorithm>
+
+namespace {
+
+struct BF16 {};
+struct F32 {};
+
+constexpr int SP_ROWS = 1024;   // output rows per workgroup = threads
+constexpr int SP_COLS = 64;     // output columns per workgroup
+constexpr int SP_KS = 512;      // rows of D per LDS slab
+constexpr int SP_LD = SP_COLS + 4;  // padded LDS row (floats)
+constexpr int LONG_ROW = 2048;  // entries above which a row goes to the long-row kernel
+
+template <class DT>
+FP4_D void load8g(const void* base, int64_t off, int valid, float (&v)[8]) {
+  if (valid >= 8) {
+    if constexpr (__is_same(DT, BF16)) {
+      u32x4 r = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(base) + off);
+      v[0] = u2f(r.x << 16); v[1] = u2f(r.x & 0xffff0000u);
+      v[2] = u2f(r.y << 16); v[3] = u2f(r.y & 0xffff0000u);
+      v[4] = u2f(r.z << 16); v[5] = u2f(r.z & 0xffff0000u);
+      v[6] = u2f(r.w << 16); v[7] = u2f(r.w & 0xffff0000u);
+    } else {
+      const f32x4* p = reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(base) + off);
+      f32x4 a = p[0], b = p[1];
+      v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+      v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float f = 0.0f;
+      if (e < valid) {
+        if constexpr (__is_same(DT, BF16))
+          f = bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(base)[off + e]);
+        else
+          f = reinterpret_cast<const float*>(base)[off + e];
+      }
+      v[e] = f;
+    }
+  }
+}
+
+template <class DT>
+__global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __restrict__ row_ptr,
+                                                            const int32_t* __restrict__ col_idx,
+                                                            const float* __restrict__ val, int64_t capacity,
+                                                            int64_t P, int64_t Q, const void* __restrict__ D,
+                                                            int64_t N, float* __restrict__ R) {
+  __shared__ __attribute__((aligned(16))) float slab[SP_KS * SP_LD];
+  const int tid = threadIdx.x;
+  const int64_t row = (int64_t)blockIdx.x * SP_ROWS + tid;
+  const int64_t n0 = (int64_t)blockIdx.y * SP_COLS;
+  int64_t cur = 0, end = 0;
+  if (row < P) {
+    cur = row_ptr[row];
+    end = min(row_ptr[row + 1], capacity);
+    if (end - cur > LONG_ROW) end = cur;   // long rows belong to spmm_long_rows_kernel
+  }
+  float acc[SP_COLS];
+#pragma unroll
+  for (int j = 0; j < SP_COLS; ++j) acc[j] = 0.0f;
+
+  // staging map: 8 threads cover the 64 columns of a D row, 128 rows per pass, 4 passes
+  const int s_unit = tid & 7, s_row = tid >> 3;
+  const int64_t s_col = n0 + s_unit * 8;
+  const int s_valid = s_col < N ? (int)min((int64_t)8, N - s_col) : 0;
+
+  int32_t c_next = cur < end ? col_idx[cur] : 0x7fffffff;
+  float v_next = cur < end ? val[cur] : 0.0f;
+
+  for (int64_t k0 = 0; k0 < Q; k0 += SP_KS) {
+    __syncthreads();
+#pragma unroll
+    for (int ps = 0; ps < SP_KS / 128; ++ps) {
+      const int r = ps * 128 + s_row;
+      float d[8];
+      if (k0 + r < Q && s_valid > 0) load8g<DT>(D, (k0 + r) * N + s_col, s_valid, d);
+      else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) d[e] = 0.0f;
+      }
+      f32x4 a = {d[0], d[1], d[2], d[3]}, b = {d[4], d[5], d[6], d[7]};
+      *reinterpret_cast<f32x4*>(&slab[r * SP_LD + s_unit * 8]) = a;
+      *reinterpret_cast<f32x4*>(&slab[r * SP_LD + s_unit * 8 + 4]) = b;
+    }
+    __syncthreads();
+    const int32_t k_end = (int32_t)min(k0 + SP_KS, Q);
+    while (c_next < k_end) {
+      const int32_t c = c_next;
+      const float v = v_next;
+      ++cur;
+      c_next = cur < end ? col_idx[cur] : 0x7fffffff;   // fetched under the FMAs below
+      v_next = cur < end ? val[cur] : 0.0f;
+      const float* dr = &slab[(c - (int32_t)k0) * SP_LD];
+#pragma unroll
+      for (int j = 0; j < SP_COLS; j += 4) {
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(dr + j);
+        acc[j + 0] = fmaf(v, d4.x, acc[j + 0]);
+        acc[j + 1] = fmaf(v, d4.y, acc[j + 1]);
+        acc[j + 2] = fmaf(v, d4.z, acc[j + 2]);
+        acc[j + 3] = fmaf(v, d4.w, acc[j + 3]);
+      }
+    }
+  }
+  if (row >= P) return;
+  const int64_t b = row_ptr[row];
+  if (min(row_ptr[row + 1], capacity) - b > LONG_ROW) return;
+  float* o = R + row * N + n0;
+  if (n0 + SP_COLS <= N && (N % 4) == 0) {
+#pragma unroll
+    for (int j = 0; j < SP_COLS; j += 4) {
+      const f32x4 v4 = {acc[j], acc[j + 1], acc[j + 2], acc[j + 3]};
+      *reinterpret_cast<f32x4*>(o + j) = v4;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < SP_COLS; ++j)
+      if (n0 + j < N) o[j] = acc[j];
+  }
+}
+
+// ---- long rows -------------------------------------------------------------------------------
+__global__ void find_long_rows_kernel(const int64_t* row_ptr, int64_t P, int64_t capacity, int32_t* list,
+                                      int32_t* count, int32_t list_cap) {
+  const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (row >= P) return;
+  if (min(row_ptr[row + 1], capacity) - row_ptr[row] > LONG_ROW) {
+    const int32_t i = atomicAdd(count, 1);
+    if (i < list_cap) list[i] = (int32_t)row;
+  }
+}
+
+__global__ void zero_i32_kernel(int32_t* p) { p[threadIdx.x] = 0; }
+
+// One workgroup per (long row, 128 columns): 16 column groups of 8 x 16 entry lanes; entry
+// lane l takes entries l, l+16, ...; the 16 partial sums are added in a fixed order.
+template <class DT>
+__global__ __launch_bounds__(256) void spmm_long_rows_kernel(const int64_t* row_ptr, const int32_t* col_idx,
+                                                             const float* val, int64_t capacity,
+                                                             const int32_t* list, const int32_t* count,
+                                                             int32_t list_cap, const void* D, int64_t N, float* R) {
+  __shared__ float part[16][16][8];
+  const int n_long = min(*count, list_cap);
+  if ((int)blockIdx.x >= n_long) return;
+  const int64_t row = list[blockIdx.x];
+  const int cg = threadIdx.x & 15, el = threadIdx.x >> 4;
+  const int64_t col = (int64_t)blockIdx.y * 128 + cg * 8;
+  const int valid = col < N ? (int)min((int64_t)8, N - col) : 0;
+  float acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+  const int64_t b = row_ptr[row], en = min(row_ptr[row + 1], capacity);
+  if (valid > 0) {
+    for (int64_t i = b + el; i < en; i += 16) {
+      const int32_t c = col_idx[i];
+      const float s = val[i];
+      float d[8];
+      load8g<DT>(D, (int64_t)c * N + col, valid, d);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = fmaf(s, d[e], acc[e]);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) part[el][cg][e] = acc[e];
+  __syncthreads();
+  if (el == 0 && valid > 0) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float sum = 0.0f;
+      for (int l = 0; l < 16; ++l) sum += part[l][cg][e];
+      if (e < valid) R[row * N + col + e] = sum;
+    }
+  }
+}
+
+// ---- CSR transpose (P x Q -> Q x P) -----------------------------------------------------------
+__global__ void fill_i32_kernel(int32_t* p, int64_t n, int32_t v) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// Column counts with a workgroup-private LDS histogram when the column range fits.
+constexpr int CNT_LDS = 16384;
+__global__ __launch_bounds__(256) void csr_count_cols_kernel(const int32_t* col_idx, const int64_t* nnz,
+                                                             int64_t capacity, int64_t Q, int32_t* cnt) {
+  __shared__ int32_t h[CNT_LDS];
+  const int64_t n = min((int64_t)*nnz, capacity);
+  const bool use_lds = Q <= CNT_LDS;
+  if (use_lds) {
+    for (int i = threadIdx.x; i < Q; i += 256) h[i] = 0;
+    __syncthreads();
+  }
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    if (use_lds) atomicAdd(&h[col_idx[i]], 1);
+    else atomicAdd(&cnt[col_idx[i]], 1);
+  }
+  if (use_lds) {
+    __syncthreads();
+    for (int i = threadIdx.x; i < Q; i += 256)
+      if (h[i]) atomicAdd(&cnt[i], h[i]);
+  }
+}
+
+// ptr[0] = 0, ptr[i+1] = sum cnt[0..i].  One workgroup.
+__global__ __launch_bounds__(1024) void scan_counts32_kernel(const int32_t* cnt, int64_t n, int64_t* ptr) {
+  __shared__ long long s[1024];
+  __shared__ long long carry;
+  if (threadIdx.x == 0) { carry = 0; ptr[0] = 0; }
+  __syncthreads();
+  for (int64_t base = 0; base < n; base += 1024) {
+    const int64_t i = base + threadIdx.x;
+    s[threadIdx.x] = i < n ? cnt[i] : 0;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+      long long add = threadIdx.x >= o ? s[threadIdx.x - o] : 0;
+      __syncthreads();
+      s[threadIdx.x] += add;
+      __syncthreads();
+    }
+    if (i < n) ptr[i + 1] = carry + s[threadIdx.x];
+    __syncthreads();
+    if (threadIdx.x == 1023) carry += s[1023];
+    __syncthreads();
+  }
+}
+
+// Unordered fill: entry (row, col) goes to some slot of column col's segment.
+__global__ __launch_bounds__(256) void csr_transpose_fill_kernel(const int64_t* row_ptr, const int32_t* col_idx,
+                                                                 const float* val, int64_t rows, int64_t capacity,
+                                                                 const int64_t* t_ptr, int32_t* cursor,
+                                                                 int32_t* u_idx, float* u_val) {
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const int64_t b = row_ptr[row], e = min(row_ptr[row + 1], capacity);
+  for (int64_t i = b + lane; i < e; i += 64) {
+    const int32_t c = col_idx[i];
+    const int64_t pos = t_ptr[c] + atomicAdd(&cursor[c], 1);
+    u_idx[pos] = (int32_t)row;
+    u_val[pos] = val[i];
+  }
+}
+
+// Order every segment by index (the indices inside a segment are distinct): an entry's final
+// slot is the number of smaller indices in its segment.  One thread per entry; the segment is
+// found by bisection on t_ptr.  Makes the transposed matrix, and so the sums over it,
+// independent of the order the atomics above happened to take.
+__global__ __launch_bounds__(256) void csr_rank_sort_kernel(const int64_t* t_ptr, int64_t Q, const int32_t* u_idx,
+                                                            const float* u_val, int32_t* t_idx, float* t_val) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t total = t_ptr[Q];
+  if (e >= total) return;
+  int64_t lo = 0, hi = Q;   // largest seg with t_ptr[seg] <= e
+  while (hi - lo > 1) {
+    const int64_t mid = (lo + hi) >> 1;
+    if (t_ptr[mid] <= e) lo = mid; else hi = mid;
+  }
+  const int64_t b = t_ptr[lo], en = t_ptr[lo + 1];
+  const int32_t key = u_idx[e];
+  int64_t rank = 0;
+  for (int64_t j = b; j < en; ++j) rank += u_idx[j] < key ? 1 : 0;
+  t_idx[b + rank] = key;
+  t_val[b + rank] = u_val[e];
+}
+
+}  // namespace
+
+// ---- launchers ---------------------------------------------------------------------------------
+int64_t fp4_spmm_long_list_cap(int64_t capacity) { return capacity / LONG_ROW + 2; }
+
+// scratch: int32 count[64 (only [0] used)] followed by int32 list[fp4_spmm_long_list_cap(capacity)]
+int fp4_launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val, int64_t capacity,
+                    int64_t P, int64_t Q, const void* D, int bf16, int64_t N, float* R, int32_t* scratch,
+                    hipStream_t s) {
+  if (P == 0 || N == 0) return FP4_OK;
+  const dim3 grid((unsigned)((P + SP_ROWS - 1) / SP_ROWS), (unsigned)((N + SP_COLS - 1) / SP_COLS));
+  if (bf16)
+    hipLaunchKernelGGL((spmm_tile_kernel<BF16>), grid, dim3(SP_ROWS), 0, s, row_ptr, col_idx, val, capacity, P, Q, D, N, R);
+  else
+    hipLaunchKernelGGL((spmm_tile_kernel<F32>), grid, dim3(SP_ROWS), 0, s, row_ptr, col_idx, val, capacity, P, Q, D, N, R);
+  if (Q > LONG_ROW && capacity > LONG_ROW) {   // otherwise no row can be long
+    int32_t* count = scratch;
+    int32_t* list = scratch + 64;
+    const int32_t list_cap = (int32_t)std::min<int64_t>(fp4_spmm_long_list_cap(capacity), P);
+    hipLaunchKernelGGL(zero_i32_kernel, dim3(1), dim3(64), 0, s, count);
+    hipLaunchKernelGGL(find_long_rows_kernel, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, row_ptr, P, capacity,
+                       list, count, list_cap);
+    const dim3 lgrid((unsigned)list_cap, (unsigned)((N + 127) / 128));
+    if (bf16)
+      hipLaunchKernelGGL((spmm_long_rows_kernel<BF16>), lgrid, dim3(256), 0, s, row_ptr, col_idx, val, capacity, list,
+                         count, list_cap, D, N, R);
+    else
+      hipLaunchKernelGGL((spmm_long_rows_kernel<F32>), lgrid, dim3(256), 0, s, row_ptr, col_idx, val, capacity, list,
+                         count, list_cap, D, N, R);
+  }
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
+
+// scratch: cnt[Q] + cursor[Q] int32; u_idx/u_val: unordered staging, capacity entries each
+int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, const float* val,
+                             const int64_t* nnz, int64_t P, int64_t Q, int64_t capacity, int64_t* t_ptr,
+                             int32_t* t_idx, float* t_val, int32_t* u_idx, float* u_val, int32_t* scratch,
+                             hipStream_t s) {
+  int32_t* cnt = scratch;
+  int32_t* cursor = scratch + Q;
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((2 * Q + 255) / 256)), dim3(256), 0, s, scratch, 2 * Q, 0);
+  const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((capacity + 4095) / 4096, 2048));
+  hipLaunchKernelGGL(csr_count_cols_kernel, dim3(grid), dim3(256), 0, s, col_idx, nnz, capacity, Q, cnt);
+  hipLaunchKernelGGL(scan_counts32_kernel, dim3(1), dim3(1024), 0, s, cnt, Q, t_ptr);
+  hipLaunchKernelGGL(csr_transpose_fill_kernel, dim3((unsigned)((P + 3) / 4)), dim3(256), 0, s, row_ptr, col_idx, val,
+                     P, capacity, t_ptr, cursor, u_idx, u_val);
+  if (capacity > 0)
+    hipLaunchKernelGGL(csr_rank_sort_kernel, dim3((unsigned)((capacity + 255) / 256)), dim3(256), 0, s, t_ptr, Q, u_idx,
+                       u_val, t_idx, t_val);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}

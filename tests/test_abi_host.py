@@ -44,7 +44,7 @@ def test_status_strings_and_queries(L):
     assert b.occ_capacity(16384, 4096, 0.999) == 2 * o.occ_tail_count(16384 * 4096, 0.999)
     assert b.occ_capacity(4, 4, 1.0) == 0
     assert b.occ_capacity(4, 4, 0.3) == -1
-    for op in range(5):
+    for op in range(6):
         assert b.workspace_bytes(op, 256, 512, 512, b.FP4_F32) > 0
     assert b.workspace_bytes(99, 256, 512, 512, b.FP4_F32) == 0
     # forward workspace holds at least both packed operands and the fp32 residual product

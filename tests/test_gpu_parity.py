@@ -207,6 +207,26 @@ def test_occ_with_ties_one_sided_and_constant(dtype):
     _check_occ(synth._finish(-x.abs(), dtype), dtype, 0.95)
 
 
+def test_residual_spmm_with_long_rows():
+    # rows far longer than the rest take the long-row path; short, empty and ragged ones the tiled path
+    g = torch.Generator().manual_seed(17)
+    P, Q, N = 1300, 5000, 200
+    dense = torch.zeros(P, Q)
+    mask = torch.rand(P, Q, generator=g) < 0.01
+    mask[3] = True                      # 5000 entries
+    mask[1000, ::2] = True              # 2500 entries
+    mask[7] = False                     # empty row
+    dense[mask] = torch.randn(int(mask.sum()), generator=g)
+    rows, cols = np.nonzero(dense.numpy())
+    row_ptr = np.zeros(P + 1, np.int64)
+    np.cumsum(np.bincount(rows, minlength=P), out=row_ptr[1:])
+    vals = dense.numpy()[rows, cols].astype(np.float32)
+    D = synth._finish(torch.randn(Q, N, generator=g), "bf16")
+    R = b.fp4_residual_spmm(torch.from_numpy(row_ptr).cuda(), torch.from_numpy(cols.astype(np.int32)).cuda(),
+                            torch.from_numpy(vals).cuda(), Q, dev(D, "bf16"))
+    assert_close(R, dense.numpy().astype(np.float64) @ D.numpy().astype(np.float64), "f32", "spmm long rows")
+
+
 def test_residual_spmm():
     g = torch.Generator().manual_seed(11)
     x = torch.randn(70, 96, generator=g)
@@ -248,6 +268,7 @@ LAYER_CASES = [
     ("rag", 288, 544, 1056, "bf16", 0.99),
     ("off", 96, 128, 96, "bf16", 1.0),
     ("tiny", 32, 32, 32, "f32", 0.9),
+    ("long", 2304, 64, 96, "bf16", 0.97),     # an outlier channel: a transposed residual row > 2048 entries
 ]
 
 
