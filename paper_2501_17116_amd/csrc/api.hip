@@ -14,19 +14,20 @@ int fp4_launch_gemm(const uint8_t* L, const float* gl, const uint8_t* Rt, const 
                     float dge_cap, hipStream_t stream);
 int fp4_launch_quantize_rows(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
                              uint8_t* codes, float* gamma, hipStream_t s);
+int fp4_launch_occ_count(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, const float* thr,
+                         int32_t* row_cnt, hipStream_t s);
 int fp4_launch_occ_rows(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, const float* thr,
                         uint8_t* codes, float* gamma, void* x_clamped, int32_t* tmp_col, float* tmp_val,
-                        int64_t* row_start, int32_t* row_cnt, unsigned long long* total, int64_t capacity,
-                        hipStream_t s);
+                        const int64_t* row_ptr, int64_t capacity, hipStream_t s);
 int fp4_launch_quantize_cols(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
                              const float* clamp_thr, uint8_t* codes_t, float* gamma, uint32_t* amax_scratch,
                              hipStream_t s);
 size_t fp4_select_scratch_bytes();
 int fp4_launch_thresholds(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, int64_t k,
                           float* thresholds, void* scratch, unsigned long long* total, hipStream_t s);
-int fp4_launch_csr_finalize(const int32_t* tmp_col, const float* tmp_val, const int64_t* row_start,
-                            const int32_t* row_cnt, int64_t rows, int64_t capacity, int64_t* row_ptr,
-                            int32_t* col_idx, float* val, int64_t* nnz, hipStream_t s);
+int fp4_launch_scan_rows(const int32_t* row_cnt, int64_t rows, int64_t* row_ptr, int64_t* nnz, hipStream_t s);
+int fp4_launch_csr_gather(const int32_t* tmp_col, const float* tmp_val, int64_t rows, int64_t capacity,
+                          const int64_t* row_ptr, int32_t* col_idx, float* val, hipStream_t s);
 int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, const float* val,
                              const int64_t* nnz, int64_t P, int64_t Q, int64_t capacity, int64_t* t_ptr,
                              int32_t* t_idx, float* t_val, int32_t* u_idx, float* u_val, int32_t* scratch,
@@ -193,11 +194,14 @@ extern "C" int occ_clamp_residual(const void* x, fp4_dtype dt, int64_t rows, int
   capacity = std::min(capacity, 2 * tail_count(rows * cols, 0.9));  // never beyond the temporaries
   int rc = fp4_launch_thresholds(x, dt == FP4_BF16, rows, cols, ld, k, thresholds, t.select, t.total, s);
   if (rc) return rc;
-  rc = fp4_launch_occ_rows(x, dt == FP4_BF16, rows, cols, ld, thresholds, codes, gamma, x_clamped, t.tmp_col,
-                           t.tmp_val, t.row_start, t.row_cnt, t.total, capacity, s);
+  rc = fp4_launch_occ_count(x, dt == FP4_BF16, rows, cols, ld, thresholds, t.row_cnt, s);
   if (rc) return rc;
-  return fp4_launch_csr_finalize(t.tmp_col, t.tmp_val, t.row_start, t.row_cnt, rows, capacity, row_ptr,
-                                 col_idx, val, nnz, s);
+  rc = fp4_launch_scan_rows(t.row_cnt, rows, row_ptr, nnz, s);
+  if (rc) return rc;
+  rc = fp4_launch_occ_rows(x, dt == FP4_BF16, rows, cols, ld, thresholds, codes, gamma, x_clamped, t.tmp_col,
+                           t.tmp_val, row_ptr, capacity, s);
+  if (rc) return rc;
+  return fp4_launch_csr_gather(t.tmp_col, t.tmp_val, rows, capacity, row_ptr, col_idx, val, s);
 }
 
 extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
@@ -230,11 +234,14 @@ extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_
     const int64_t cap = std::min(saved->capacity, 2 * tail_count(M * K, 0.9));  // never beyond the temporaries
     rc = fp4_launch_thresholds(A, bf16, M, K, K, k, saved->thresholds, w.occ.select, w.occ.total, s);
     if (rc) return rc;
-    rc = fp4_launch_occ_rows(A, bf16, M, K, K, saved->thresholds, w.qA, w.gA, nullptr, w.occ.tmp_col,
-                             w.occ.tmp_val, w.occ.row_start, w.occ.row_cnt, w.occ.total, cap, s);
+    rc = fp4_launch_occ_count(A, bf16, M, K, K, saved->thresholds, w.occ.row_cnt, s);
     if (rc) return rc;
-    rc = fp4_launch_csr_finalize(w.occ.tmp_col, w.occ.tmp_val, w.occ.row_start, w.occ.row_cnt, M, cap,
-                                 saved->row_ptr, saved->col_idx, saved->val, saved->nnz, s);
+    rc = fp4_launch_scan_rows(w.occ.row_cnt, M, saved->row_ptr, saved->nnz, s);
+    if (rc) return rc;
+    rc = fp4_launch_occ_rows(A, bf16, M, K, K, saved->thresholds, w.qA, w.gA, nullptr, w.occ.tmp_col,
+                             w.occ.tmp_val, saved->row_ptr, cap, s);
+    if (rc) return rc;
+    rc = fp4_launch_csr_gather(w.occ.tmp_col, w.occ.tmp_val, M, cap, saved->row_ptr, saved->col_idx, saved->val, s);
     if (rc) return rc;
     // Delta_A W with the unquantized W, fp32; lands where the GEMM epilogue picks it up
     float* R = bf16 ? w.R : reinterpret_cast<float*>(Y);

@@ -19,16 +19,6 @@ struct SelState {
   uint32_t pad[2];
 };
 
-template <class DT>
-FP4_D uint32_t load_key(const void* x, int64_t off) {
-  if constexpr (__is_same(DT, BF16)) {
-    uint32_t h = reinterpret_cast<const uint16_t*>(x)[off];
-    return f32_order_key(h << 16) >> 16;  // 16-bit key
-  } else {
-    return f32_order_key(reinterpret_cast<const uint32_t*>(x)[off]);
-  }
-}
-
 __global__ void sel_init_kernel(SelState* st, unsigned long long* hist, unsigned long long k,
                                 unsigned long long n, unsigned long long* total) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -43,33 +33,74 @@ __global__ void sel_init_kernel(SelState* st, unsigned long long* hist, unsigned
 
 // One digit pass: histogram of key digit (key >> shift) & (2^bits - 1) over the elements whose
 // higher bits equal the prefix found so far (first pass: all elements, one shared histogram).
+// The workgroup histogram is replicated (by lane) to thin out same-address LDS atomics: real
+// tensors put most of their mass in a few dozen exponent bins.
+template <class DT>
+FP4_D uint32_t key_of(uint32_t raw) {   // raw: bf16 bits (low 16) or fp32 bits
+  if constexpr (__is_same(DT, BF16)) return f32_order_key(raw << 16) >> 16;
+  else return f32_order_key(raw);
+}
+
 template <class DT>
 __global__ __launch_bounds__(256) void sel_hist_kernel(const void* x, int64_t rows, int64_t cols,
                                                        int64_t ld, int shift, int bits, int first,
                                                        const SelState* st, unsigned long long* hist) {
-  __shared__ uint32_t h[2][SEL_BINS];
-  for (int i = threadIdx.x; i < 2 * SEL_BINS; i += 256) (&h[0][0])[i] = 0;
+  __shared__ uint32_t h[8 * SEL_BINS];   // first pass: 8 replicas; later: 4 replicas x 2 targets
+  for (int i = threadIdx.x; i < 8 * SEL_BINS; i += 256) h[i] = 0;
   __syncthreads();
   const uint32_t mask = (1u << bits) - 1u;
   const uint32_t p0 = st->prefix[0], p1 = st->prefix[1];
   const int hs = shift + bits;
-  const int64_t n = rows * cols;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-    const int64_t r = i / cols, c = i - r * cols;
-    const uint32_t key = load_key<DT>(x, r * ld + c);
+  const int lane = threadIdx.x & 63;
+  uint32_t* const hrep = first ? &h[(lane & 7) * SEL_BINS] : &h[(lane & 3) * 2 * SEL_BINS];
+  auto visit = [&](uint32_t raw) {
+    const uint32_t key = key_of<DT>(raw);
     const uint32_t d = (key >> shift) & mask;
     if (first) {
-      atomicAdd(&h[0][d], 1u);
+      atomicAdd(&hrep[d], 1u);
     } else {
       const uint32_t hi_bits = hs >= 32 ? 0u : (key >> hs);
-      if (hi_bits == p0) atomicAdd(&h[0][d], 1u);
-      if (hi_bits == p1) atomicAdd(&h[1][d], 1u);
+      if (hi_bits == p0) atomicAdd(&hrep[d], 1u);
+      if (hi_bits == p1) atomicAdd(&hrep[SEL_BINS + d], 1u);
+    }
+  };
+  constexpr int EPV = __is_same(DT, BF16) ? 8 : 4;   // elements per 16-byte load
+  const bool flat = (ld == cols) && (cols % EPV) == 0;
+  if (flat) {
+    const int64_t nvec = rows * cols / EPV;
+    const u32x4* xv = reinterpret_cast<const u32x4*>(x);
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * 256) {
+      const u32x4 r = xv[i];
+      if constexpr (__is_same(DT, BF16)) {
+        visit(r.x & 0xffffu); visit(r.x >> 16); visit(r.y & 0xffffu); visit(r.y >> 16);
+        visit(r.z & 0xffffu); visit(r.z >> 16); visit(r.w & 0xffffu); visit(r.w >> 16);
+      } else {
+        visit(r.x); visit(r.y); visit(r.z); visit(r.w);
+      }
+    }
+  } else {
+    const int64_t n = rows * cols;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+      const int64_t r = i / cols, c = i - r * cols;
+      if constexpr (__is_same(DT, BF16)) visit(reinterpret_cast<const uint16_t*>(x)[r * ld + c]);
+      else visit(reinterpret_cast<const uint32_t*>(x)[r * ld + c]);
     }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < 2 * SEL_BINS; i += 256) {
-    uint32_t v = (&h[0][0])[i];
-    if (v) atomicAdd(&hist[i], (unsigned long long)v);
+  if (first) {
+    for (int i = threadIdx.x; i < SEL_BINS; i += 256) {
+      uint32_t v = 0;
+#pragma unroll
+      for (int r = 0; r < 8; ++r) v += h[r * SEL_BINS + i];
+      if (v) atomicAdd(&hist[i], (unsigned long long)v);
+    }
+  } else {
+    for (int i = threadIdx.x; i < 2 * SEL_BINS; i += 256) {
+      uint32_t v = 0;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) v += h[r * 2 * SEL_BINS + i];
+      if (v) atomicAdd(&hist[i], (unsigned long long)v);
+    }
   }
 }
 
@@ -143,24 +174,24 @@ __global__ __launch_bounds__(1024) void scan_counts_kernel(const int32_t* cnt, i
   if (threadIdx.x == 0 && total_out) *total_out = carry;
 }
 
-// One wave per row: move the row's temporary entries to their canonical place, ascending
-// column order (rank of a column among the row's columns; columns are distinct).
+// One wave per row: move the row's temporary entries to their canonical place (same segment
+// of the final arrays), ascending column order (rank of a column among the row's columns; columns are distinct).
 __global__ __launch_bounds__(256) void csr_gather_kernel(const int32_t* tmp_col, const float* tmp_val,
-                                                         const int64_t* row_start, const int32_t* row_cnt,
                                                          const int64_t* row_ptr, int64_t rows, int64_t capacity,
                                                          int32_t* col_idx, float* val) {
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (row >= rows) return;
-  const int L = row_cnt[row];
-  const int64_t src = row_start[row], dst = row_ptr[row];
-  if (src + L > capacity || dst + L > capacity) return;  // truncated output, nnz tells
+  const int64_t src = row_ptr[row];
+  const int64_t en = row_ptr[row + 1];
+  if (en > capacity) return;  // truncated output, nnz tells
+  const int L = (int)(en - src);
   for (int i = lane; i < L; i += 64) {
     const int32_t c = tmp_col[src + i];
     int rank = 0;
     for (int j = 0; j < L; ++j) rank += tmp_col[src + j] < c ? 1 : 0;
-    col_idx[dst + rank] = c;
-    val[dst + rank] = tmp_val[src + i];
+    col_idx[src + rank] = c;
+    val[src + rank] = tmp_val[src + i];
   }
 }
 
@@ -187,7 +218,7 @@ int fp4_launch_thresholds(const void* x, int bf16, int64_t rows, int64_t cols, i
   if (bf16) { digits[0] = 11; digits[1] = 5; nd = 2; }
   else { digits[0] = 11; digits[1] = 11; digits[2] = 10; nd = 3; }
   int shift = key_bits;
-  const unsigned grid = (unsigned)std::min<int64_t>((n + 256 * 16 - 1) / (256 * 16), 2048);
+  const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + 256 * 64 - 1) / (256 * 64), 1024));
   for (int p = 0; p < nd; ++p) {
     shift -= digits[p];
     if (bf16)
@@ -203,13 +234,16 @@ int fp4_launch_thresholds(const void* x, int bf16, int64_t rows, int64_t cols, i
   return FP4_OK;
 }
 
-int fp4_launch_csr_finalize(const int32_t* tmp_col, const float* tmp_val, const int64_t* row_start,
-                            const int32_t* row_cnt, int64_t rows, int64_t capacity, int64_t* row_ptr,
-                            int32_t* col_idx, float* val, int64_t* nnz, hipStream_t s) {
+int fp4_launch_scan_rows(const int32_t* row_cnt, int64_t rows, int64_t* row_ptr, int64_t* nnz, hipStream_t s) {
   hipLaunchKernelGGL(scan_counts_kernel, dim3(1), dim3(1024), 0, s, row_cnt, rows, row_ptr, nnz);
-  hipLaunchKernelGGL(csr_gather_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, tmp_col, tmp_val,
-                     row_start, row_cnt, row_ptr, rows, capacity, col_idx, val);
   FP4_CHECK_LAUNCH();
   return FP4_OK;
 }
 
+int fp4_launch_csr_gather(const int32_t* tmp_col, const float* tmp_val, int64_t rows, int64_t capacity,
+                          const int64_t* row_ptr, int32_t* col_idx, float* val, hipStream_t s) {
+  hipLaunchKernelGGL(csr_gather_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, tmp_col, tmp_val,
+                     row_ptr, rows, capacity, col_idx, val);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}

@@ -95,9 +95,9 @@ FP4_D void store_codes(uint8_t* dst, uint32_t w, int valid, bool word_ok) {
 // Row-wise: one scale per row.  TPR threads share a row (64: one wave, 256: the workgroup).
 // With NV > 0 a thread keeps its NV units in registers between the absmax pass and the
 // quantize pass (row read once); NV == 0 streams the row twice (second read served by L2).
-// With OCC the values are clamped to [lo, hi] first and the clamped-away part is appended,
-// in a deterministic but not column-sorted order, to a per-row segment of a temporary
-// entry list whose start and length are recorded per row.
+// With OCC the values are clamped to [lo, hi] first and the clamped-away part is written, in a
+// deterministic but not column-sorted order, to the row's segment of a temporary entry list
+// (segment starts come from a counting pass, so no atomics are needed here).
 // ------------------------------------------------------------------------------------------
 struct RowArgs {
   const void* x;
@@ -107,9 +107,7 @@ struct RowArgs {
   const float* thr;      // {lo, hi} (OCC)
   int32_t* tmp_col;      // OCC: temporary entries
   float* tmp_val;
-  int64_t* row_start;    // OCC: [rows]
-  int32_t* row_cnt;      // OCC: [rows]
-  unsigned long long* total;  // OCC: running entry count
+  const int64_t* row_ptr;  // OCC: [rows + 1] first entry slot of every row (counted beforehand)
   int64_t rows, cols, ld, capacity;
 };
 
@@ -119,7 +117,6 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
   constexpr bool CACHED = NV > 0;
   __shared__ float s_max[4];
   __shared__ int s_cnt[4];
-  __shared__ long long s_base;
 
   const int tid = threadIdx.x;
   const int t = tid % TPR;
@@ -213,23 +210,9 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
       row_total = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
       for (int w = 0; w < wave; ++w) excl += s_cnt[w];
     }
-    long long base = 0;
-    if (TPR == 256) {
-      if (tid == 0) {
-        s_base = row_total ? (long long)atomicAdd(a.total, (unsigned long long)row_total) : 0;
-      }
-      __syncthreads();
-      base = s_base;
-    } else {
-      if (lane == 0 && row_ok)
-        base = row_total ? (long long)atomicAdd(a.total, (unsigned long long)row_total) : 0;
-      base = __shfl(base, 0, 64);
-    }
-    if (row_ok && t == 0) {
-      a.row_start[row] = base;
-      a.row_cnt[row] = row_total;
-    }
-    emit = row_ok && (base + row_total <= a.capacity);
+    (void)row_total;
+    const long long base = row_ok ? a.row_ptr[row] : 0;
+    emit = row_ok && (a.row_ptr[row + 1] <= a.capacity);
     wr = base + excl;
   }
 
@@ -274,6 +257,28 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
       finish(u, v, valid);
     }
   }
+}
+
+// Entries each row will contribute to the residual: elements outside [lo, hi].  One wave per row.
+template <class DT>
+__global__ __launch_bounds__(256) void occ_count_rows_kernel(const void* x, int64_t rows, int64_t cols, int64_t ld,
+                                                             const float* thr, int32_t* row_cnt) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const float lo = thr[0], hi = thr[1];
+  const int64_t nunits = (cols + 7) / 8;
+  int cnt = 0;
+  for (int64_t u = lane; u < nunits; u += 64) {
+    const int valid = (int)min((int64_t)8, cols - u * 8);
+    float v[8];
+    load8<DT>(x, row * ld + u * 8, valid, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) cnt += (e < valid && ((v[e] < lo) | (v[e] > hi))) ? 1 : 0;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 64);
+  if (lane == 0) row_cnt[row] = cnt;
 }
 
 template <class DT, bool OCC>
@@ -475,15 +480,25 @@ int fp4_launch_quantize_rows(const void* x, int bf16, int64_t rows, int64_t cols
   return bf16 ? launch_rows<BF16, false>(a, s) : launch_rows<F32, false>(a, s);
 }
 
+int fp4_launch_occ_count(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, const float* thr,
+                         int32_t* row_cnt, hipStream_t s) {
+  if (rows == 0) return FP4_OK;
+  const dim3 grid((unsigned)((rows + 3) / 4));
+  if (bf16) hipLaunchKernelGGL((occ_count_rows_kernel<BF16>), grid, dim3(256), 0, s, x, rows, cols, ld, thr, row_cnt);
+  else hipLaunchKernelGGL((occ_count_rows_kernel<F32>), grid, dim3(256), 0, s, x, rows, cols, ld, thr, row_cnt);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
+
 int fp4_launch_occ_rows(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
                         const float* thr, uint8_t* codes, float* gamma, void* x_clamped,
-                        int32_t* tmp_col, float* tmp_val, int64_t* row_start, int32_t* row_cnt,
-                        unsigned long long* total, int64_t capacity, hipStream_t s) {
+                        int32_t* tmp_col, float* tmp_val, const int64_t* row_ptr, int64_t capacity,
+                        hipStream_t s) {
   if (rows == 0 || cols == 0) return FP4_OK;
   RowArgs a = {};
   a.x = x; a.codes = codes; a.gamma = gamma; a.x_clamped = x_clamped; a.thr = thr;
-  a.tmp_col = tmp_col; a.tmp_val = tmp_val; a.row_start = row_start; a.row_cnt = row_cnt;
-  a.total = total; a.rows = rows; a.cols = cols; a.ld = ld; a.capacity = capacity;
+  a.tmp_col = tmp_col; a.tmp_val = tmp_val; a.row_ptr = row_ptr;
+  a.rows = rows; a.cols = cols; a.ld = ld; a.capacity = capacity;
   return bf16 ? launch_rows<BF16, true>(a, s) : launch_rows<F32, true>(a, s);
 }
 

@@ -24,6 +24,7 @@ namespace {
 
 struct BF16 {};
 struct F32 {};
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int SP_ROWS = 1024;   // output rows per workgroup = threads
 constexpr int SP_COLS = 64;     // output columns per workgroup
@@ -86,8 +87,28 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
   const int64_t s_col = n0 + s_unit * 8;
   const int s_valid = s_col < N ? (int)min((int64_t)8, N - s_col) : 0;
 
-  int32_t c_next = cur < end ? col_idx[cur] : 0x7fffffff;
-  float v_next = cur < end ? val[cur] : 0.0f;
+  // The row's entries are fetched four at a time (one 16-byte request per array instead of
+  // four 4-byte ones: every lane walks a different row, so requests, not bytes, are what the
+  // cache path runs out of).  A quad may run past the row's end; what lies there is ignored.
+  const int64_t limit = min(row_ptr[P], capacity);   // entries that exist
+  int64_t qb = cur;
+  int32_t cq[4] = {0x7fffffff, 0x7fffffff, 0x7fffffff, 0x7fffffff};
+  float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+  auto load_quad = [&]() {
+    if (qb + 4 <= limit) {
+      const i32x4 c4 = *reinterpret_cast<const i32x4*>(col_idx + qb);   // dword-aligned 16-byte loads
+      const f32x4 v4 = *reinterpret_cast<const f32x4*>(val + qb);
+      cq[0] = c4.x; cq[1] = c4.y; cq[2] = c4.z; cq[3] = c4.w;
+      vq[0] = v4.x; vq[1] = v4.y; vq[2] = v4.z; vq[3] = v4.w;
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        cq[i] = qb + i < limit ? col_idx[qb + i] : 0x7fffffff;
+        vq[i] = qb + i < limit ? val[qb + i] : 0.0f;
+      }
+    }
+  };
+  if (cur < end) load_quad();
 
   for (int64_t k0 = 0; k0 < Q; k0 += SP_KS) {
     __syncthreads();
@@ -106,12 +127,13 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
     }
     __syncthreads();
     const int32_t k_end = (int32_t)min(k0 + SP_KS, Q);
-    while (c_next < k_end) {
-      const int32_t c = c_next;
-      const float v = v_next;
+    while (cur < end) {
+      if (cur >= qb + 4) { qb = cur; load_quad(); }
+      const int sel = (int)(cur - qb);
+      const int32_t c = sel == 0 ? cq[0] : sel == 1 ? cq[1] : sel == 2 ? cq[2] : cq[3];
+      if (c >= k_end) break;
+      const float v = sel == 0 ? vq[0] : sel == 1 ? vq[1] : sel == 2 ? vq[2] : vq[3];
       ++cur;
-      c_next = cur < end ? col_idx[cur] : 0x7fffffff;   // fetched under the FMAs below
-      v_next = cur < end ? val[cur] : 0.0f;
       const float* dr = &slab[(c - (int32_t)k0) * SP_LD];
 #pragma unroll
       for (int j = 0; j < SP_COLS; j += 4) {
@@ -153,44 +175,45 @@ __global__ void find_long_rows_kernel(const int64_t* row_ptr, int64_t P, int64_t
 
 __global__ void zero_i32_kernel(int32_t* p) { p[threadIdx.x] = 0; }
 
-// One workgroup per (long row, 128 columns): 16 column groups of 8 x 16 entry lanes; entry
-// lane l takes entries l, l+16, ...; the 16 partial sums are added in a fixed order.
+// One workgroup per (long row, 32 columns): 4 column groups of 8 x 64 entry lanes; entry lane l
+// takes entries l, l+64, ...; the 64 partial sums are added in a fixed order.
 template <class DT>
 __global__ __launch_bounds__(256) void spmm_long_rows_kernel(const int64_t* row_ptr, const int32_t* col_idx,
                                                              const float* val, int64_t capacity,
                                                              const int32_t* list, const int32_t* count,
                                                              int32_t list_cap, const void* D, int64_t N, float* R) {
-  __shared__ float part[16][16][8];
+  __shared__ float part[64][4][8];
   const int n_long = min(*count, list_cap);
-  if ((int)blockIdx.x >= n_long) return;
-  const int64_t row = list[blockIdx.x];
-  const int cg = threadIdx.x & 15, el = threadIdx.x >> 4;
-  const int64_t col = (int64_t)blockIdx.y * 128 + cg * 8;
+  const int cg = threadIdx.x & 3, el = threadIdx.x >> 2;
+  const int64_t col = (int64_t)blockIdx.y * 32 + cg * 8;
   const int valid = col < N ? (int)min((int64_t)8, N - col) : 0;
-  float acc[8];
+  for (int li = blockIdx.x; li < n_long; li += gridDim.x) {
+    const int64_t row = list[li];
+    float acc[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
-  const int64_t b = row_ptr[row], en = min(row_ptr[row + 1], capacity);
-  if (valid > 0) {
-    for (int64_t i = b + el; i < en; i += 16) {
-      const int32_t c = col_idx[i];
-      const float s = val[i];
-      float d[8];
-      load8g<DT>(D, (int64_t)c * N + col, valid, d);
+    for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+    const int64_t b = row_ptr[row], en = min(row_ptr[row + 1], capacity);
+    if (valid > 0) {
+      for (int64_t i = b + el; i < en; i += 64) {
+        const int32_t c = col_idx[i];
+        const float s = val[i];
+        float d[8];
+        load8g<DT>(D, (int64_t)c * N + col, valid, d);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] = fmaf(s, d[e], acc[e]);
+        for (int e = 0; e < 8; ++e) acc[e] = fmaf(s, d[e], acc[e]);
+      }
     }
-  }
 #pragma unroll
-  for (int e = 0; e < 8; ++e) part[el][cg][e] = acc[e];
-  __syncthreads();
-  if (el == 0 && valid > 0) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
+    for (int e = 0; e < 8; ++e) part[el][cg][e] = acc[e];
+    __syncthreads();
+    if (threadIdx.x < 32) {
+      const int g = threadIdx.x >> 3, e = threadIdx.x & 7;
       float sum = 0.0f;
-      for (int l = 0; l < 16; ++l) sum += part[l][cg][e];
-      if (e < valid) R[row * N + col + e] = sum;
+      for (int l = 0; l < 64; ++l) sum += part[l][g][e];
+      const int64_t c1 = (int64_t)blockIdx.y * 32 + g * 8 + e;
+      if (c1 < N) R[row * N + c1] = sum;
     }
+    __syncthreads();
   }
 }
 
@@ -284,6 +307,55 @@ __global__ __launch_bounds__(256) void csr_rank_sort_kernel(const int64_t* t_ptr
   t_val[b + rank] = u_val[e];
 }
 
+// Same ordering, linear time, for matrices whose index range fits an LDS bitmap: one workgroup
+// per segment marks the indices present, prefix-counts the bitmap words, and an entry's slot is
+// the number of marked indices below its own.
+constexpr int BM_WORDS = 15872;   // bitmap words that fit 64 KiB of LDS with the block sums: indices below 507904
+__global__ __launch_bounds__(256) void csr_bitmap_sort_kernel(const int64_t* t_ptr, int64_t P, const int32_t* u_idx,
+                                                              const float* u_val, int32_t* t_idx, float* t_val) {
+  extern __shared__ uint32_t bm_lds[];
+  const int nwords = (int)((P + 31) / 32);
+  const int nblk = (nwords + 63) / 64;
+  uint32_t* const bits = bm_lds;            // [nwords]
+  uint32_t* const pre = bm_lds + nwords;    // [nblk] exclusive count before every 64-word block
+  const int64_t seg = blockIdx.x;
+  const int64_t b = t_ptr[seg], en = t_ptr[seg + 1];
+  const int L = (int)(en - b);
+  if (L == 0) return;
+  if (L == 1) {
+    if (threadIdx.x == 0) { t_idx[b] = u_idx[b]; t_val[b] = u_val[b]; }
+    return;
+  }
+  for (int i = threadIdx.x; i < nwords; i += 256) bits[i] = 0;
+  __syncthreads();
+  for (int i = threadIdx.x; i < L; i += 256) {
+    const uint32_t k = (uint32_t)u_idx[b + i];
+    atomicOr(&bits[k >> 5], 1u << (k & 31));
+  }
+  __syncthreads();
+  // block sums (64 words per block), then a serial-in-LDS exclusive scan over <= 512 blocks
+  for (int blk = threadIdx.x; blk < nblk; blk += 256) {
+    uint32_t c = 0;
+    for (int w = blk * 64; w < min(nwords, blk * 64 + 64); ++w) c += __popc(bits[w]);
+    pre[blk] = c;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t run = 0;
+    for (int blk = 0; blk < nblk; ++blk) { const uint32_t c = pre[blk]; pre[blk] = run; run += c; }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < L; i += 256) {
+    const uint32_t k = (uint32_t)u_idx[b + i];
+    const int w = (int)(k >> 5);
+    uint32_t rank = pre[w >> 6];
+    for (int j = (w & ~63); j < w; ++j) rank += __popc(bits[j]);
+    rank += __popc(bits[w] & ((1u << (k & 31)) - 1u));
+    t_idx[b + rank] = (int32_t)k;
+    t_val[b + rank] = u_val[b + i];
+  }
+}
+
 }  // namespace
 
 // ---- launchers ---------------------------------------------------------------------------------
@@ -306,7 +378,7 @@ int fp4_launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float*
     hipLaunchKernelGGL(zero_i32_kernel, dim3(1), dim3(64), 0, s, count);
     hipLaunchKernelGGL(find_long_rows_kernel, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, row_ptr, P, capacity,
                        list, count, list_cap);
-    const dim3 lgrid((unsigned)list_cap, (unsigned)((N + 127) / 128));
+    const dim3 lgrid((unsigned)std::min<int32_t>(list_cap, 8), (unsigned)((N + 31) / 32));
     if (bf16)
       hipLaunchKernelGGL((spmm_long_rows_kernel<BF16>), lgrid, dim3(256), 0, s, row_ptr, col_idx, val, capacity, list,
                          count, list_cap, D, N, R);
@@ -331,7 +403,10 @@ int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, con
   hipLaunchKernelGGL(scan_counts32_kernel, dim3(1), dim3(1024), 0, s, cnt, Q, t_ptr);
   hipLaunchKernelGGL(csr_transpose_fill_kernel, dim3((unsigned)((P + 3) / 4)), dim3(256), 0, s, row_ptr, col_idx, val,
                      P, capacity, t_ptr, cursor, u_idx, u_val);
-  if (capacity > 0)
+  if (capacity > 0 && P <= (int64_t)BM_WORDS * 32)
+    hipLaunchKernelGGL(csr_bitmap_sort_kernel, dim3((unsigned)Q), dim3(256),
+                       (size_t)(((P + 31) / 32) + ((P + 31) / 32 + 63) / 64) * 4, s, t_ptr, P, u_idx, u_val, t_idx, t_val);
+  else if (capacity > 0)
     hipLaunchKernelGGL(csr_rank_sort_kernel, dim3((unsigned)((capacity + 255) / 256)), dim3(256), 0, s, t_ptr, Q, u_idx,
                        u_val, t_idx, t_val);
   FP4_CHECK_LAUNCH();
