@@ -33,6 +33,8 @@ int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, con
                              int32_t* t_idx, float* t_val, int32_t* u_idx, float* u_val, int32_t* scratch,
                              hipStream_t s);
 int64_t fp4_spmm_long_list_cap(int64_t capacity);
+int fp4_launch_order_rows(const int64_t* row_ptr, int64_t rows, int64_t nidx, int64_t capacity,
+                          const int32_t* u_idx, const float* u_val, int32_t* idx, float* val, hipStream_t s);
 int fp4_launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val, int64_t capacity,
                     int64_t P, int64_t Q, const void* D, int bf16, int64_t N, float* R, int32_t* scratch,
                     hipStream_t s);
@@ -201,7 +203,9 @@ extern "C" int occ_clamp_residual(const void* x, fp4_dtype dt, int64_t rows, int
   rc = fp4_launch_occ_rows(x, dt == FP4_BF16, rows, cols, ld, thresholds, codes, gamma, x_clamped, t.tmp_col,
                            t.tmp_val, row_ptr, capacity, s);
   if (rc) return rc;
-  return fp4_launch_csr_gather(t.tmp_col, t.tmp_val, rows, capacity, row_ptr, col_idx, val, s);
+  rc = fp4_launch_order_rows(row_ptr, rows, cols, capacity, t.tmp_col, t.tmp_val, col_idx, val, s);
+  if (rc == 1) rc = fp4_launch_csr_gather(t.tmp_col, t.tmp_val, rows, capacity, row_ptr, col_idx, val, s);
+  return rc;
 }
 
 extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
@@ -241,7 +245,9 @@ extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_
     rc = fp4_launch_occ_rows(A, bf16, M, K, K, saved->thresholds, w.qA, w.gA, nullptr, w.occ.tmp_col,
                              w.occ.tmp_val, saved->row_ptr, cap, s);
     if (rc) return rc;
-    rc = fp4_launch_csr_gather(w.occ.tmp_col, w.occ.tmp_val, M, cap, saved->row_ptr, saved->col_idx, saved->val, s);
+    rc = fp4_launch_order_rows(saved->row_ptr, M, K, cap, w.occ.tmp_col, w.occ.tmp_val, saved->col_idx, saved->val, s);
+    if (rc == 1)
+      rc = fp4_launch_csr_gather(w.occ.tmp_col, w.occ.tmp_val, M, cap, saved->row_ptr, saved->col_idx, saved->val, s);
     if (rc) return rc;
     // Delta_A W with the unquantized W, fp32; lands where the GEMM epilogue picks it up
     float* R = bf16 ? w.R : reinterpret_cast<float*>(Y);

@@ -307,19 +307,21 @@ __global__ __launch_bounds__(256) void csr_rank_sort_kernel(const int64_t* t_ptr
   t_val[b + rank] = u_val[e];
 }
 
-// Same ordering, linear time, for matrices whose index range fits an LDS bitmap: one workgroup
-// per segment marks the indices present, prefix-counts the bitmap words, and an entry's slot is
-// the number of marked indices below its own.
-constexpr int BM_WORDS = 15872;   // bitmap words that fit 64 KiB of LDS with the block sums: indices below 507904
-__global__ __launch_bounds__(256) void csr_bitmap_sort_kernel(const int64_t* t_ptr, int64_t P, const int32_t* u_idx,
-                                                              const float* u_val, int32_t* t_idx, float* t_val) {
+// Same ordering in linear time when the index range fits an LDS bitmap: one workgroup per
+// segment marks the indices present, turns the bitmap's word counts into an exclusive prefix,
+// and an entry's slot is the number of marked indices below its own.
+constexpr int BM_WORDS = 8000;   // bitmap words (plus as many prefix words) within 64 KiB of LDS: indices < 256000
+__global__ __launch_bounds__(256) void csr_bitmap_sort_kernel(const int64_t* seg_ptr, int64_t nidx, int64_t capacity,
+                                                              const int32_t* u_idx, const float* u_val,
+                                                              int32_t* t_idx, float* t_val) {
   extern __shared__ uint32_t bm_lds[];
-  const int nwords = (int)((P + 31) / 32);
-  const int nblk = (nwords + 63) / 64;
+  __shared__ uint32_t blk_sum[256];
+  const int nwords = (int)((nidx + 31) / 32);
   uint32_t* const bits = bm_lds;            // [nwords]
-  uint32_t* const pre = bm_lds + nwords;    // [nblk] exclusive count before every 64-word block
+  uint32_t* const pre = bm_lds + nwords;    // [nwords] marked indices before each word
   const int64_t seg = blockIdx.x;
-  const int64_t b = t_ptr[seg], en = t_ptr[seg + 1];
+  const int64_t b = seg_ptr[seg], en = seg_ptr[seg + 1];
+  if (en > capacity) return;                // truncated output
   const int L = (int)(en - b);
   if (L == 0) return;
   if (L == 1) {
@@ -333,24 +335,25 @@ __global__ __launch_bounds__(256) void csr_bitmap_sort_kernel(const int64_t* t_p
     atomicOr(&bits[k >> 5], 1u << (k & 31));
   }
   __syncthreads();
-  // block sums (64 words per block), then a serial-in-LDS exclusive scan over <= 512 blocks
-  for (int blk = threadIdx.x; blk < nblk; blk += 256) {
-    uint32_t c = 0;
-    for (int w = blk * 64; w < min(nwords, blk * 64 + 64); ++w) c += __popc(bits[w]);
-    pre[blk] = c;
-  }
+  // exclusive prefix over words: each thread scans a contiguous run, then the runs are offset
+  const int per = (nwords + 255) / 256;
+  const int w0 = threadIdx.x * per, w1 = min(nwords, w0 + per);
+  uint32_t run = 0;
+  for (int w = w0; w < w1; ++w) { pre[w] = run; run += __popc(bits[w]); }
+  blk_sum[threadIdx.x] = run;
   __syncthreads();
   if (threadIdx.x == 0) {
-    uint32_t run = 0;
-    for (int blk = 0; blk < nblk; ++blk) { const uint32_t c = pre[blk]; pre[blk] = run; run += c; }
+    uint32_t acc = 0;
+    for (int t = 0; t < 256; ++t) { const uint32_t c = blk_sum[t]; blk_sum[t] = acc; acc += c; }
   }
+  __syncthreads();
+  const uint32_t off = blk_sum[threadIdx.x];
+  for (int w = w0; w < w1; ++w) pre[w] += off;
   __syncthreads();
   for (int i = threadIdx.x; i < L; i += 256) {
     const uint32_t k = (uint32_t)u_idx[b + i];
     const int w = (int)(k >> 5);
-    uint32_t rank = pre[w >> 6];
-    for (int j = (w & ~63); j < w; ++j) rank += __popc(bits[j]);
-    rank += __popc(bits[w] & ((1u << (k & 31)) - 1u));
+    const uint32_t rank = pre[w] + __popc(bits[w] & ((1u << (k & 31)) - 1u));
     t_idx[b + rank] = (int32_t)k;
     t_val[b + rank] = u_val[b + i];
   }
@@ -404,11 +407,24 @@ int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, con
   hipLaunchKernelGGL(csr_transpose_fill_kernel, dim3((unsigned)((P + 3) / 4)), dim3(256), 0, s, row_ptr, col_idx, val,
                      P, capacity, t_ptr, cursor, u_idx, u_val);
   if (capacity > 0 && P <= (int64_t)BM_WORDS * 32)
-    hipLaunchKernelGGL(csr_bitmap_sort_kernel, dim3((unsigned)Q), dim3(256),
-                       (size_t)(((P + 31) / 32) + ((P + 31) / 32 + 63) / 64) * 4, s, t_ptr, P, u_idx, u_val, t_idx, t_val);
+    hipLaunchKernelGGL(csr_bitmap_sort_kernel, dim3((unsigned)Q), dim3(256), (size_t)((P + 31) / 32) * 8, s, t_ptr, P,
+                       capacity, u_idx, u_val, t_idx, t_val);
   else if (capacity > 0)
     hipLaunchKernelGGL(csr_rank_sort_kernel, dim3((unsigned)((capacity + 255) / 256)), dim3(256), 0, s, t_ptr, Q, u_idx,
                        u_val, t_idx, t_val);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
+
+// Rows of a CSR matrix whose entries sit, unordered, in (u_idx, u_val): write them ordered by
+// index to (idx, val).  nidx = number of columns.  Returns 1 if the index range is too large
+// for the LDS bitmap (the caller then uses its own fallback).
+int fp4_launch_order_rows(const int64_t* row_ptr, int64_t rows, int64_t nidx, int64_t capacity,
+                          const int32_t* u_idx, const float* u_val, int32_t* idx, float* val, hipStream_t s) {
+  if (nidx > (int64_t)BM_WORDS * 32) return 1;
+  if (rows == 0) return FP4_OK;
+  hipLaunchKernelGGL(csr_bitmap_sort_kernel, dim3((unsigned)rows), dim3(256), (size_t)((nidx + 31) / 32) * 8, s, row_ptr,
+                     nidx, capacity, u_idx, u_val, idx, val);
   FP4_CHECK_LAUNCH();
   return FP4_OK;
 }

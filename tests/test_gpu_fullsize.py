@@ -1,0 +1,89 @@
+"""GPU parity at benchmark size: one LLaMA-7B-shaped layer (16384 tokens, 4096 -> 4096, bf16
+masters, OCC alpha = 0.99, DGE k = 5) in the launch configuration bench.py times, checked on
+sampled outputs the oracle can compute one by one.  Thresholds, scales, the residual count and
+the sampled rows' codes / CSR entries are bit-exact; sampled Y, dA, dW rows within tolerance."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fp4_oracle as o
+from paper_2501_17116_amd import binding as b
+from paper_2501_17116_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+RTOL, FLOOR = 1e-3, 2e-6
+
+
+def _close(got, ref, bf16, scale):
+    g = got.astype(np.float64)
+    ref = ref.astype(np.float64)
+    tol = RTOL * np.abs(ref) + FLOOR * scale
+    if bf16:
+        tol = tol + 2.0 ** -8 * np.abs(ref)
+    bad = np.abs(g - ref) > tol
+    assert not bad.any(), (int(bad.sum()), g[bad][:3], ref[bad][:3])
+
+
+@pytest.fixture(scope="module")
+def layer():
+    cfg = synth.CONFIGS["c3"]
+    shape = [l for l in cfg.layers if l.name == "o"][0]
+    A, W, dY = synth.make_layer(cfg, shape)
+    return cfg, shape, A, W, dY
+
+
+def test_full_size_layer_sampled(layer):
+    cfg, shape, A, W, dY = layer
+    M, K, N = shape.M, shape.K, shape.N
+    Ad, Wd, dYd = (t.to(torch.bfloat16).cuda() for t in (A, W, dY))
+    An, Wn, dYn = A.numpy(), W.numpy(), dY.numpy()
+    rows = np.array([0, 1, 255, 256, 4097, 8191, 12345, M - 1])
+    chans = np.array([0, 31, 32, 1000, 2047, K - 1] + synth.outlier_channels(cfg.idx, K, cfg.outlier_frac).tolist()[:2])
+
+    # ---- OCC on the full activation tensor
+    occ = b.occ_clamp_residual(Ad, cfg.alpha, want_codes=True)
+    lo, hi = o.occ_thresholds(An, cfg.alpha)
+    thr = occ["thresholds"].cpu().numpy()
+    assert thr[0] == lo and thr[1] == hi
+    xc_s, csr_s = o.occ_clamp_residual(An[rows], lo, hi)
+    k = o.occ_tail_count(M * K, cfg.alpha)
+    nnz = int(occ["nnz"].item())
+    assert nnz == int(((An < lo) | (An > hi)).sum()) <= 2 * k
+    rp = occ["row_ptr"].cpu().numpy()
+    ci = occ["col_idx"].cpu().numpy()
+    cv = occ["val"].cpu().numpy()
+    assert rp[0] == 0 and rp[-1] == nnz and np.all(np.diff(rp) >= 0)
+    for si, r in enumerate(rows):
+        a, e = rp[r], rp[r + 1]
+        sa, se = csr_s.row_ptr[si], csr_s.row_ptr[si + 1]
+        assert np.array_equal(ci[a:e], csr_s.col_idx[sa:se])
+        assert np.array_equal(cv[a:e].view(np.uint32), csr_s.val[sa:se].view(np.uint32))
+    rc, rg = o.quantize_rows(xc_s)
+    assert np.array_equal(occ["gamma"].cpu().numpy()[rows].view(np.uint32), rg.view(np.uint32))
+    assert np.array_equal(o.unpack_codes(occ["codes"].cpu().numpy()[rows]), rc)
+
+    # ---- forward
+    Y, ctx = b.fp4_linear_fwd(Ad, Wd, cfg.alpha)
+    Yref, st = o.fp4_linear_fwd(An, Wn, cfg.alpha, "f32", rows=rows)
+    assert np.array_equal(ctx.gamma_W.cpu().numpy().view(np.uint32), st.gamma_w.view(np.uint32))
+    assert int(ctx.nnz.item()) == nnz
+    scale = float(np.abs(Yref).max())
+    _close(Y.float().cpu().numpy()[rows], Yref, True, scale)
+
+    # ---- activation gradient
+    dA = b.fp4_linear_bwd_dgrad(dYd, Wd)
+    dAref = o.fp4_linear_bwd_dgrad(dYn, Wn, "f32", rows=rows)
+    _close(dA.float().cpu().numpy()[rows], dAref, True, float(np.abs(dAref).max()))
+
+    # ---- weight gradient with DGE (sampled input channels, outlier channels included)
+    dW = b.fp4_linear_bwd_wgrad(Ad, dYd, Wd, ctx, cfg.dge_k, cfg.dge_cap)
+    dWref = o.fp4_linear_bwd_wgrad(An, dYn, Wn, cfg.alpha, cfg.dge_k, cfg.dge_cap, rows=chans)
+    _close(dW.cpu().numpy()[chans], dWref, False, float(np.abs(dWref).max()))
+
+    # ---- properties that hold at any size
+    assert torch.isfinite(Y.float()).all() and torch.isfinite(dW).all()
+    codes, gamma = b.fp4_quantize(Wd, b.FP4_AXIS_COL)
+    un = b.fp4_unpack(codes)
+    assert int((un == 8).sum().item()) == 0                         # -0 is never emitted
+    assert bool(((un & 7) == 7).any(dim=1).all().item())            # every channel reaches magnitude 6
