@@ -81,6 +81,55 @@ def cpu_baseline(cfg):
                       (l.name, l.K, l.N, Ms, l.M, dt)}
 
 
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E (published)
+
+
+def _time(fn, torch, n=10, warm=2):
+    for _ in range(warm):
+        fn()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(n):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / n * 1e-3
+
+
+def kernel_report(cfg, L, b, torch, ws):
+    """Stand-alone rates of the bandwidth-bound entry points on the workload's first layer:
+    algorithmic bytes (what the operation must read and write once) / time."""
+    l = L["shape"]
+    eb = 2 if cfg.dtype == "bf16" else 4
+    rep = {}
+
+    def add(name, fn, nbytes):
+        t = _time(fn, torch)
+        rep[name] = {"GB/s": nbytes / t / 1e9, "frac_of_hbm_peak": nbytes / t / 1e9 / HBM_PEAK_GBS, "us": t * 1e6}
+
+    MK, KN, MN = l.M * l.K, l.K * l.N, l.M * l.N
+    add("quantize_rows(dY)", lambda: b.fp4_quantize(L["dY"], b.FP4_AXIS_ROW, ws=ws), MN * (eb + 0.5) + 4 * l.M)
+    add("quantize_rows(A)", lambda: b.fp4_quantize(L["A"], b.FP4_AXIS_ROW, ws=ws), MK * (eb + 0.5) + 4 * l.M)
+    # a column scale spans all rows: the tensor has to be read twice
+    add("quantize_cols(W)", lambda: b.fp4_quantize(L["W"], b.FP4_AXIS_COL, ws=ws), KN * (2 * eb + 0.5) + 4 * l.N)
+    add("quantize_cols(dY)", lambda: b.fp4_quantize(L["dY"], b.FP4_AXIS_COL, ws=ws), MN * (2 * eb + 0.5) + 4 * l.N)
+    # OCC: thresholds cannot be applied in the pass that finds them: two reads, codes, CSR entries
+    dens = 2 * (1 - cfg.alpha)
+    add("occ_clamp_residual(A)", lambda: b.occ_clamp_residual(L["A"], cfg.alpha, ws=ws),
+        MK * (2 * eb + 0.5 + 8 * dens) + 12 * l.M)
+    G = torch.empty(l.K, l.N, device="cuda", dtype=torch.float32).normal_()
+    add("dge_apply(W)", lambda: b.fp4_dge_apply(G, L["W"], L["ctx"].gamma_W, cfg.dge_k, cfg.dge_cap, dW=L["dW"]),
+        KN * (eb + 8))
+    nnz = int(L["ctx"].nnz.item())
+    R = torch.empty(l.M, l.N, device="cuda", dtype=torch.float32)
+    t = _time(lambda: b.fp4_residual_spmm(L["ctx"].row_ptr, L["ctx"].col_idx, L["ctx"].val, l.K, L["W"], R=R, ws=ws),
+              torch)
+    rep["residual_spmm(fwd)"] = {"nnz": nnz, "us": t * 1e6, "GFLOP/s": 2.0 * nnz * l.N / t / 1e9}
+    return rep
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -88,6 +137,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device copy (gives hardware counters a kernel of known traffic)")
+    ap.add_argument("--no-kernel-report", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.stderr.write("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -149,6 +201,18 @@ def main():
                      "traffic": None, "avg_launch_ms": avg_gemm_ms, "launches": len(gemm_ms),
                      "gemm_share_of_step": sum(gemm_ms) / ms_total if ms_total else None},
     }
+    tfile = os.path.join(ROOT, "profiles", "fp4_gemm_nt_kernel_%s_hbm_traffic.txt" % args.workload)
+    if os.path.exists(tfile):
+        for line in open(tfile):
+            if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
+                out["roofline"]["traffic"] = float(line.split("=", 1)[1])
+    if not args.no_kernel_report:
+        out["kernels"] = kernel_report(cfg, layers[0], b, torch, ws)
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
