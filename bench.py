@@ -130,6 +130,25 @@ def kernel_report(cfg, L, b, torch, ws):
     return rep
 
 
+def ceilings(b, torch):
+    """What this part sustains: FP4 MFMA issue loop (constant and random operand data) and a
+    streaming copy.  Context for the roofline fractions, which stay quoted against the
+    published peaks."""
+    out = {}
+    wgs, iters = 256, 20000
+    sink = torch.empty(wgs * 512, device="cuda", dtype=torch.float32)
+    flop = wgs * 8.0 * iters * 8 * 131072
+    for name, data in (("constant", torch.full((1 << 20,), 0x21, dtype=torch.uint8, device="cuda")),
+                       ("random", torch.randint(0, 256, (1 << 20,), dtype=torch.uint8, device="cuda"))):
+        t = _time(lambda: b.fp4_probe_mfma(data, wgs, iters, sink), torch, n=3, warm=1)
+        out["fp4_mfma_issue_loop_%s_operands_TFLOPs" % name] = flop / t / 1e12
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
+    dst = torch.empty_like(src)
+    t = _time(lambda: b.fp4_probe_copy(src, dst), torch, n=5, warm=1)
+    out["stream_copy_GBs_read_plus_write"] = 2.0 * src.numel() / t / 1e9
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -208,6 +227,7 @@ def main():
                 out["roofline"]["traffic"] = float(line.split("=", 1)[1])
     if not args.no_kernel_report:
         out["kernels"] = kernel_report(cfg, layers[0], b, torch, ws)
+        out["ceilings"] = ceilings(b, torch)
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
         dst = torch.empty_like(src)

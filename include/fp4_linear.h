@@ -180,6 +180,17 @@ int fp4_residual_spmm(const int64_t* row_ptr, const int32_t* col_idx, const floa
  * the CPU; lets the rounding be checked exhaustively without a GPU). */
 int fp4_host_round_codes(const float* x_host, int64_t n, uint8_t* codes_host);
 
+/* ---- ceilings measured on the part (for reading the rooflines; not part of the method) ----
+ * fp4_probe_mfma: `workgroups` workgroups of 8 waves each run `iters` iterations of 8 FP4
+ *   32x32x64 MFMAs per wave with operands taken from operand_bytes (device, >= 16 bytes): an
+ *   issue loop without memory traffic.  FLOP = workgroups * 8 * iters * 8 * 131072.  The rate
+ *   depends on the operand data (random codes draw more power than constant ones).
+ *   sink: device, workgroups * 512 floats.
+ * fp4_probe_copy: dst[0..nbytes) = src[0..nbytes), 16 bytes per lane (streaming copy). */
+int fp4_probe_mfma(const void* operand_bytes, int64_t nbytes, int workgroups, int iters, float* sink,
+                   void* stream);
+int fp4_probe_copy(const void* src, void* dst, int64_t nbytes, void* stream);
+
 /* ---- measurement helper (host-side state, off by default; not thread-safe) ----
  * Between fp4_trace_gemm_begin(n) and fp4_trace_gemm_end() every launch of the FP4 GEMM
  * kernel, from any entry point, is bracketed by a pair of HIP events recorded on the

@@ -62,6 +62,10 @@ def lib() -> C.CDLL:
         L.fp4_dge_apply.argtypes = [vp, vp, i32, vp, i64, i64, f32, f32, vp, vp]
         L.fp4_residual_spmm.argtypes = [vp, vp, vp, i64, i64, vp, i32, i64, vp, vp, sz, vp]
         L.fp4_host_round_codes.argtypes = [vp, i64, vp]
+        L.fp4_probe_mfma.argtypes = [vp, i64, i32, i32, vp, vp]
+        L.fp4_probe_mfma.restype = i32
+        L.fp4_probe_copy.argtypes = [vp, vp, i64, vp]
+        L.fp4_probe_copy.restype = i32
         L.fp4_trace_gemm_begin.argtypes = [i32]
         L.fp4_trace_gemm_begin.restype = i32
         L.fp4_trace_gemm_end.argtypes = [vp, i32]
@@ -326,3 +330,15 @@ def fp4_trace_gemm_end(max_launches: int):
     if n < 0:
         raise Fp4Error(n, "fp4_trace_gemm_end")
     return [float(buf[i]) for i in range(min(n, max_launches))]
+
+
+def fp4_probe_mfma(operand_bytes: torch.Tensor, workgroups: int, iters: int, sink: torch.Tensor) -> None:
+    _dev_check(operand_bytes, sink)
+    _check(lib().fp4_probe_mfma(_ptr(operand_bytes), operand_bytes.numel() * operand_bytes.element_size(),
+                                int(workgroups), int(iters), _ptr(sink), _stream()), "fp4_probe_mfma")
+
+
+def fp4_probe_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    _dev_check(src, dst)
+    _check(lib().fp4_probe_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream()),
+           "fp4_probe_copy")

@@ -13,6 +13,7 @@
 // 2^22/36 and does not depend on summation order.
 #include "fp4_common.h"
 
+#include <algorithm>
 #include <utility>
 #include <vector>
 
@@ -92,17 +93,6 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
 
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of the
   // tile sequence so that tiles sharing operand rows meet in the same L2.
-  const int total = g.tiles_p * g.tiles_q;
-  const int per_xcd = (total + 7) / 8;
-  const int lid = (int)(blockIdx.x % 8) * per_xcd + (int)(blockIdx.x / 8);
-  if (lid >= total) return;
-  const int in_group = GROUP_P * g.tiles_q;
-  const int group = lid / in_group;
-  const int first_p = group * GROUP_P;
-  const int gsz = min(g.tiles_p - first_p, GROUP_P);
-  const int tp = first_p + (lid % in_group) % gsz;
-  const int tq = (lid % in_group) / gsz;
-
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept scalar
@@ -110,6 +100,22 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
   const int wave_q = wave >> 1;   // 0 .. WQ-1
   const int l32 = lane & 31;
   const int lhi = lane >> 5;
+
+  // Persistent workgroups: the grid is at most one workgroup per CU and each walks a strided
+  // share of its XCD's run of tiles, so a tile's stores drain while the next tile computes and
+  // no workgroup relaunch sits between tiles.
+  const int total = g.tiles_p * g.tiles_q;
+  const int per_xcd = (total + 7) / 8;
+  const int xcd = (int)(blockIdx.x % 8);
+  const int wg_in_xcd = (int)(blockIdx.x / 8), wgs_per_xcd = (int)(gridDim.x / 8);
+  const int run_end = min(total, (xcd + 1) * per_xcd);
+  for (int lid = xcd * per_xcd + wg_in_xcd; lid < run_end; lid += wgs_per_xcd) {
+  const int in_group = GROUP_P * g.tiles_q;
+  const int group = lid / in_group;
+  const int first_p = group * GROUP_P;
+  const int gsz = min(g.tiles_p - first_p, GROUP_P);
+  const int tp = first_p + (lid % in_group) % gsz;
+  const int tq = (lid % in_group) / gsz;
 
   const int64_t P0 = (int64_t)tp * BM;
   const int64_t Q0 = (int64_t)tq * BN;
@@ -411,6 +417,8 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
   }
+  __syncthreads();   // the staging regions overlap the operand stages of the next tile
+  }  // tiles
 }
 
 __global__ void fp4_unpack_kernel(const uint8_t* codes, int64_t nbytes, uint8_t* out) {
@@ -445,7 +453,13 @@ int fp4_launch_gemm(const uint8_t* L, const float* gl, const uint8_t* Rt, const 
   g.tiles_q = (int)((Q + BN - 1) / BN);
   const bool dge = W != nullptr && dge_k > 0.0f;
   const int total = g.tiles_p * g.tiles_q;
-  const dim3 grid(((total + 7) / 8) * 8), block(NTHREADS);
+  static int n_cu = 0;
+  if (n_cu == 0) {
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 8) n_cu = 256;
+  }
+  const dim3 grid(std::min(((total + 7) / 8) * 8, (n_cu / 8) * 8)), block(NTHREADS);
   const bool traced = g_trace.on && 2 * g_trace.used + 1 < (int)g_trace.ev.size();
   if (traced) (void)hipEventRecord(g_trace.ev[2 * g_trace.used], stream);
   const bool ragged = (g.Kb % BKB) != 0;

@@ -1,0 +1,68 @@
+// Ceilings the rooflines are read against, measured on the part itself: an FP4 MFMA issue loop
+// (no memory traffic inside the loop) and a streaming copy.  The issue loop takes its operands
+// from a caller buffer because the sustained matrix-core rate of this part depends on the data:
+// with random codes the chip settles at a lower clock than with constant operands.
+#include "fp4_common.h"
+
+typedef int i32x8p __attribute__((ext_vector_type(8)));
+typedef float f32x16p __attribute__((ext_vector_type(16)));
+
+namespace {
+
+// 512 threads = 8 waves = 2 per SIMD, 8 independent 32x32 accumulators per wave: the shape of
+// the GEMM's compute phase.
+__global__ __launch_bounds__(512) void probe_mfma_kernel(const u32x4* __restrict__ data, int64_t nvec, int iters,
+                                                         float* __restrict__ sink) {
+  f32x16p acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
+  u32x4 f[6];
+#pragma unroll
+  for (int i = 0; i < 6; ++i) f[i] = data[((int64_t)blockIdx.x * 512 + threadIdx.x + (int64_t)i * 8191) % nvec];
+  const int one = 0x7f7f7f7f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      i32x8p a = {(int)f[q].x, (int)f[q].y, (int)f[q].z, (int)f[q].w, 0, 0, 0, 0};
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        i32x8p b = {(int)f[2 + p].x, (int)f[2 + p].y, (int)f[2 + p].z, (int)f[2 + p].w, 0, 0, 0, 0};
+        acc[q * 4 + p] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[q * 4 + p], 4, 4, 0, one, 0, one);
+      }
+    }
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][7];
+  sink[(int64_t)blockIdx.x * 512 + threadIdx.x] = s;
+}
+
+__global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst,
+                                                         int64_t nvec) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+}  // namespace
+
+extern "C" int fp4_probe_mfma(const void* operand_bytes, int64_t nbytes, int workgroups, int iters, float* sink,
+                              void* stream) {
+  if (!operand_bytes || !sink) return FP4_ERR_NULL;
+  if (nbytes < 16 || workgroups <= 0 || iters <= 0) return FP4_ERR_SHAPE;
+  if (!aligned16(operand_bytes)) return FP4_ERR_ARG;
+  hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(512), 0, (hipStream_t)stream,
+                     reinterpret_cast<const u32x4*>(operand_bytes), nbytes / 16, iters, sink);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
+
+extern "C" int fp4_probe_copy(const void* src, void* dst, int64_t nbytes, void* stream) {
+  if (!src || !dst) return FP4_ERR_NULL;
+  if (nbytes < 16) return FP4_ERR_SHAPE;
+  if (!aligned16(src) || !aligned16(dst)) return FP4_ERR_ARG;
+  hipLaunchKernelGGL(probe_copy_kernel, dim3(8192), dim3(256), 0, (hipStream_t)stream,
+                     reinterpret_cast<const u32x4*>(src), reinterpret_cast<u32x4*>(dst), nbytes / 16);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
