@@ -29,7 +29,8 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr int SP_ROWS = 1024;   // output rows per workgroup = threads
 constexpr int SP_COLS = 64;     // output columns per workgroup
 constexpr int SP_KS = 512;      // rows of D per LDS slab
-constexpr int SP_LD = SP_COLS + 4;  // padded LDS row (floats)
+constexpr int SP_LD = SP_COLS;   // LDS row (floats), unpadded: see the lane swizzle in the kernel
+constexpr int SP_XM = 15;        // lane bits that rotate the order in which a thread reads a D row
 constexpr int LONG_ROW = 2048;  // entries above which a row goes to the long-row kernel
 
 template <class DT>
@@ -110,6 +111,16 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
   };
   if (cur < end) load_quad();
 
+  // Every lane gathers a different LDS row, so the bank a 16-byte read lands on cannot depend
+  // on the row or the lanes collide at random.  Rows are unpadded (every row starts at bank 0)
+  // and lane l reads the row's 16-byte chunks in the order j ^ (l & SP_XM): neighbouring lanes
+  // always sit on different banks, whatever rows they read.  acc[4 j ..] of lane l therefore
+  // holds columns 4 (j ^ (l & SP_XM)) ..; the final store undoes the permutation.
+  const int swz = tid & SP_XM;
+  int xo[SP_XM + 1];
+#pragma unroll
+  for (int j = 0; j <= SP_XM; ++j) xo[j] = (j ^ swz) * 4;
+
   for (int64_t k0 = 0; k0 < Q; k0 += SP_KS) {
     __syncthreads();
 #pragma unroll
@@ -136,12 +147,17 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
       ++cur;
       const float* dr = &slab[(c - (int32_t)k0) * SP_LD];
 #pragma unroll
-      for (int j = 0; j < SP_COLS; j += 4) {
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(dr + j);
-        acc[j + 0] = fmaf(v, d4.x, acc[j + 0]);
-        acc[j + 1] = fmaf(v, d4.y, acc[j + 1]);
-        acc[j + 2] = fmaf(v, d4.z, acc[j + 2]);
-        acc[j + 3] = fmaf(v, d4.w, acc[j + 3]);
+      for (int jl = 0; jl <= SP_XM; ++jl) {
+        const float* p = dr + xo[jl];
+#pragma unroll
+        for (int jh = 0; jh < SP_COLS / 4; jh += SP_XM + 1) {
+          const int j = (jh + jl) * 4;
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(p + jh * 4);
+          acc[j + 0] = fmaf(v, d4.x, acc[j + 0]);
+          acc[j + 1] = fmaf(v, d4.y, acc[j + 1]);
+          acc[j + 2] = fmaf(v, d4.z, acc[j + 2]);
+          acc[j + 3] = fmaf(v, d4.w, acc[j + 3]);
+        }
       }
     }
   }
@@ -153,12 +169,14 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
 #pragma unroll
     for (int j = 0; j < SP_COLS; j += 4) {
       const f32x4 v4 = {acc[j], acc[j + 1], acc[j + 2], acc[j + 3]};
-      *reinterpret_cast<f32x4*>(o + j) = v4;
+      *reinterpret_cast<f32x4*>(o + (j ^ (swz * 4))) = v4;
     }
   } else {
 #pragma unroll
-    for (int j = 0; j < SP_COLS; ++j)
-      if (n0 + j < N) o[j] = acc[j];
+    for (int j = 0; j < SP_COLS; ++j) {
+      const int col = j ^ (swz * 4);
+      if (n0 + col < N) o[col] = acc[j];
+    }
   }
 }
 
