@@ -35,9 +35,10 @@ int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, con
 int64_t fp4_spmm_long_list_cap(int64_t capacity);
 int fp4_launch_order_rows(const int64_t* row_ptr, int64_t rows, int64_t nidx, int64_t capacity,
                           const int32_t* u_idx, const float* u_val, int32_t* idx, float* val, hipStream_t s);
+int64_t fp4_spmm_scratch_words(int64_t list_cap, int64_t Q, int64_t N);
 int fp4_launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val, int64_t capacity,
                     int64_t P, int64_t Q, const void* D, int bf16, int64_t N, float* R, int32_t* scratch,
-                    hipStream_t s);
+                    int64_t list_cap, hipStream_t s);
 
 namespace {
 
@@ -100,7 +101,7 @@ FwdWs carve_fwd(Carver& c, int64_t M, int64_t K, int64_t N, fp4_dtype dt) {
   // the workspace query does not know alpha, so it provides for alpha >= 0.9
   w.occ = carve_occ(c, M, 2 * tail_count(M * K, 0.9));
   w.R = dt == FP4_BF16 ? c.take<float>((size_t)(M * N)) : nullptr;
-  w.sp_scratch = c.take<int32_t>((size_t)(64 + fp4_spmm_long_list_cap(2 * tail_count(M * K, 0.9))));
+  w.sp_scratch = c.take<int32_t>((size_t)fp4_spmm_scratch_words(fp4_spmm_long_list_cap(2 * tail_count(M * K, 0.9)), K, N));
   return w;
 }
 
@@ -133,7 +134,7 @@ WgradWs carve_wgrad(Carver& c, int64_t M, int64_t K, int64_t N) {
   w.u_idx = c.take<int32_t>((size_t)cap);
   w.u_val = c.take<float>((size_t)cap);
   w.t_scratch = c.take<int32_t>((size_t)(2 * K));
-  w.sp_scratch = c.take<int32_t>((size_t)(64 + fp4_spmm_long_list_cap(cap)));
+  w.sp_scratch = c.take<int32_t>((size_t)fp4_spmm_scratch_words(fp4_spmm_long_list_cap(cap), M, N));
   return w;
 }
 
@@ -167,7 +168,7 @@ extern "C" size_t fp4_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, f
     case FP4_OP_FWD: carve_fwd(c, M, K, N, dt); break;
     case FP4_OP_DGRAD: carve_dgrad(c, M, K, N); break;
     case FP4_OP_WGRAD: carve_wgrad(c, M, K, N); break;
-    case FP4_OP_SPMM: c.take<int32_t>((size_t)(64 + M + 2)); break;   // long-row list, at most M rows
+    case FP4_OP_SPMM: c.take<int32_t>((size_t)fp4_spmm_scratch_words(M + 2, K, N)); break;   // long-row list: at most M rows
     default: return 0;
   }
   return c.off + 256;
@@ -251,7 +252,8 @@ extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_
     if (rc) return rc;
     // Delta_A W with the unquantized W, fp32; lands where the GEMM epilogue picks it up
     float* R = bf16 ? w.R : reinterpret_cast<float*>(Y);
-    rc = fp4_launch_spmm(saved->row_ptr, saved->col_idx, saved->val, cap, M, K, W, bf16, N, R, w.sp_scratch, s);
+    rc = fp4_launch_spmm(saved->row_ptr, saved->col_idx, saved->val, cap, M, K, W, bf16, N, R, w.sp_scratch,
+                         fp4_spmm_long_list_cap(2 * tail_count(M * K, 0.9)), s);
     if (rc) return rc;
     addend = R;
   } else {
@@ -315,7 +317,8 @@ extern "C" int fp4_linear_bwd_wgrad(const void* A, const void* dY, const void* W
     rc = fp4_launch_csr_transpose(saved->row_ptr, saved->col_idx, saved->val, saved->nnz, M, K,
                                   saved->capacity, w.t_ptr, w.t_idx, w.t_val, w.u_idx, w.u_val, w.t_scratch, s);
     if (rc) return rc;
-    rc = fp4_launch_spmm(w.t_ptr, w.t_idx, w.t_val, saved->capacity, K, M, dY, bf16, N, dW, w.sp_scratch, s);
+    rc = fp4_launch_spmm(w.t_ptr, w.t_idx, w.t_val, saved->capacity, K, M, dY, bf16, N, dW, w.sp_scratch,
+                         fp4_spmm_long_list_cap(2 * tail_count(M * K, 0.9)), s);
     if (rc) return rc;
     addend = dW;
   }
@@ -333,7 +336,7 @@ extern "C" int fp4_residual_spmm(const int64_t* row_ptr, const int32_t* col_idx,
   if (!aligned16(D) || !aligned16(R)) return FP4_ERR_ARG;
   if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_SPMM, P, Q, N, dt)) return FP4_ERR_WORKSPACE;
   int32_t* scratch = reinterpret_cast<int32_t*>(align_up((size_t)(uintptr_t)workspace, 256));
-  // the long-row list is sized by P here, so any capacity is safe
-  return fp4_launch_spmm(row_ptr, col_idx, val, (int64_t)P * 2048, P, Q, D, dt == FP4_BF16, N, R, scratch,
+  // no entry limit besides row_ptr itself; the long-row list is sized by P
+  return fp4_launch_spmm(row_ptr, col_idx, val, INT64_MAX, P, Q, D, dt == FP4_BF16, N, R, scratch, P + 2,
                          (hipStream_t)stream);
 }

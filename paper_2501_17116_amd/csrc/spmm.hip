@@ -181,31 +181,161 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
 }
 
 // ---- long rows -------------------------------------------------------------------------------
-__global__ void find_long_rows_kernel(const int64_t* row_ptr, int64_t P, int64_t capacity, int32_t* list,
-                                      int32_t* count, int32_t list_cap) {
-  const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (row >= P) return;
-  if (min(row_ptr[row + 1], capacity) - row_ptr[row] > LONG_ROW) {
-    const int32_t i = atomicAdd(count, 1);
-    if (i < list_cap) list[i] = (int32_t)row;
+// Rows above LONG_ROW entries, listed in ascending order by one workgroup (ballot + scan), so the
+// split between the two long-row kernels below does not depend on timing.
+__global__ __launch_bounds__(1024) void find_long_rows_kernel(const int64_t* row_ptr, int64_t P, int64_t capacity,
+                                                              int32_t* list, int32_t* count, int32_t list_cap) {
+  __shared__ int s_w[16];
+  __shared__ int s_base;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) s_base = 0;
+  __syncthreads();
+  for (int64_t r0 = 0; r0 < P; r0 += 1024) {
+    const int64_t row = r0 + threadIdx.x;
+    const bool is_long = row < P && min(row_ptr[row + 1], capacity) - row_ptr[row] > LONG_ROW;
+    const unsigned long long m = __ballot(is_long);
+    if (lane == 0) s_w[wave] = __popcll(m);
+    __syncthreads();
+    int before = s_base;
+    for (int w = 0; w < wave; ++w) before += s_w[w];
+    const int pos = before + __popcll(m & ((1ull << lane) - 1ull));
+    if (is_long && pos < list_cap) list[pos] = (int32_t)row;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int t = 0;
+      for (int w = 0; w < 16; ++w) t += s_w[w];
+      s_base += t;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *count = s_base;
+}
+
+// The first LD_CAP long rows (outlier channels of the transposed residual: nearly dense) are
+// multiplied as a small dense matrix so that D is streamed once for all of them instead of once
+// per row: a workgroup takes LD_SLICE rows of D x 512 columns x LD_LB long rows, scatters those
+// rows' values for its slice into an LDS table V[slice row][long row] (zero where a row has no
+// entry), and every lane keeps LD_LB x 8 accumulators for its 8 columns while the four waves
+// split the slice's rows.  Partial sums per slice go to a scratch array and are added in slice
+// order by a second kernel, so the result does not depend on scheduling.
+constexpr int LD_LB = 16;        // long rows per workgroup pass
+constexpr int LD_SLICE = 1024;   // rows of D per workgroup
+constexpr int LD_CAP = 32;       // long rows the dense path takes; the rest go row by row
+constexpr int LD_COLS = 512;     // columns per workgroup (64 lanes x 8)
+
+template <class DT>
+__global__ __launch_bounds__(256) void spmm_long_dense_kernel(const int64_t* row_ptr, const int32_t* col_idx,
+                                                              const float* val, int64_t capacity,
+                                                              const int32_t* list, const int32_t* count,
+                                                              const void* D, int64_t Q, int64_t N, float* part) {
+  __shared__ __attribute__((aligned(16))) float V[LD_SLICE * LD_LB];   // 64 KiB, reused for the wave reduction
+  const int n_long = min(*count, LD_CAP);
+  const int g0 = blockIdx.z * LD_LB;
+  if (g0 >= n_long) return;
+  const int nl = min(LD_LB, n_long - g0);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t m0 = (int64_t)blockIdx.y * LD_SLICE;
+  const int rows_here = (int)min((int64_t)LD_SLICE, Q - m0);
+  for (int i = tid; i < LD_SLICE * LD_LB; i += 256) V[i] = 0.0f;
+  __syncthreads();
+  for (int l = wave; l < nl; l += 4) {
+    const int64_t row = list[g0 + l];
+    int64_t lo = row_ptr[row];
+    const int64_t en = min(row_ptr[row + 1], capacity);
+    int64_t hi = en;
+    while (lo < hi) {   // first entry with column >= m0
+      const int64_t mid = (lo + hi) >> 1;
+      if (col_idx[mid] < m0) lo = mid + 1; else hi = mid;
+    }
+    for (int64_t i = lo + lane; i < en; i += 64) {
+      const int64_t c = col_idx[i];
+      if (c >= m0 + rows_here) break;
+      V[(c - m0) * LD_LB + l] = val[i];
+    }
+  }
+  __syncthreads();
+  const int64_t col = (int64_t)blockIdx.x * LD_COLS + lane * 8;
+  const int valid = col < N ? (int)min((int64_t)8, N - col) : 0;
+  float acc[LD_LB][8];
+#pragma unroll
+  for (int l = 0; l < LD_LB; ++l)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[l][e] = 0.0f;
+  if (valid > 0) {
+#pragma unroll 2
+    for (int r = wave; r < rows_here; r += 4) {
+      float d[8];
+      load8g<DT>(D, (m0 + r) * N + col, valid, d);
+      const f32x4* vr = reinterpret_cast<const f32x4*>(&V[r * LD_LB]);
+#pragma unroll
+      for (int q = 0; q < LD_LB / 4; ++q) {
+        const f32x4 v4 = vr[q];   // same address in every lane: an LDS broadcast
+        const float v[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[q * 4 + i][e] = fmaf(v[i], d[e], acc[q * 4 + i][e]);
+      }
+    }
+  }
+  // add the four waves' sums, four long rows at a time, in wave order
+  float* red = V;   // [4 waves][4 rows][512 columns]
+  const int64_t S_stride = (int64_t)LD_CAP * N;
+  float* const pout = part + (int64_t)blockIdx.y * S_stride;
+#pragma unroll
+  for (int q = 0; q < LD_LB / 4; ++q) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float* dst = red + ((wave * 4 + i) * LD_COLS + lane * 8);
+      *reinterpret_cast<f32x4*>(dst) = f32x4{acc[q * 4 + i][0], acc[q * 4 + i][1], acc[q * 4 + i][2], acc[q * 4 + i][3]};
+      *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[q * 4 + i][4], acc[q * 4 + i][5], acc[q * 4 + i][6], acc[q * 4 + i][7]};
+    }
+    __syncthreads();
+    const int i = tid >> 6;   // long row of this quarter summed by this thread
+    if (q * 4 + i < nl && valid > 0) {
+      float sum[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum[e] = 0.0f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sum[e] += red[(w * 4 + i) * LD_COLS + lane * 8 + e];
+      float* o = pout + (int64_t)(g0 + q * 4 + i) * N + col;
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (e < valid) o[e] = sum[e];
+    }
   }
 }
 
-__global__ void zero_i32_kernel(int32_t* p) { p[threadIdx.x] = 0; }
+__global__ __launch_bounds__(256) void spmm_long_reduce_kernel(const int32_t* list, const int32_t* count,
+                                                               const float* part, int slices, int64_t N, float* R) {
+  const int n_long = min(*count, LD_CAP);
+  const int li = blockIdx.y;
+  if (li >= n_long) return;
+  const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  float sum = 0.0f;
+  for (int sidx = 0; sidx < slices; ++sidx) sum += part[((int64_t)sidx * LD_CAP + li) * N + n];
+  R[(int64_t)list[li] * N + n] = sum;
+}
 
-// One workgroup per (long row, 32 columns): 4 column groups of 8 x 64 entry lanes; entry lane l
+// Long rows beyond the dense path's share (list positions >= first), one at a time: one
+// workgroup per (long row, 32 columns): 4 column groups of 8 x 64 entry lanes; entry lane l
 // takes entries l, l+64, ...; the 64 partial sums are added in a fixed order.
 template <class DT>
 __global__ __launch_bounds__(256) void spmm_long_rows_kernel(const int64_t* row_ptr, const int32_t* col_idx,
                                                              const float* val, int64_t capacity,
                                                              const int32_t* list, const int32_t* count,
-                                                             int32_t list_cap, const void* D, int64_t N, float* R) {
+                                                             int32_t list_cap, int32_t first, const void* D,
+                                                             int64_t N, float* R) {
   __shared__ float part[64][4][8];
   const int n_long = min(*count, list_cap);
   const int cg = threadIdx.x & 3, el = threadIdx.x >> 2;
   const int64_t col = (int64_t)blockIdx.y * 32 + cg * 8;
   const int valid = col < N ? (int)min((int64_t)8, N - col) : 0;
-  for (int li = blockIdx.x; li < n_long; li += gridDim.x) {
+  for (int li = first + blockIdx.x; li < n_long; li += gridDim.x) {
     const int64_t row = list[li];
     float acc[8];
 #pragma unroll
@@ -382,10 +512,16 @@ __global__ __launch_bounds__(256) void csr_bitmap_sort_kernel(const int64_t* seg
 // ---- launchers ---------------------------------------------------------------------------------
 int64_t fp4_spmm_long_list_cap(int64_t capacity) { return capacity / LONG_ROW + 2; }
 
-// scratch: int32 count[64 (only [0] used)] followed by int32 list[fp4_spmm_long_list_cap(capacity)]
+// int32 words of scratch fp4_launch_spmm needs: count[64 (only [0] used)], list[list_cap], then
+// the fp32 partial sums of the dense long-row path, [slices][LD_CAP][N].
+int64_t fp4_spmm_scratch_words(int64_t list_cap, int64_t Q, int64_t N) {
+  const int64_t slices = (Q + LD_SLICE - 1) / LD_SLICE;
+  return 64 + ((list_cap + 63) / 64) * 64 + slices * LD_CAP * N;
+}
+
 int fp4_launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val, int64_t capacity,
                     int64_t P, int64_t Q, const void* D, int bf16, int64_t N, float* R, int32_t* scratch,
-                    hipStream_t s) {
+                    int64_t list_cap64, hipStream_t s) {
   if (P == 0 || N == 0) return FP4_OK;
   const dim3 grid((unsigned)((P + SP_ROWS - 1) / SP_ROWS), (unsigned)((N + SP_COLS - 1) / SP_COLS));
   if (bf16)
@@ -395,17 +531,28 @@ int fp4_launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float*
   if (Q > LONG_ROW && capacity > LONG_ROW) {   // otherwise no row can be long
     int32_t* count = scratch;
     int32_t* list = scratch + 64;
-    const int32_t list_cap = (int32_t)std::min<int64_t>(fp4_spmm_long_list_cap(capacity), P);
-    hipLaunchKernelGGL(zero_i32_kernel, dim3(1), dim3(64), 0, s, count);
-    hipLaunchKernelGGL(find_long_rows_kernel, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, row_ptr, P, capacity,
-                       list, count, list_cap);
-    const dim3 lgrid((unsigned)std::min<int32_t>(list_cap, 8), (unsigned)((N + 31) / 32));
+    const int32_t list_cap = (int32_t)std::min<int64_t>(list_cap64, P);
+    float* part = reinterpret_cast<float*>(scratch + 64 + ((list_cap64 + 63) / 64) * 64);
+    const int slices = (int)((Q + LD_SLICE - 1) / LD_SLICE);
+    hipLaunchKernelGGL(find_long_rows_kernel, dim3(1), dim3(1024), 0, s, row_ptr, P, capacity, list, count, list_cap);
+    const dim3 dgrid((unsigned)((N + LD_COLS - 1) / LD_COLS), (unsigned)slices, LD_CAP / LD_LB);
     if (bf16)
-      hipLaunchKernelGGL((spmm_long_rows_kernel<BF16>), lgrid, dim3(256), 0, s, row_ptr, col_idx, val, capacity, list,
-                         count, list_cap, D, N, R);
+      hipLaunchKernelGGL((spmm_long_dense_kernel<BF16>), dgrid, dim3(256), 0, s, row_ptr, col_idx, val, capacity, list,
+                         count, D, Q, N, part);
     else
-      hipLaunchKernelGGL((spmm_long_rows_kernel<F32>), lgrid, dim3(256), 0, s, row_ptr, col_idx, val, capacity, list,
-                         count, list_cap, D, N, R);
+      hipLaunchKernelGGL((spmm_long_dense_kernel<F32>), dgrid, dim3(256), 0, s, row_ptr, col_idx, val, capacity, list,
+                         count, D, Q, N, part);
+    hipLaunchKernelGGL(spmm_long_reduce_kernel, dim3((unsigned)((N + 255) / 256), LD_CAP), dim3(256), 0, s, list, count,
+                       part, slices, N, R);
+    if (list_cap > LD_CAP) {
+      const dim3 lgrid((unsigned)std::min<int32_t>(list_cap - LD_CAP, 8), (unsigned)((N + 31) / 32));
+      if (bf16)
+        hipLaunchKernelGGL((spmm_long_rows_kernel<BF16>), lgrid, dim3(256), 0, s, row_ptr, col_idx, val, capacity, list,
+                           count, list_cap, LD_CAP, D, N, R);
+      else
+        hipLaunchKernelGGL((spmm_long_rows_kernel<F32>), lgrid, dim3(256), 0, s, row_ptr, col_idx, val, capacity, list,
+                           count, list_cap, LD_CAP, D, N, R);
+    }
   }
   FP4_CHECK_LAUNCH();
   return FP4_OK;
