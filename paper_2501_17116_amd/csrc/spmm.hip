@@ -223,6 +223,82 @@ constexpr int LD_SLICE = 1024;   // rows of D per workgroup
 constexpr int LD_CAP = 32;       // long rows the dense path takes; the rest go row by row
 constexpr int LD_COLS = 512;     // columns per workgroup (64 lanes x 8)
 
+// Main loop and wave reduction of spmm_long_dense_kernel for NL accumulated long rows.
+template <class DT, int NL>
+FP4_D void long_dense_body(float* V, const void* D, int64_t m0, int rows_here, int64_t N, int nl, float* pout) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t col = (int64_t)blockIdx.x * LD_COLS + lane * 8;
+  const int valid = col < N ? (int)min((int64_t)8, N - col) : 0;
+  float acc[NL][8];
+#pragma unroll
+  for (int l = 0; l < NL; ++l)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[l][e] = 0.0f;
+  if (valid > 0) {
+    constexpr int UN = NL <= 8 ? 4 : 2;   // rows in flight per wave
+    int r = wave;
+    for (; r + 4 * (UN - 1) < rows_here; r += 4 * UN) {
+      float d[UN][8];
+#pragma unroll
+      for (int u = 0; u < UN; ++u) load8g<DT>(D, (m0 + r + 4 * u) * N + col, valid, d[u]);
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        const f32x4* vr = reinterpret_cast<const f32x4*>(&V[(r + 4 * u) * LD_LB]);
+#pragma unroll
+        for (int q = 0; q < NL / 4; ++q) {
+          const f32x4 v4 = vr[q];   // same address in every lane: an LDS broadcast
+          const float v[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[q * 4 + i][e] = fmaf(v[i], d[u][e], acc[q * 4 + i][e]);
+        }
+      }
+    }
+    for (; r < rows_here; r += 4) {
+      float d[8];
+      load8g<DT>(D, (m0 + r) * N + col, valid, d);
+      const f32x4* vr = reinterpret_cast<const f32x4*>(&V[r * LD_LB]);
+#pragma unroll
+      for (int q = 0; q < NL / 4; ++q) {
+        const f32x4 v4 = vr[q];
+        const float v[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[q * 4 + i][e] = fmaf(v[i], d[e], acc[q * 4 + i][e]);
+      }
+    }
+  }
+  // add the four waves' sums, four long rows at a time, in wave order
+  float* red = V;   // [4 waves][4 rows][512 columns]
+#pragma unroll
+  for (int q = 0; q < NL / 4; ++q) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float* dst = red + ((wave * 4 + i) * LD_COLS + lane * 8);
+      *reinterpret_cast<f32x4*>(dst) = f32x4{acc[q * 4 + i][0], acc[q * 4 + i][1], acc[q * 4 + i][2], acc[q * 4 + i][3]};
+      *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[q * 4 + i][4], acc[q * 4 + i][5], acc[q * 4 + i][6], acc[q * 4 + i][7]};
+    }
+    __syncthreads();
+    const int i = tid >> 6;   // long row of this quarter summed by this thread
+    if (q * 4 + i < nl && valid > 0) {
+      float sum[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum[e] = 0.0f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sum[e] += red[(w * 4 + i) * LD_COLS + lane * 8 + e];
+      float* o = pout + (int64_t)(q * 4 + i) * N + col;
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (e < valid) o[e] = sum[e];
+    }
+  }
+}
+
 template <class DT>
 __global__ __launch_bounds__(256) void spmm_long_dense_kernel(const int64_t* row_ptr, const int32_t* col_idx,
                                                               const float* val, int64_t capacity,
@@ -254,59 +330,11 @@ __global__ __launch_bounds__(256) void spmm_long_dense_kernel(const int64_t* row
     }
   }
   __syncthreads();
-  const int64_t col = (int64_t)blockIdx.x * LD_COLS + lane * 8;
-  const int valid = col < N ? (int)min((int64_t)8, N - col) : 0;
-  float acc[LD_LB][8];
-#pragma unroll
-  for (int l = 0; l < LD_LB; ++l)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[l][e] = 0.0f;
-  if (valid > 0) {
-#pragma unroll 2
-    for (int r = wave; r < rows_here; r += 4) {
-      float d[8];
-      load8g<DT>(D, (m0 + r) * N + col, valid, d);
-      const f32x4* vr = reinterpret_cast<const f32x4*>(&V[r * LD_LB]);
-#pragma unroll
-      for (int q = 0; q < LD_LB / 4; ++q) {
-        const f32x4 v4 = vr[q];   // same address in every lane: an LDS broadcast
-        const float v[4] = {v4.x, v4.y, v4.z, v4.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[q * 4 + i][e] = fmaf(v[i], d[e], acc[q * 4 + i][e]);
-      }
-    }
-  }
-  // add the four waves' sums, four long rows at a time, in wave order
-  float* red = V;   // [4 waves][4 rows][512 columns]
-  const int64_t S_stride = (int64_t)LD_CAP * N;
-  float* const pout = part + (int64_t)blockIdx.y * S_stride;
-#pragma unroll
-  for (int q = 0; q < LD_LB / 4; ++q) {
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float* dst = red + ((wave * 4 + i) * LD_COLS + lane * 8);
-      *reinterpret_cast<f32x4*>(dst) = f32x4{acc[q * 4 + i][0], acc[q * 4 + i][1], acc[q * 4 + i][2], acc[q * 4 + i][3]};
-      *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[q * 4 + i][4], acc[q * 4 + i][5], acc[q * 4 + i][6], acc[q * 4 + i][7]};
-    }
-    __syncthreads();
-    const int i = tid >> 6;   // long row of this quarter summed by this thread
-    if (q * 4 + i < nl && valid > 0) {
-      float sum[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) sum[e] = 0.0f;
-#pragma unroll
-      for (int w = 0; w < 4; ++w)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) sum[e] += red[(w * 4 + i) * LD_COLS + lane * 8 + e];
-      float* o = pout + (int64_t)(g0 + q * 4 + i) * N + col;
-#pragma unroll
-      for (int e = 0; e < 8; ++e)
-        if (e < valid) o[e] = sum[e];
-    }
-  }
+  float* const pout = part + (int64_t)blockIdx.y * LD_CAP * N + (int64_t)g0 * N;
+  // accumulators only for as many long rows as there are (4, 8 or 16): usually a handful
+  if (nl <= 4) long_dense_body<DT, 4>(V, D, m0, rows_here, N, nl, pout);
+  else if (nl <= 8) long_dense_body<DT, 8>(V, D, m0, rows_here, N, nl, pout);
+  else long_dense_body<DT, LD_LB>(V, D, m0, rows_here, N, nl, pout);
 }
 
 __global__ __launch_bounds__(256) void spmm_long_reduce_kernel(const int32_t* list, const int32_t* count,

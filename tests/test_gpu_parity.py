@@ -227,20 +227,20 @@ def test_residual_spmm_with_long_rows():
     assert_close(R, dense.numpy().astype(np.float64) @ D.numpy().astype(np.float64), "f32", "spmm long rows")
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_residual_spmm_many_long_rows(dtype):
+@pytest.mark.parametrize("dtype,P,n_long", [("f32", 45, 40), ("bf16", 45, 40), ("bf16", 8, 7), ("f32", 14, 12)])
+def test_residual_spmm_many_long_rows(dtype, P, n_long):
     # more long rows than the batched dense path accepts: the remainder goes row by row; two
     # slices of D rows, the second ragged; short rows in between
     g = torch.Generator().manual_seed(23)
-    P, Q, N = 45, 2600, 520
+    Q, N = 2600, 520
     dense = torch.zeros(P, Q)
     mask = torch.rand(P, Q, generator=g) < 0.9
-    mask[::9] = torch.rand(5, Q, generator=g) < 0.02      # rows 0, 9, .. stay short
+    mask[::9] = torch.rand((P + 8) // 9, Q, generator=g) < 0.02      # rows 0, 9, .. stay short
     dense[mask] = torch.randn(int(mask.sum()), generator=g)
     rows, cols = np.nonzero(dense.numpy())
     row_ptr = np.zeros(P + 1, np.int64)
     np.cumsum(np.bincount(rows, minlength=P), out=row_ptr[1:])
-    assert int((np.diff(row_ptr) > 2048).sum()) == 40
+    assert int((np.diff(row_ptr) > 2048).sum()) == n_long
     vals = dense.numpy()[rows, cols].astype(np.float32)
     D = synth._finish(torch.randn(Q, N, generator=g), dtype)
     args = (torch.from_numpy(row_ptr).cuda(), torch.from_numpy(cols.astype(np.int32)).cuda(),
