@@ -461,6 +461,42 @@ __global__ __launch_bounds__(256) void csr_transpose_fill_kernel(const int64_t* 
   }
 }
 
+// The same for a block of FILL_ROWS rows per workgroup when the column range fits an LDS table:
+// the workgroup counts its entries per column in LDS, reserves each column's share with one
+// global atomic, then places its entries with LDS atomics.  A column every row has an entry in
+// (an outlier channel) then costs one global atomic per workgroup instead of one per row.
+constexpr int FILL_ROWS = 128;
+__global__ __launch_bounds__(256) void csr_transpose_fill_block_kernel(const int64_t* row_ptr, const int32_t* col_idx,
+                                                                       const float* val, int64_t rows, int64_t Q,
+                                                                       int64_t capacity, const int64_t* t_ptr,
+                                                                       int32_t* cursor, int32_t* u_idx, float* u_val) {
+  __shared__ int32_t h[CNT_LDS];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t r0 = (int64_t)blockIdx.x * FILL_ROWS;
+  const int64_t r1 = min(r0 + FILL_ROWS, rows);
+  for (int i = threadIdx.x; i < Q; i += 256) h[i] = 0;
+  __syncthreads();
+  for (int64_t row = r0 + wave; row < r1; row += 4) {
+    const int64_t b = row_ptr[row], e = min(row_ptr[row + 1], capacity);
+    for (int64_t i = b + lane; i < e; i += 64) atomicAdd(&h[col_idx[i]], 1);
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < Q; i += 256) {
+    const int32_t n = h[i];
+    if (n) h[i] = atomicAdd(&cursor[i], n);   // first slot of this workgroup's share of column i
+  }
+  __syncthreads();
+  for (int64_t row = r0 + wave; row < r1; row += 4) {
+    const int64_t b = row_ptr[row], e = min(row_ptr[row + 1], capacity);
+    for (int64_t i = b + lane; i < e; i += 64) {
+      const int32_t c = col_idx[i];
+      const int64_t pos = t_ptr[c] + atomicAdd(&h[c], 1);
+      u_idx[pos] = (int32_t)row;
+      u_val[pos] = val[i];
+    }
+  }
+}
+
 // Order every segment by index (the indices inside a segment are distinct): an entry's final
 // slot is the number of smaller indices in its segment.  One thread per entry; the segment is
 // found by bisection on t_ptr.  Makes the transposed matrix, and so the sums over it,
@@ -597,8 +633,12 @@ int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, con
   const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((capacity + 4095) / 4096, 2048));
   hipLaunchKernelGGL(csr_count_cols_kernel, dim3(grid), dim3(256), 0, s, col_idx, nnz, capacity, Q, cnt);
   hipLaunchKernelGGL(scan_counts32_kernel, dim3(1), dim3(1024), 0, s, cnt, Q, t_ptr);
-  hipLaunchKernelGGL(csr_transpose_fill_kernel, dim3((unsigned)((P + 3) / 4)), dim3(256), 0, s, row_ptr, col_idx, val,
-                     P, capacity, t_ptr, cursor, u_idx, u_val);
+  if (Q <= CNT_LDS)
+    hipLaunchKernelGGL(csr_transpose_fill_block_kernel, dim3((unsigned)((P + FILL_ROWS - 1) / FILL_ROWS)), dim3(256), 0, s,
+                       row_ptr, col_idx, val, P, Q, capacity, t_ptr, cursor, u_idx, u_val);
+  else
+    hipLaunchKernelGGL(csr_transpose_fill_kernel, dim3((unsigned)((P + 3) / 4)), dim3(256), 0, s, row_ptr, col_idx, val,
+                       P, capacity, t_ptr, cursor, u_idx, u_val);
   if (capacity > 0 && P <= (int64_t)BM_WORDS * 32)
     hipLaunchKernelGGL(csr_bitmap_sort_kernel, dim3((unsigned)Q), dim3(256), (size_t)((P + 31) / 32) * 8, s, t_ptr, P,
                        capacity, u_idx, u_val, t_idx, t_val);

@@ -292,6 +292,7 @@ LAYER_CASES = [
     ("off", 96, 128, 96, "bf16", 1.0),
     ("tiny", 32, 32, 32, "f32", 0.9),
     ("long", 2304, 64, 96, "bf16", 0.97),     # an outlier channel: a transposed residual row > 2048 entries
+    ("wide", 64, 16416, 32, "bf16", 0.98),    # more input channels than the transpose's LDS tables hold
 ]
 
 
