@@ -41,6 +41,49 @@ FP4_D void load8(const void* base, int64_t off, int valid, float (&v)[8]) {
   }
 }
 
+// Eight elements as loaded (bf16: 16 bytes, fp32: 32 bytes): what the row kernel keeps in
+// registers between its two passes; widened to fp32 on use.
+template <class DT> struct Raw8;
+template <> struct Raw8<BF16> { u32x4 r; };
+template <> struct Raw8<F32> { f32x4 a, b; };
+
+template <class DT>
+FP4_D void load_raw8(const void* base, int64_t off, int valid, Raw8<DT>& w) {
+  if constexpr (__is_same(DT, BF16)) {
+    if (valid >= 8) {
+      w.r = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(base) + off);
+    } else {
+      uint32_t h[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) h[e] = e < valid ? (uint32_t)reinterpret_cast<const uint16_t*>(base)[off + e] : 0u;
+      w.r = u32x4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+    }
+  } else {
+    if (valid >= 8) {
+      const f32x4* p = reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(base) + off);
+      w.a = p[0]; w.b = p[1];
+    } else {
+      float f[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] = e < valid ? reinterpret_cast<const float*>(base)[off + e] : 0.0f;
+      w.a = f32x4{f[0], f[1], f[2], f[3]}; w.b = f32x4{f[4], f[5], f[6], f[7]};
+    }
+  }
+}
+
+template <class DT>
+FP4_D void widen8(const Raw8<DT>& w, float (&v)[8]) {
+  if constexpr (__is_same(DT, BF16)) {
+    v[0] = u2f(w.r.x << 16); v[1] = u2f(w.r.x & 0xffff0000u);
+    v[2] = u2f(w.r.y << 16); v[3] = u2f(w.r.y & 0xffff0000u);
+    v[4] = u2f(w.r.z << 16); v[5] = u2f(w.r.z & 0xffff0000u);
+    v[6] = u2f(w.r.w << 16); v[7] = u2f(w.r.w & 0xffff0000u);
+  } else {
+    v[0] = w.a.x; v[1] = w.a.y; v[2] = w.a.z; v[3] = w.a.w;
+    v[4] = w.b.x; v[5] = w.b.y; v[6] = w.b.z; v[7] = w.b.w;
+  }
+}
+
 template <class DT>
 FP4_D void store8(void* base, int64_t off, int valid, const float (&v)[8]) {
   if (valid >= 8) {
@@ -131,7 +174,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
   float lo = 0.0f, hi = 0.0f;
   if (OCC) { lo = a.thr[0]; hi = a.thr[1]; }
 
-  float cache[CACHED ? NV : 1][8];
+  Raw8<DT> cache[CACHED ? NV : 1];
   float amax = 0.0f;
   int cnt = 0;
 
@@ -149,11 +192,19 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
   if constexpr (CACHED) {
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
-      int valid;
-      visit(u, cache[u], valid);
+      const int64_t unit = (int64_t)u * TPR + t;
+      const int valid = (row_ok && unit < nunits) ? (int)min((int64_t)8, a.cols - unit * 8) : 0;
+      load_raw8<DT>(a.x, xoff + unit * 8, valid, cache[u]);   // valid <= 0 reads nothing and yields zeros
+    }
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+      const int64_t unit = (int64_t)u * TPR + t;
+      const int valid = (row_ok && unit < nunits) ? (int)min((int64_t)8, a.cols - unit * 8) : 0;
+      float v[8];
+      widen8<DT>(cache[u], v);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        float x = cache[u][e];
+        float x = v[e];
         if (OCC) {
           bool out = (x < lo) | (x > hi);
           cnt += (out && e < valid) ? 1 : 0;
@@ -182,6 +233,17 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
     }
   }
 
+  if constexpr (CACHED) {
+    // Pass 2 widens (and clamps) the cached units again.  Hide that they are the values pass 1
+    // saw, or the optimizer keeps all of pass 1's fp32 values alive instead, several times the
+    // registers of the raw units.
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+      if constexpr (__is_same(DT, BF16)) asm volatile("" : "+v"(cache[u].r));
+      else asm volatile("" : "+v"(cache[u].a), "+v"(cache[u].b));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
   amax = wave_max(amax);
   if (TPR == 256) {
     if (lane == 0) s_max[wave] = amax;
@@ -222,18 +284,29 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
     if (valid <= 0) return;
     const int64_t unit = (int64_t)u * TPR + t;
     if (OCC) {
+      // clamp, remembering which elements were clamped; the few that were are then emitted in
+      // a short loop over the set bits instead of one branch per element
+      uint32_t om = 0;
+      float x0[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        float x = v[e];
-        bool below = x < lo, above = x > hi;
-        if ((below | above) && e < valid) {
-          if (emit) {
-            a.tmp_col[wr] = (int32_t)(unit * 8 + e);
-            a.tmp_val[wr] = __fsub_rn(x, below ? lo : hi);
-          }
-          ++wr;
-        }
+        const float x = v[e];
+        x0[e] = x;
+        const bool below = x < lo, above = x > hi;
+        om |= ((below | above) && e < valid) ? (1u << e) : 0u;
         v[e] = below ? lo : (above ? hi : x);
+      }
+      while (om) {
+        const int e = __builtin_ctz(om);
+        om &= om - 1;
+        const float xa = (e & 1) ? x0[1] : x0[0], xb = (e & 1) ? x0[3] : x0[2];
+        const float xc = (e & 1) ? x0[5] : x0[4], xd = (e & 1) ? x0[7] : x0[6];
+        const float x = (e & 4) ? ((e & 2) ? xd : xc) : ((e & 2) ? xb : xa);
+        if (emit) {
+          a.tmp_col[wr] = (int32_t)(unit * 8 + e);
+          a.tmp_val[wr] = __fsub_rn(x, x < lo ? lo : hi);
+        }
+        ++wr;
       }
       if (a.x_clamped) store8<DT>(a.x_clamped, xoff + unit * 8, valid, v);
     }
@@ -247,7 +320,10 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
     for (int u = 0; u < NV; ++u) {
       const int64_t unit = (int64_t)u * TPR + t;
       int valid = (row_ok && unit < nunits) ? (int)min((int64_t)8, a.cols - unit * 8) : 0;
-      finish(u, cache[u], valid);
+      float v[8];
+      widen8<DT>(cache[u], v);
+      finish(u, v, valid);
+      if (OCC) __builtin_amdgcn_sched_barrier(0);   // one unit at a time: keeps the register count down
     }
   } else {
     for (int u = 0; u < nloop; ++u) {
