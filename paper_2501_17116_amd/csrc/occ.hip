@@ -69,15 +69,23 @@ __global__ __launch_bounds__(256) void sel_hist_kernel(const void* x, int64_t ro
   if (flat) {
     const int64_t nvec = rows * cols / EPV;
     const u32x4* xv = reinterpret_cast<const u32x4*>(x);
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * 256) {
-      const u32x4 r = xv[i];
+    auto visit_vec = [&](const u32x4& r) {
       if constexpr (__is_same(DT, BF16)) {
         visit(r.x & 0xffffu); visit(r.x >> 16); visit(r.y & 0xffffu); visit(r.y >> 16);
         visit(r.z & 0xffffu); visit(r.z >> 16); visit(r.w & 0xffffu); visit(r.w >> 16);
       } else {
         visit(r.x); visit(r.y); visit(r.z); visit(r.w);
       }
+    };
+    // four loads in flight per lane: with the LDS tables limiting a CU to two workgroups, one
+    // load at a time leaves the memory pipe mostly idle
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < nvec; i += 4 * stride) {
+      const u32x4 r0 = xv[i], r1 = xv[i + stride], r2 = xv[i + 2 * stride], r3 = xv[i + 3 * stride];
+      visit_vec(r0); visit_vec(r1); visit_vec(r2); visit_vec(r3);
     }
+    for (; i < nvec; i += stride) visit_vec(xv[i]);
   } else {
     const int64_t n = rows * cols;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
