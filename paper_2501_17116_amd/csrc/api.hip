@@ -33,6 +33,7 @@ int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, con
                              int32_t* t_idx, float* t_val, int32_t* u_idx, float* u_val, int32_t* scratch,
                              hipStream_t s);
 int64_t fp4_spmm_long_list_cap(int64_t capacity);
+int64_t fp4_csr_transpose_scratch_words(int64_t Q);
 int fp4_launch_order_rows(const int64_t* row_ptr, int64_t rows, int64_t nidx, int64_t capacity,
                           const int32_t* u_idx, const float* u_val, int32_t* idx, float* val, hipStream_t s);
 int64_t fp4_spmm_scratch_words(int64_t list_cap, int64_t Q, int64_t N);
@@ -133,7 +134,7 @@ WgradWs carve_wgrad(Carver& c, int64_t M, int64_t K, int64_t N) {
   w.t_val = c.take<float>((size_t)cap);
   w.u_idx = c.take<int32_t>((size_t)cap);
   w.u_val = c.take<float>((size_t)cap);
-  w.t_scratch = c.take<int32_t>((size_t)(2 * K));
+  w.t_scratch = c.take<int32_t>((size_t)fp4_csr_transpose_scratch_words(K));
   w.sp_scratch = c.take<int32_t>((size_t)fp4_spmm_scratch_words(fp4_spmm_long_list_cap(cap), M, N));
   return w;
 }

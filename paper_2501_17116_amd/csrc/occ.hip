@@ -156,27 +156,39 @@ __global__ __launch_bounds__(256) void sel_pick_kernel(SelState* st, unsigned lo
 }
 
 // ---- CSR finalisation ---------------------------------------------------------------------
-// ptr[0] = 0, ptr[i+1] = sum cnt[0..i]; optional copy of the total.  One workgroup.
+// ptr[0] = 0, ptr[i+1] = sum cnt[0..i]; optional copy of the total.  One workgroup; a thread
+// takes 16 consecutive counts, so one block scan covers 16384 of them.
 __global__ __launch_bounds__(1024) void scan_counts_kernel(const int32_t* cnt, int64_t n, int64_t* ptr,
                                                            int64_t* total_out) {
-  __shared__ long long s[1024];
+  __shared__ long long s_w[16];
   __shared__ long long carry;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (threadIdx.x == 0) { carry = 0; ptr[0] = 0; }
   __syncthreads();
-  for (int64_t base = 0; base < n; base += 1024) {
-    const int64_t i = base + threadIdx.x;
-    long long v = i < n ? cnt[i] : 0;
-    s[threadIdx.x] = v;
-    __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {
-      long long add = threadIdx.x >= o ? s[threadIdx.x - o] : 0;
-      __syncthreads();
-      s[threadIdx.x] += add;
-      __syncthreads();
+  for (int64_t base = 0; base < n; base += 16 * 1024) {
+    const int64_t i0 = base + (int64_t)threadIdx.x * 16;
+    long long v[16];
+    long long sum = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      sum += i0 + j < n ? cnt[i0 + j] : 0;
+      v[j] = sum;   // inclusive inside the thread
     }
-    if (i < n) ptr[i + 1] = carry + s[threadIdx.x];
+    long long incl = sum;   // inclusive over the wave
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const long long up = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += up;
+    }
+    if (lane == 63) s_w[wave] = incl;
     __syncthreads();
-    if (threadIdx.x == 1023) carry += s[1023];
+    long long before = carry + incl - sum;
+    for (int w = 0; w < wave; ++w) before += s_w[w];
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+      if (i0 + j < n) ptr[i0 + j + 1] = before + v[j];
+    __syncthreads();
+    if (threadIdx.x == 1023) carry = before + sum;
     __syncthreads();
   }
   if (threadIdx.x == 0 && total_out) *total_out = carry;

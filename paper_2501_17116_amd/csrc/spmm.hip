@@ -461,19 +461,19 @@ __global__ __launch_bounds__(256) void csr_transpose_fill_kernel(const int64_t* 
   }
 }
 
-// The same for a block of FILL_ROWS rows per workgroup when the column range fits an LDS table:
-// the workgroup counts its entries per column in LDS, reserves each column's share with one
-// global atomic, then places its entries with LDS atomics.  A column every row has an entry in
-// (an outlier channel) then costs one global atomic per workgroup instead of one per row.
-constexpr int FILL_ROWS = 128;
-__global__ __launch_bounds__(256) void csr_transpose_fill_block_kernel(const int64_t* row_ptr, const int32_t* col_idx,
-                                                                       const float* val, int64_t rows, int64_t Q,
-                                                                       int64_t capacity, const int64_t* t_ptr,
-                                                                       int32_t* cursor, int32_t* u_idx, float* u_val) {
+// ---- transpose without global atomics (column range fits the LDS table) ---------------------
+// The rows are cut into at most TB_MAX blocks.  Pass 1: every block's column counts, cb[block][col].
+// Pass 2: per column, exclusive scan of the counts over the blocks (in place) and the column
+// total.  Pass 3 (after the scan of the totals into t_ptr): a block places its entries at
+// t_ptr[col] + cb[block][col] + rank inside the block (LDS atomics).
+constexpr int TB_MAX = 256;
+__global__ __launch_bounds__(256) void csr_block_count_kernel(const int64_t* row_ptr, const int32_t* col_idx,
+                                                              int64_t rows, int64_t rows_per_block, int64_t Q,
+                                                              int64_t capacity, int32_t* cb) {
   __shared__ int32_t h[CNT_LDS];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t r0 = (int64_t)blockIdx.x * FILL_ROWS;
-  const int64_t r1 = min(r0 + FILL_ROWS, rows);
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+  const int64_t r1 = min(r0 + rows_per_block, rows);
   for (int i = threadIdx.x; i < Q; i += 256) h[i] = 0;
   __syncthreads();
   for (int64_t row = r0 + wave; row < r1; row += 4) {
@@ -481,10 +481,37 @@ __global__ __launch_bounds__(256) void csr_transpose_fill_block_kernel(const int
     for (int64_t i = b + lane; i < e; i += 64) atomicAdd(&h[col_idx[i]], 1);
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < Q; i += 256) {
-    const int32_t n = h[i];
-    if (n) h[i] = atomicAdd(&cursor[i], n);   // first slot of this workgroup's share of column i
+  int32_t* out = cb + (int64_t)blockIdx.x * Q;
+  for (int i = threadIdx.x; i < Q; i += 256) out[i] = h[i];
+}
+
+__global__ __launch_bounds__(64) void csr_block_scan_kernel(int32_t* cb, int nblocks, int64_t Q, int32_t* cnt) {
+  const int64_t c = (int64_t)blockIdx.x * 64 + threadIdx.x;
+  if (c >= Q) return;
+  int32_t run = 0;
+  for (int b0 = 0; b0 < nblocks; b0 += 16) {   // 16 independent loads at a time
+    int32_t v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v[j] = b0 + j < nblocks ? cb[(int64_t)(b0 + j) * Q + c] : 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      if (b0 + j < nblocks) cb[(int64_t)(b0 + j) * Q + c] = run;
+      run += v[j];
+    }
   }
+  cnt[c] = run;
+}
+
+__global__ __launch_bounds__(256) void csr_block_fill_kernel(const int64_t* row_ptr, const int32_t* col_idx,
+                                                             const float* val, int64_t rows, int64_t rows_per_block,
+                                                             int64_t Q, int64_t capacity, const int64_t* t_ptr,
+                                                             const int32_t* cb, int32_t* u_idx, float* u_val) {
+  __shared__ int32_t h[CNT_LDS];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
+  const int64_t r1 = min(r0 + rows_per_block, rows);
+  const int32_t* base = cb + (int64_t)blockIdx.x * Q;
+  for (int i = threadIdx.x; i < Q; i += 256) h[i] = base[i];
   __syncthreads();
   for (int64_t row = r0 + wave; row < r1; row += 4) {
     const int64_t b = row_ptr[row], e = min(row_ptr[row + 1], capacity);
@@ -622,23 +649,34 @@ int fp4_launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float*
   return FP4_OK;
 }
 
-// scratch: cnt[Q] + cursor[Q] int32; u_idx/u_val: unordered staging, capacity entries each
+// int32 words of scratch the transpose needs: cnt[Q], cursor[Q], block counts [TB_MAX][Q]
+// (the last only while the column range fits the LDS table).
+int64_t fp4_csr_transpose_scratch_words(int64_t Q) { return 2 * Q + (Q <= CNT_LDS ? (int64_t)TB_MAX * Q : 0); }
+
+// u_idx/u_val: unordered staging, capacity entries each
 int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, const float* val,
                              const int64_t* nnz, int64_t P, int64_t Q, int64_t capacity, int64_t* t_ptr,
                              int32_t* t_idx, float* t_val, int32_t* u_idx, float* u_val, int32_t* scratch,
                              hipStream_t s) {
   int32_t* cnt = scratch;
   int32_t* cursor = scratch + Q;
-  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((2 * Q + 255) / 256)), dim3(256), 0, s, scratch, 2 * Q, 0);
-  const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((capacity + 4095) / 4096, 2048));
-  hipLaunchKernelGGL(csr_count_cols_kernel, dim3(grid), dim3(256), 0, s, col_idx, nnz, capacity, Q, cnt);
-  hipLaunchKernelGGL(scan_counts32_kernel, dim3(1), dim3(1024), 0, s, cnt, Q, t_ptr);
-  if (Q <= CNT_LDS)
-    hipLaunchKernelGGL(csr_transpose_fill_block_kernel, dim3((unsigned)((P + FILL_ROWS - 1) / FILL_ROWS)), dim3(256), 0, s,
-                       row_ptr, col_idx, val, P, Q, capacity, t_ptr, cursor, u_idx, u_val);
-  else
+  if (Q <= CNT_LDS) {
+    int32_t* cb = scratch + 2 * Q;
+    const int64_t rpb = std::max<int64_t>(64, (P + TB_MAX - 1) / TB_MAX);
+    const int nblocks = (int)std::max<int64_t>(1, (P + rpb - 1) / rpb);
+    hipLaunchKernelGGL(csr_block_count_kernel, dim3(nblocks), dim3(256), 0, s, row_ptr, col_idx, P, rpb, Q, capacity, cb);
+    hipLaunchKernelGGL(csr_block_scan_kernel, dim3((unsigned)((Q + 63) / 64)), dim3(64), 0, s, cb, nblocks, Q, cnt);
+    hipLaunchKernelGGL(scan_counts32_kernel, dim3(1), dim3(1024), 0, s, cnt, Q, t_ptr);
+    hipLaunchKernelGGL(csr_block_fill_kernel, dim3(nblocks), dim3(256), 0, s, row_ptr, col_idx, val, P, rpb, Q, capacity,
+                       t_ptr, cb, u_idx, u_val);
+  } else {
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((2 * Q + 255) / 256)), dim3(256), 0, s, scratch, 2 * Q, 0);
+    const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((capacity + 4095) / 4096, 2048));
+    hipLaunchKernelGGL(csr_count_cols_kernel, dim3(grid), dim3(256), 0, s, col_idx, nnz, capacity, Q, cnt);
+    hipLaunchKernelGGL(scan_counts32_kernel, dim3(1), dim3(1024), 0, s, cnt, Q, t_ptr);
     hipLaunchKernelGGL(csr_transpose_fill_kernel, dim3((unsigned)((P + 3) / 4)), dim3(256), 0, s, row_ptr, col_idx, val,
                        P, capacity, t_ptr, cursor, u_idx, u_val);
+  }
   if (capacity > 0 && P <= (int64_t)BM_WORDS * 32)
     hipLaunchKernelGGL(csr_bitmap_sort_kernel, dim3((unsigned)Q), dim3(256), (size_t)((P + 31) / 32) * 8, s, t_ptr, P,
                        capacity, u_idx, u_val, t_idx, t_val);
