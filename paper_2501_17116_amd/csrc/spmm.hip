@@ -70,6 +70,7 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
                                                             int64_t P, int64_t Q, const void* __restrict__ D,
                                                             int64_t N, float* __restrict__ R) {
   __shared__ __attribute__((aligned(16))) float slab[SP_KS * SP_LD];
+  __shared__ int s_skip[SP_ROWS];
   const int tid = threadIdx.x;
   const int64_t row = (int64_t)blockIdx.x * SP_ROWS + tid;
   const int64_t n0 = (int64_t)blockIdx.y * SP_COLS;
@@ -161,22 +162,38 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
       }
     }
   }
-  if (row >= P) return;
-  const int64_t b = row_ptr[row];
-  if (min(row_ptr[row + 1], capacity) - b > LONG_ROW) return;
-  float* o = R + row * N + n0;
-  if (n0 + SP_COLS <= N && (N % 4) == 0) {
+  // A lane's 64 sums belong to one row of R (lanes are N floats apart); they go through LDS once
+  // more so that the stores run along rows: 16 lanes x 16 B per row, four rows per instruction.
+  // A wave's 64 x 64 tile takes 16 KiB, so the workgroup stores in two rounds of eight waves.
+  bool skip = row >= P;   // rows outside the matrix, and long rows (other kernels write those)
+  if (!skip) skip = min(row_ptr[row + 1], capacity) - row_ptr[row] > LONG_ROW;
+  s_skip[tid] = skip ? 1 : 0;
+  __syncthreads();   // everyone is done with the last slab
+  const int lane = tid & 63, wave = tid >> 6;
+  float* const tile = slab + (wave & 7) * (64 * SP_COLS);
+  static_assert(8 * 64 * SP_COLS <= SP_KS * SP_LD, "eight wave tiles fit the slab");
+#pragma unroll 1
+  for (int round = 0; round < SP_ROWS / 512; ++round) {
+    if ((wave >> 3) == round) {
 #pragma unroll
-    for (int j = 0; j < SP_COLS; j += 4) {
-      const f32x4 v4 = {acc[j], acc[j + 1], acc[j + 2], acc[j + 3]};
-      *reinterpret_cast<f32x4*>(o + (j ^ (swz * 4))) = v4;
+      for (int j = 0; j < SP_COLS; j += 4)
+        *reinterpret_cast<f32x4*>(&tile[lane * SP_COLS + (j ^ (swz * 4))]) = f32x4{acc[j], acc[j + 1], acc[j + 2], acc[j + 3]};
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      const int tc = lane & 15;
+      const int64_t col = n0 + tc * 4;   // N is a multiple of 8: a 4-column chunk is inside or outside
+      if (col < N) {
+#pragma unroll 4
+        for (int ps = 0; ps < 16; ++ps) {
+          const int r = 4 * ps + (lane >> 4);
+          if (!s_skip[wave * 64 + r]) {
+            const f32x4 t = *reinterpret_cast<const f32x4*>(&tile[r * SP_COLS + tc * 4]);
+            *reinterpret_cast<f32x4*>(R + ((int64_t)blockIdx.x * SP_ROWS + wave * 64 + r) * N + col) = t;
+          }
+        }
+      }
     }
-  } else {
-#pragma unroll
-    for (int j = 0; j < SP_COLS; ++j) {
-      const int col = j ^ (swz * 4);
-      if (n0 + col < N) o[col] = acc[j];
-    }
+    __syncthreads();
   }
 }
 
