@@ -1,7 +1,10 @@
 """GPU parity at benchmark size: one LLaMA-7B-shaped layer (16384 tokens, 4096 -> 4096, bf16
 masters, OCC alpha = 0.99, DGE k = 5) in the launch configuration bench.py times, checked on
-sampled outputs the oracle can compute one by one.  Thresholds, scales, the residual count and
-the sampled rows' codes / CSR entries are bit-exact; sampled Y, dA, dW rows within tolerance."""
+sampled outputs the oracle can compute one by one; the same on a layer of the 1.3B-shaped
+configuration (8192 tokens, 5504 -> 2048: a contraction length that is not a multiple of the
+GEMM's K step) and on the heavy-tailed (Student-t) configuration at a reduced token count.
+Thresholds, scales, the residual count and the sampled rows' codes / CSR entries are bit-exact;
+sampled Y, dA, dW rows within tolerance."""
 import numpy as np
 import pytest
 import torch
@@ -25,20 +28,18 @@ def _close(got, ref, bf16, scale):
     assert not bad.any(), (int(bad.sum()), g[bad][:3], ref[bad][:3])
 
 
-@pytest.fixture(scope="module")
-def layer():
-    cfg = synth.CONFIGS["c3"]
-    shape = [l for l in cfg.layers if l.name == "o"][0]
-    A, W, dY = synth.make_layer(cfg, shape)
-    return cfg, shape, A, W, dY
+CASES = [("c3", "o", None), ("c2", "down", None), ("c4", "ffn", 2048)]
 
 
-def test_full_size_layer_sampled(layer):
-    cfg, shape, A, W, dY = layer
-    M, K, N = shape.M, shape.K, shape.N
+@pytest.mark.parametrize("cfg_name,layer_name,tokens", CASES)
+def test_full_size_layer_sampled(cfg_name, layer_name, tokens):
+    cfg = synth.CONFIGS[cfg_name]
+    shape = [l for l in cfg.layers if l.name == layer_name][0]
+    A, W, dY = synth.make_layer(cfg, shape) if tokens is None else synth.make_layer(cfg, shape, M=tokens)
+    M, K, N = A.shape[0], shape.K, shape.N
     Ad, Wd, dYd = (t.to(torch.bfloat16).cuda() for t in (A, W, dY))
     An, Wn, dYn = A.numpy(), W.numpy(), dY.numpy()
-    rows = np.array([0, 1, 255, 256, 4097, 8191, 12345, M - 1])
+    rows = np.unique(np.array([0, 1, 255, 256, 4097, 8191, 12345, M - 1]) % M)
     chans = np.array([0, 31, 32, 1000, 2047, K - 1] + synth.outlier_channels(cfg.idx, K, cfg.outlier_frac).tolist()[:2])
 
     # ---- OCC on the full activation tensor
