@@ -5,12 +5,13 @@
 //
 // out[p, q] = sum_k v(L[p, k]) v(Rt[q, k]) * (1/gamma_l[p]) * (1/gamma_r[q]) (+ addend) (* f')
 //
-// Both operands are K-major packed E2M1 ("NT" GEMM).  Tile 256 x 256 per workgroup of four
-// wave64s (2 x 2, 128 x 128 each), K step 256 codes (128 bytes per row), operands staged
-// through LDS in two buffers, 32x32x64 MFMA with both operands in the FP4 format and the
-// hardware block scales held at 2^0.  Every product of two E2M1 values is a multiple of
-// 1/4 and bounded by 36, so the fp32 accumulator is exact for any contraction length below
-// 2^22/36 and does not depend on summation order.
+// Both operands are K-major packed E2M1 ("NT" GEMM).  Tile 256 x 256 per workgroup of eight
+// wave64s (2 along rows x 4 along columns, 128 x 64 each), K step 256 codes (128 bytes per
+// row), operands brought into two LDS stages by direct-to-LDS buffer loads, 32x32x64 MFMA with
+// both operands in the FP4 format and the hardware block scales held at 2^0.  Workgroups are
+// persistent (one per CU, walking an XCD-local run of tiles).  Every product of two E2M1 values
+// is a multiple of 1/4 and bounded by 36, so the fp32 accumulator is exact for any contraction
+// length below 2^22/36 and does not depend on summation order.
 #include "fp4_common.h"
 
 #include <algorithm>
@@ -206,77 +207,74 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
     frag_l[ks] = (wave_p * 128 + l32) * BKB + slot * 16;
     frag_r[ks] = (wave_q * (QI * 32) + l32) * BKB + slot * 16;
   }
-  u32x4 fl[4], fr[QI];
-  auto read_frags = [&](int buf, int ks) {
+  u32x4 fl[2][4], fr[2][QI];   // fragments of two k-slices
+  auto read_frags = [&](int buf, int half) {
 #pragma unroll
-    for (int j = 0; j < QI; ++j)
-      fr[j] = *reinterpret_cast<const u32x4*>(sR + buf * TILE_BYTES + frag_r[ks] + j * 32 * BKB);
+    for (int s2 = 0; s2 < 2; ++s2) {
+      const int ks = 2 * half + s2;
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      fl[j] = *reinterpret_cast<const u32x4*>(sL + buf * TILE_BYTES + frag_l[ks] + j * 32 * BKB);
+      for (int j = 0; j < QI; ++j)
+        fr[s2][j] = *reinterpret_cast<const u32x4*>(sR + buf * TILE_BYTES + frag_r[ks] + j * 32 * BKB);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        fl[s2][j] = *reinterpret_cast<const u32x4*>(sL + buf * TILE_BYTES + frag_l[ks] + j * 32 * BKB);
+    }
   };
   const int one = 0x7f7f7f7f;  // E8M0 127 = 2^0 in every byte: hardware block scale off
-  // MFMA "A" operand = Rt rows (output columns, indexed by the accumulator registers),
-  // "B" operand = L rows (output rows, indexed by lane % 32): a lane ends up holding runs of
-  // 4 consecutive output columns of one output row.
-  auto mfma_slice = [&]() {
+  auto mfma_pair = [&]() {
 #pragma unroll
-    for (int qi = 0; qi < QI; ++qi) {
-      i32x8 a = {(int)fr[qi].x, (int)fr[qi].y, (int)fr[qi].z, (int)fr[qi].w, 0, 0, 0, 0};
+    for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-      for (int pj = 0; pj < 4; ++pj) {
-        i32x8 b = {(int)fl[pj].x, (int)fl[pj].y, (int)fl[pj].z, (int)fl[pj].w, 0, 0, 0, 0};
-        acc[qi][pj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[qi][pj], 4, 4, 0, one, 0, one);
+      for (int qi = 0; qi < QI; ++qi) {
+        i32x8 a = {(int)fr[s2][qi].x, (int)fr[s2][qi].y, (int)fr[s2][qi].z, (int)fr[s2][qi].w, 0, 0, 0, 0};
+#pragma unroll
+        for (int pj = 0; pj < 4; ++pj) {
+          i32x8 b = {(int)fl[s2][pj].x, (int)fl[s2][pj].y, (int)fl[s2][pj].z, (int)fl[s2][pj].w, 0, 0, 0, 0};
+          acc[qi][pj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[qi][pj], 4, 4, 0, one, 0, one);
+        }
       }
-    }
   };
 
   load_tile(0, 0, 0, NLD);
-  __builtin_amdgcn_s_waitcnt(0);   // direct loads are tracked by vmcnt: all of this wave's have landed
+  load_tile(min(1, KT - 1), 1, 0, NLD);
+  __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   read_frags(0, 0);
 
-  // Ping-pong: the two waves of a SIMD (wave w and w + 4) alternate between a compute phase
-  // (the MFMAs of one k-slice, back to back) and a memory phase (fragment reads of the next
-  // k-slice and this wave's share of the next tile's global -> LDS loads), half a period apart,
-  // so one wave's MFMAs cover the other's memory instructions.  Every phase ends in a
-  // workgroup barrier; the second group takes one extra barrier first, the first group one
-  // extra at the end.  The order inside a phase is pinned with scheduling barriers.
+  // Ping-pong with two k-slices per phase: the two waves of a SIMD (wave w and w + 4) alternate
+  // between a compute phase (16 MFMAs) and a memory phase (the 12 fragment reads of the next two
+  // slices; once per K step the wave's share of the loads of the tile after next, into the
+  // buffer whose last fragments everyone read two phases ago), half a period apart.
   const bool second_group = wave >= NWAVES / 2;
   if (second_group) __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
   for (int kt = 0; kt < KT; ++kt) {
     const int cur = kt & 1;
-    const int ktn = min(kt + 1, KT - 1);   // last iteration refetches its own tile: harmless, branch-free
-    static_for<4>([&](auto ksc) {
-      constexpr int ks = decltype(ksc)::value;
-      // ---- compute phase
+    const int ktn2 = min(kt + 2, KT - 1);
+    static_for<2>([&](auto hc) {
+      constexpr int h = decltype(hc)::value;
       __builtin_amdgcn_sched_barrier(0);
       __builtin_amdgcn_s_setprio(1);
-      mfma_slice();
-      // pin the MFMAs to this phase: the accumulators pass through an (empty) volatile asm
-      // that the optimizer must keep in order with the barriers
+      mfma_pair();
 #pragma unroll
       for (int qi = 0; qi < QI; ++qi)
         asm volatile("" : "+v"(acc[qi][0]), "+v"(acc[qi][1]), "+v"(acc[qi][2]), "+v"(acc[qi][3]));
       __builtin_amdgcn_s_setprio(0);
       __builtin_amdgcn_sched_barrier(0);
-      // before anyone reads the next tile (memory phase of k-slice 3) every wave's loads of
-      // it must have landed: each wave drains its own before the barrier that precedes the
-      // first such read (the first group's barrier after compute 3, the second group's
-      // barrier after memory 2)
-      if constexpr (ks == 3) {
+      // the next tile is first read in the memory phase h = 1; every wave's loads of it (issued
+      // a K step ago) must have landed by the barrier before the first group's
+      if constexpr (h == 1) {
         if (!second_group) __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
       }
       __builtin_amdgcn_s_barrier();
-      asm volatile("" ::: "memory");   // LDS is filled by direct loads the compiler does not see as stores
+      asm volatile("" ::: "memory");
       __builtin_amdgcn_sched_barrier(0);
-      // ---- memory phase
-      if constexpr (ks < 3) read_frags(cur, ks + 1);
-      else read_frags(cur ^ 1, 0);
-      if constexpr (ks < 2) load_tile(ktn, cur ^ 1, ks * (NLD / 2), (ks + 1) * (NLD / 2));
-      if constexpr (ks == 2) {
-        if (second_group) __builtin_amdgcn_s_waitcnt(0x0f70);    // vmcnt(0)
+      if constexpr (h == 0) {
+        read_frags(cur, 1);
+        if (second_group) __builtin_amdgcn_s_waitcnt(0x0f70);    // vmcnt(0): after the reads are issued
+      } else {
+        read_frags(cur ^ 1, 0);
+        load_tile(ktn2, cur, 0, NLD);
       }
       __builtin_amdgcn_sched_barrier(0);
       __builtin_amdgcn_s_barrier();
