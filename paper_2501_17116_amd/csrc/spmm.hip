@@ -29,6 +29,12 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr int SP_ROWS = 1024;   // output rows per workgroup = threads
 constexpr int SP_COLS = 64;     // output columns per workgroup
 constexpr int SP_KS = 512;      // rows of D per LDS slab
+constexpr int SP_RIF = 4;       // LDS chunk reads a lane has in flight before the FMAs that use them:
+                                // more do not fit the 128 VGPRs of a 1024-thread workgroup, and a smaller
+                                // workgroup with more registers loses more through occupancy
+constexpr int SP_RPP = SP_ROWS / 8;   // rows of D staged per pass (8 threads per row)
+constexpr int SP_WPR = SP_KS / 64;    // waves whose 64 x 64 tiles fit the slab at once
+static_assert(SP_KS % SP_RPP == 0, "whole staging passes");
 constexpr int SP_LD = SP_COLS;   // LDS row (floats), unpadded: see the lane swizzle in the kernel
 constexpr int SP_XM = 15;        // lane bits that rotate the order in which a thread reads a D row
 constexpr int LONG_ROW = 2048;  // entries above which a row goes to the long-row kernel
@@ -74,12 +80,19 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
   const int tid = threadIdx.x;
   const int64_t row = (int64_t)blockIdx.x * SP_ROWS + tid;
   const int64_t n0 = (int64_t)blockIdx.y * SP_COLS;
-  int64_t cur = 0, end = 0;
+  // Entry positions are kept as 32-bit offsets from the workgroup's first entry (a workgroup's
+  // rows hold fewer than 2^31 entries: the launcher bounds Q); the base stays in scalar registers.
+  const int64_t ebase = row_ptr[min((int64_t)blockIdx.x * SP_ROWS, P)];
+  uint32_t cur = 0, end = 0;
   if (row < P) {
-    cur = row_ptr[row];
-    end = min(row_ptr[row + 1], capacity);
-    if (end - cur > LONG_ROW) end = cur;   // long rows belong to spmm_long_rows_kernel
+    const int64_t b = row_ptr[row];
+    int64_t e = max(min(row_ptr[row + 1], capacity), b);
+    if (e - b > LONG_ROW) e = b;   // long rows belong to the long-row kernels
+    cur = (uint32_t)(b - ebase);
+    end = (uint32_t)(e - ebase);
   }
+  const int32_t* const cbase = col_idx + ebase;
+  const float* const vbase = val + ebase;
   float acc[SP_COLS];
 #pragma unroll
   for (int j = 0; j < SP_COLS; ++j) acc[j] = 0.0f;
@@ -92,21 +105,22 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
   // The row's entries are fetched four at a time (one 16-byte request per array instead of
   // four 4-byte ones: every lane walks a different row, so requests, not bytes, are what the
   // cache path runs out of).  A quad may run past the row's end; what lies there is ignored.
-  const int64_t limit = min(row_ptr[P], capacity);   // entries that exist
-  int64_t qb = cur;
+  const uint32_t limit =   // entries that exist, as an offset
+      (uint32_t)min(max(min(row_ptr[P], capacity) - ebase, (int64_t)0), (int64_t)0x7ffffff0);
+  uint32_t qb = cur;
   int32_t cq[4] = {0x7fffffff, 0x7fffffff, 0x7fffffff, 0x7fffffff};
   float vq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
   auto load_quad = [&]() {
     if (qb + 4 <= limit) {
-      const i32x4 c4 = *reinterpret_cast<const i32x4*>(col_idx + qb);   // dword-aligned 16-byte loads
-      const f32x4 v4 = *reinterpret_cast<const f32x4*>(val + qb);
+      const i32x4 c4 = *reinterpret_cast<const i32x4*>(cbase + qb);   // dword-aligned 16-byte loads
+      const f32x4 v4 = *reinterpret_cast<const f32x4*>(vbase + qb);
       cq[0] = c4.x; cq[1] = c4.y; cq[2] = c4.z; cq[3] = c4.w;
       vq[0] = v4.x; vq[1] = v4.y; vq[2] = v4.z; vq[3] = v4.w;
     } else {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        cq[i] = qb + i < limit ? col_idx[qb + i] : 0x7fffffff;
-        vq[i] = qb + i < limit ? val[qb + i] : 0.0f;
+        cq[i] = qb + i < limit ? cbase[qb + i] : 0x7fffffff;
+        vq[i] = qb + i < limit ? vbase[qb + i] : 0.0f;
       }
     }
   };
@@ -118,15 +132,18 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
   // always sit on different banks, whatever rows they read.  acc[4 j ..] of lane l therefore
   // holds columns 4 (j ^ (l & SP_XM)) ..; the final store undoes the permutation.
   const int swz = tid & SP_XM;
-  int xo[SP_XM + 1];
+  // chunk j = jl + 8 jh sits at (jl ^ (swz & 7)) + 8 (jh ^ (swz >> 3)): eight lane constants
+  // and two row bases instead of sixteen constants
+  int xo[8];
 #pragma unroll
-  for (int j = 0; j <= SP_XM; ++j) xo[j] = (j ^ swz) * 4;
+  for (int j = 0; j < 8; ++j) xo[j] = (j ^ (swz & 7)) * 4;
+  const int hi_off = (swz >> 3) * 32;
 
   for (int64_t k0 = 0; k0 < Q; k0 += SP_KS) {
     __syncthreads();
 #pragma unroll
-    for (int ps = 0; ps < SP_KS / 128; ++ps) {
-      const int r = ps * 128 + s_row;
+    for (int ps = 0; ps < SP_KS / SP_RPP; ++ps) {
+      const int r = ps * SP_RPP + s_row;
       float d[8];
       if (k0 + r < Q && s_valid > 0) load8g<DT>(D, (k0 + r) * N + s_col, s_valid, d);
       else {
@@ -147,17 +164,21 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
       const float v = sel == 0 ? vq[0] : sel == 1 ? vq[1] : sel == 2 ? vq[2] : vq[3];
       ++cur;
       const float* dr = &slab[(c - (int32_t)k0) * SP_LD];
+      // SP_RIF chunk reads in flight before the first FMA that needs one
+      static_assert(SP_XM == 15 && SP_COLS == 64, "one chunk per swizzle constant");
 #pragma unroll
-      for (int jl = 0; jl <= SP_XM; ++jl) {
-        const float* p = dr + xo[jl];
+      for (int g0 = 0; g0 < 16; g0 += SP_RIF) {
+        f32x4 d4[SP_RIF];
 #pragma unroll
-        for (int jh = 0; jh < SP_COLS / 4; jh += SP_XM + 1) {
-          const int j = (jh + jl) * 4;
-          const f32x4 d4 = *reinterpret_cast<const f32x4*>(p + jh * 4);
-          acc[j + 0] = fmaf(v, d4.x, acc[j + 0]);
-          acc[j + 1] = fmaf(v, d4.y, acc[j + 1]);
-          acc[j + 2] = fmaf(v, d4.z, acc[j + 2]);
-          acc[j + 3] = fmaf(v, d4.w, acc[j + 3]);
+        for (int q = 0; q < SP_RIF; ++q)
+          d4[q] = *reinterpret_cast<const f32x4*>(dr + (((g0 + q) & 8) ? 32 - hi_off : hi_off) + xo[(g0 + q) & 7]);
+#pragma unroll
+        for (int q = 0; q < SP_RIF; ++q) {
+          const int j = (g0 + q) * 4;
+          acc[j + 0] = fmaf(v, d4[q].x, acc[j + 0]);
+          acc[j + 1] = fmaf(v, d4[q].y, acc[j + 1]);
+          acc[j + 2] = fmaf(v, d4[q].z, acc[j + 2]);
+          acc[j + 3] = fmaf(v, d4[q].w, acc[j + 3]);
         }
       }
     }
@@ -170,11 +191,10 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
   s_skip[tid] = skip ? 1 : 0;
   __syncthreads();   // everyone is done with the last slab
   const int lane = tid & 63, wave = tid >> 6;
-  float* const tile = slab + (wave & 7) * (64 * SP_COLS);
-  static_assert(8 * 64 * SP_COLS <= SP_KS * SP_LD, "eight wave tiles fit the slab");
+  float* const tile = slab + (wave % SP_WPR) * (64 * SP_COLS);
 #pragma unroll 1
-  for (int round = 0; round < SP_ROWS / 512; ++round) {
-    if ((wave >> 3) == round) {
+  for (int round = 0; round < (SP_ROWS / 64 + SP_WPR - 1) / SP_WPR; ++round) {
+    if (wave / SP_WPR == round) {
 #pragma unroll
       for (int j = 0; j < SP_COLS; j += 4)
         *reinterpret_cast<f32x4*>(&tile[lane * SP_COLS + (j ^ (swz * 4))]) = f32x4{acc[j], acc[j + 1], acc[j + 2], acc[j + 3]};
@@ -631,6 +651,7 @@ int fp4_launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float*
                     int64_t P, int64_t Q, const void* D, int bf16, int64_t N, float* R, int32_t* scratch,
                     int64_t list_cap64, hipStream_t s) {
   if (P == 0 || N == 0) return FP4_OK;
+  if (Q >= ((int64_t)1 << 21)) return FP4_ERR_SHAPE;   // 32-bit entry offsets inside a workgroup's 1024 rows
   const dim3 grid((unsigned)((P + SP_ROWS - 1) / SP_ROWS), (unsigned)((N + SP_COLS - 1) / SP_COLS));
   if (bf16)
     hipLaunchKernelGGL((spmm_tile_kernel<BF16>), grid, dim3(SP_ROWS), 0, s, row_ptr, col_idx, val, capacity, P, Q, D, N, R);
