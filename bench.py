@@ -98,9 +98,20 @@ def _time(fn, torch, n=10, warm=2):
     return e0.elapsed_time(e1) / n * 1e-3
 
 
-def kernel_report(cfg, L, b, torch, ws):
-    """Stand-alone rates of the bandwidth-bound entry points on the workload's first layer:
-    algorithmic bytes (what the operation must read and write once) / time."""
+def _rotating(t, torch, min_bytes=320 << 20):
+    """Copies of t whose total size exceeds the 256 MB memory-side cache, so that a kernel timed
+    on them in turn reads HBM, not cache."""
+    n = max(2, -(-min_bytes // (t.numel() * t.element_size())))
+    return [t] + [t.clone() for _ in range(n - 1)]
+
+
+def kernel_report(cfg, layers, b, torch, ws):
+    """Stand-alone rates of the bandwidth-bound entry points on the workload's first layer
+    (algorithmic bytes -- what the operation must read and write once -- over time, inputs rotated
+    through more copies than the last-level cache holds), the cost of the fused pieces (DGE in the
+    weight-gradient GEMM, the residual in the forward pass) and a bf16 GEMM chain of the same
+    shapes through torch.matmul (the vendor BLAS: a yardstick, not part of the library)."""
+    L = layers[0]
     l = L["shape"]
     eb = 2 if cfg.dtype == "bf16" else 4
     rep = {}
@@ -109,24 +120,57 @@ def kernel_report(cfg, L, b, torch, ws):
         t = _time(fn, torch)
         rep[name] = {"GB/s": nbytes / t / 1e9, "frac_of_hbm_peak": nbytes / t / 1e9 / HBM_PEAK_GBS, "us": t * 1e6}
 
+    def cyc(fn, tensors):
+        state = {"i": 0}
+
+        def run():
+            state["i"] += 1
+            return fn(tensors[state["i"] % len(tensors)])
+        return run
+
     MK, KN, MN = l.M * l.K, l.K * l.N, l.M * l.N
-    add("quantize_rows(dY)", lambda: b.fp4_quantize(L["dY"], b.FP4_AXIS_ROW, ws=ws), MN * (eb + 0.5) + 4 * l.M)
-    add("quantize_rows(A)", lambda: b.fp4_quantize(L["A"], b.FP4_AXIS_ROW, ws=ws), MK * (eb + 0.5) + 4 * l.M)
+    As, Ws, dYs = _rotating(L["A"], torch), _rotating(L["W"], torch), _rotating(L["dY"], torch)
+    add("quantize_rows(dY)", cyc(lambda x: b.fp4_quantize(x, b.FP4_AXIS_ROW, ws=ws), dYs), MN * (eb + 0.5) + 4 * l.M)
+    add("quantize_rows(A)", cyc(lambda x: b.fp4_quantize(x, b.FP4_AXIS_ROW, ws=ws), As), MK * (eb + 0.5) + 4 * l.M)
     # a column scale spans all rows: the tensor has to be read twice
-    add("quantize_cols(W)", lambda: b.fp4_quantize(L["W"], b.FP4_AXIS_COL, ws=ws), KN * (2 * eb + 0.5) + 4 * l.N)
-    add("quantize_cols(dY)", lambda: b.fp4_quantize(L["dY"], b.FP4_AXIS_COL, ws=ws), MN * (2 * eb + 0.5) + 4 * l.N)
+    add("quantize_cols(W)", cyc(lambda x: b.fp4_quantize(x, b.FP4_AXIS_COL, ws=ws), Ws), KN * (2 * eb + 0.5) + 4 * l.N)
+    add("quantize_cols(dY)", cyc(lambda x: b.fp4_quantize(x, b.FP4_AXIS_COL, ws=ws), dYs), MN * (2 * eb + 0.5) + 4 * l.N)
     # OCC: thresholds cannot be applied in the pass that finds them: two reads, codes, CSR entries
     dens = 2 * (1 - cfg.alpha)
-    add("occ_clamp_residual(A)", lambda: b.occ_clamp_residual(L["A"], cfg.alpha, ws=ws),
+    add("occ_clamp_residual(A)", cyc(lambda x: b.occ_clamp_residual(x, cfg.alpha, ws=ws), As),
         MK * (2 * eb + 0.5 + 8 * dens) + 12 * l.M)
     G = torch.empty(l.K, l.N, device="cuda", dtype=torch.float32).normal_()
-    add("dge_apply(W)", lambda: b.fp4_dge_apply(G, L["W"], L["ctx"].gamma_W, cfg.dge_k, cfg.dge_cap, dW=L["dW"]),
+    add("dge_apply(W)", cyc(lambda x: b.fp4_dge_apply(G, x, L["ctx"].gamma_W, cfg.dge_k, cfg.dge_cap, dW=L["dW"]), Ws),
         KN * (eb + 8))
+    del As, Ws, dYs
     nnz = int(L["ctx"].nnz.item())
     R = torch.empty(l.M, l.N, device="cuda", dtype=torch.float32)
     t = _time(lambda: b.fp4_residual_spmm(L["ctx"].row_ptr, L["ctx"].col_idx, L["ctx"].val, l.K, L["W"], R=R, ws=ws),
               torch)
     rep["residual_spmm(fwd)"] = {"nnz": nnz, "us": t * 1e6, "GFLOP/s": 2.0 * nnz * l.N / t / 1e9}
+    del R
+    # what the fused pieces cost: forward with and without the outlier residual, weight gradient
+    # with the DGE factor and with the straight-through estimator (dge_k = 0)
+    ctx1 = b.FwdCtx(l.M, l.K, l.N, 1.0)
+    t_occ = _time(lambda: b.fp4_linear_fwd(L["A"], L["W"], cfg.alpha, ctx=L["ctx"], Y=L["Y"], ws=ws), torch)
+    t_plain = _time(lambda: b.fp4_linear_fwd(L["A"], L["W"], 1.0, ctx=ctx1, Y=L["Y"], ws=ws), torch)
+    rep["fwd(layer 0)"] = {"us_with_residual": t_occ * 1e6, "us_without": t_plain * 1e6, "nnz": nnz}
+    t_dge = _time(lambda: b.fp4_linear_bwd_wgrad(L["A"], L["dY"], L["W"], ctx1, cfg.dge_k, cfg.dge_cap, dW=L["dW"],
+                                                 ws=ws), torch)
+    t_ste = _time(lambda: b.fp4_linear_bwd_wgrad(L["A"], L["dY"], L["W"], ctx1, 0.0, cfg.dge_cap, dW=L["dW"], ws=ws),
+                  torch)
+    rep["wgrad(layer 0, no residual)"] = {"us_with_dge": t_dge * 1e6, "us_ste": t_ste * 1e6}
+    b.fp4_linear_fwd(L["A"], L["W"], cfg.alpha, ctx=L["ctx"], Y=L["Y"], ws=ws)   # restore the saved state
+
+    def bf16_chain():
+        for X in layers:
+            torch.matmul(X["A"], X["W"], out=X["Y"])
+            torch.matmul(X["dY"], X["W"].t(), out=X["dA"])
+            torch.matmul(X["A"].t(), X["dY"])
+    if cfg.dtype == "bf16":
+        t = _time(bf16_chain, torch, n=5, warm=2)
+        flops = sum(3 * 2.0 * X["shape"].M * X["shape"].K * X["shape"].N for X in layers)
+        rep["bf16_gemm_chain(torch.matmul)"] = {"ms": t * 1e3, "TFLOP/s": flops / t / 1e12}
     return rep
 
 
@@ -155,6 +199,8 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3")
+    ap.add_argument("--alpha", type=float, default=None,
+                    help="OCC quantile instead of the workload's (1.0 switches the residual off)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device copy (gives hardware counters a kernel of known traffic)")
@@ -171,6 +217,9 @@ def main():
 
     b.lib()   # fail loudly if the HIP library is missing
     cfg = synth.CONFIGS[args.workload]
+    if args.alpha is not None:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, alpha=args.alpha)
     torch.cuda.set_device(0)
     layers = build_layers(cfg, torch, b)
     ws = b.Workspace()
@@ -226,7 +275,7 @@ def main():
             if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
                 out["roofline"]["traffic"] = float(line.split("=", 1)[1])
     if not args.no_kernel_report:
-        out["kernels"] = kernel_report(cfg, layers[0], b, torch, ws)
+        out["kernels"] = kernel_report(cfg, layers, b, torch, ws)
         out["ceilings"] = ceilings(b, torch)
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
