@@ -17,8 +17,8 @@ int fp4_launch_quantize_rows(const void* x, int bf16, int64_t rows, int64_t cols
 int fp4_launch_occ_count(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, const float* thr,
                          int32_t* row_cnt, hipStream_t s);
 int fp4_launch_occ_rows(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, const float* thr,
-                        uint8_t* codes, float* gamma, void* x_clamped, int32_t* tmp_col, float* tmp_val,
-                        const int64_t* row_ptr, int64_t capacity, hipStream_t s);
+                        uint8_t* codes, float* gamma, void* x_clamped, int32_t* col_idx, float* val,
+                        int32_t* tmp_col, float* tmp_val, const int64_t* row_ptr, int64_t capacity, hipStream_t s);
 int fp4_launch_quantize_cols(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
                              const float* clamp_thr, uint8_t* codes_t, float* gamma, uint32_t* amax_scratch,
                              hipStream_t s);
@@ -202,11 +202,12 @@ extern "C" int occ_clamp_residual(const void* x, fp4_dtype dt, int64_t rows, int
   if (rc) return rc;
   rc = fp4_launch_scan_rows(t.row_cnt, rows, row_ptr, nnz, s);
   if (rc) return rc;
-  rc = fp4_launch_occ_rows(x, dt == FP4_BF16, rows, cols, ld, thresholds, codes, gamma, x_clamped, t.tmp_col,
-                           t.tmp_val, row_ptr, capacity, s);
-  if (rc) return rc;
-  rc = fp4_launch_order_rows(row_ptr, rows, cols, capacity, t.tmp_col, t.tmp_val, col_idx, val, s);
-  if (rc == 1) rc = fp4_launch_csr_gather(t.tmp_col, t.tmp_val, rows, capacity, row_ptr, col_idx, val, s);
+  rc = fp4_launch_occ_rows(x, dt == FP4_BF16, rows, cols, ld, thresholds, codes, gamma, x_clamped, col_idx, val,
+                           t.tmp_col, t.tmp_val, row_ptr, capacity, s);
+  if (rc == 1) {   // streamed rows: entries unordered in the temporaries
+    rc = fp4_launch_order_rows(row_ptr, rows, cols, capacity, t.tmp_col, t.tmp_val, col_idx, val, s);
+    if (rc == 1) rc = fp4_launch_csr_gather(t.tmp_col, t.tmp_val, rows, capacity, row_ptr, col_idx, val, s);
+  }
   return rc;
 }
 
@@ -244,12 +245,13 @@ extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_
     if (rc) return rc;
     rc = fp4_launch_scan_rows(w.occ.row_cnt, M, saved->row_ptr, saved->nnz, s);
     if (rc) return rc;
-    rc = fp4_launch_occ_rows(A, bf16, M, K, K, saved->thresholds, w.qA, w.gA, nullptr, w.occ.tmp_col,
-                             w.occ.tmp_val, saved->row_ptr, cap, s);
-    if (rc) return rc;
-    rc = fp4_launch_order_rows(saved->row_ptr, M, K, cap, w.occ.tmp_col, w.occ.tmp_val, saved->col_idx, saved->val, s);
-    if (rc == 1)
-      rc = fp4_launch_csr_gather(w.occ.tmp_col, w.occ.tmp_val, M, cap, saved->row_ptr, saved->col_idx, saved->val, s);
+    rc = fp4_launch_occ_rows(A, bf16, M, K, K, saved->thresholds, w.qA, w.gA, nullptr, saved->col_idx, saved->val,
+                             w.occ.tmp_col, w.occ.tmp_val, saved->row_ptr, cap, s);
+    if (rc == 1) {   // streamed rows: entries unordered in the temporaries
+      rc = fp4_launch_order_rows(saved->row_ptr, M, K, cap, w.occ.tmp_col, w.occ.tmp_val, saved->col_idx, saved->val, s);
+      if (rc == 1)
+        rc = fp4_launch_csr_gather(w.occ.tmp_col, w.occ.tmp_val, M, cap, saved->row_ptr, saved->col_idx, saved->val, s);
+    }
     if (rc) return rc;
     // Delta_A W with the unquantized W, fp32; lands where the GEMM epilogue picks it up
     float* R = bf16 ? w.R : reinterpret_cast<float*>(Y);

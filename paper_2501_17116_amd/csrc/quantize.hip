@@ -148,7 +148,7 @@ struct RowArgs {
   float* gamma;          // may be null (OCC only)
   void* x_clamped;       // may be null
   const float* thr;      // {lo, hi} (OCC)
-  int32_t* tmp_col;      // OCC: temporary entries
+  int32_t* tmp_col;      // OCC: where the entries go (final arrays when the kernel emits them in order)
   float* tmp_val;
   const int64_t* row_ptr;  // OCC: [rows + 1] first entry slot of every row (counted beforehand)
   int64_t rows, cols, ld, capacity;
@@ -160,6 +160,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
   constexpr bool CACHED = NV > 0;
   __shared__ float s_max[4];
   __shared__ int s_cnt[4];
+  __shared__ int s_round[CACHED ? NV : 1][4];
 
   const int tid = threadIdx.x;
   const int t = tid % TPR;
@@ -177,6 +178,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
   Raw8<DT> cache[CACHED ? NV : 1];
   float amax = 0.0f;
   int cnt = 0;
+  uint32_t cpk = 0;   // cached rows: this thread's outlier count per unit, 4 bits each
 
   auto visit = [&](int u, float (&v)[8], int& valid) {
     const int64_t unit = (int64_t)u * TPR + t;
@@ -202,17 +204,20 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
       const int valid = (row_ok && unit < nunits) ? (int)min((int64_t)8, a.cols - unit * 8) : 0;
       float v[8];
       widen8<DT>(cache[u], v);
+      int cu = 0;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         float x = v[e];
         if (OCC) {
           bool out = (x < lo) | (x > hi);
-          cnt += (out && e < valid) ? 1 : 0;
+          cu += (out && e < valid) ? 1 : 0;
           x = x < lo ? lo : (x > hi ? hi : x);
           if (e >= valid) x = 0.0f;
         }
         amax = fmaxf(amax, fabsf(x));
       }
+      cnt += cu;
+      cpk |= (uint32_t)cu << (4 * u);   // 0..8 outliers per unit
     }
   } else {
     for (int u = 0; u < nloop; ++u) {
@@ -253,29 +258,68 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
   const float gamma = absmax_to_gamma(amax);
   if (row_ok && t == 0 && a.gamma) a.gamma[row] = gamma;
 
-  // ---- OCC: reserve a segment of the entry list for this row
-  int64_t wr = 0;       // this thread's first entry slot
+  // ---- OCC: where this thread's entries go inside the row's segment of the entry list.
+  // Cached rows: a unit's entries follow those of all lower-numbered units of the row (unit
+  // u TPR + t holds columns 8 (u TPR + t) ..), so the row comes out in ascending column order
+  // and needs no ordering pass: per round u an exclusive scan of the unit counts over the
+  // row's threads, plus the totals of the rounds before.  Streamed rows (no cache): one
+  // segment per thread, columns not ascending; the caller orders them afterwards.
+  int64_t wr = 0;       // this thread's next entry slot
+  int64_t upos[CACHED ? NV : 1];
   bool emit = false;
   if (OCC) {
-    int incl = cnt;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      int n = __shfl_up(incl, o, 64);
-      if (lane >= o) incl += n;
-    }
-    int wave_total = __shfl(incl, 63, 64);
-    int excl = incl - cnt;
-    int row_total = wave_total;
-    if (TPR == 256) {
-      if (lane == 0) s_cnt[wave] = wave_total;
-      __syncthreads();
-      row_total = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
-      for (int w = 0; w < wave; ++w) excl += s_cnt[w];
-    }
-    (void)row_total;
     const long long base = row_ok ? a.row_ptr[row] : 0;
     emit = row_ok && (a.row_ptr[row + 1] <= a.capacity);
-    wr = base + excl;
+    if constexpr (CACHED) {
+      int excl_u[NV];
+#pragma unroll
+      for (int u = 0; u < NV; ++u) {
+        const int cu = (int)((cpk >> (4 * u)) & 15u);
+        int incl = cu;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          int n = __shfl_up(incl, o, 64);
+          if (lane >= o) incl += n;
+        }
+        excl_u[u] = incl - cu;
+        if (TPR == 256) {
+          if (lane == 63) s_round[u][wave] = incl;
+        } else {
+          excl_u[u] |= __shfl(incl, 63, 64) << 16;   // the round's total rides in the high half
+        }
+      }
+      if (TPR == 256) __syncthreads();
+      int before = 0;   // entries of the rounds already placed
+#pragma unroll
+      for (int u = 0; u < NV; ++u) {
+        int total, ex;
+        if (TPR == 256) {
+          ex = excl_u[u];
+          for (int w = 0; w < wave; ++w) ex += s_round[u][w];
+          total = s_round[u][0] + s_round[u][1] + s_round[u][2] + s_round[u][3];
+        } else {
+          ex = excl_u[u] & 0xffff;
+          total = excl_u[u] >> 16;
+        }
+        upos[u] = base + before + ex;
+        before += total;
+      }
+    } else {
+      int incl = cnt;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        int n = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += n;
+      }
+      int wave_total = __shfl(incl, 63, 64);
+      int excl = incl - cnt;
+      if (TPR == 256) {
+        if (lane == 0) s_cnt[wave] = wave_total;
+        __syncthreads();
+        for (int w = 0; w < wave; ++w) excl += s_cnt[w];
+      }
+      wr = base + excl;
+    }
   }
 
   // ---- pass 2: clamp again, emit residual entries, quantize, pack, store
@@ -284,6 +328,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
     if (valid <= 0) return;
     const int64_t unit = (int64_t)u * TPR + t;
     if (OCC) {
+      if constexpr (CACHED) wr = upos[u];
       // clamp, remembering which elements were clamped; the few that were are then emitted in
       // a short loop over the set bits instead of one branch per element
       uint32_t om = 0;
@@ -566,16 +611,24 @@ int fp4_launch_occ_count(const void* x, int bf16, int64_t rows, int64_t cols, in
   return FP4_OK;
 }
 
+// Rows short enough to stay in registers between the passes (up to 16384 elements) leave their
+// entries in ascending column order straight in (col_idx, val) and the call returns 0; longer
+// rows are streamed, their entries go unordered to (tmp_col, tmp_val) and the call returns 1:
+// the caller then orders them into (col_idx, val).  Negative: fp4_status.
 int fp4_launch_occ_rows(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
                         const float* thr, uint8_t* codes, float* gamma, void* x_clamped,
-                        int32_t* tmp_col, float* tmp_val, const int64_t* row_ptr, int64_t capacity,
-                        hipStream_t s) {
+                        int32_t* col_idx, float* val, int32_t* tmp_col, float* tmp_val,
+                        const int64_t* row_ptr, int64_t capacity, hipStream_t s) {
   if (rows == 0 || cols == 0) return FP4_OK;
+  const bool ordered = (cols + 7) / 8 <= 256 * 8;   // the variants launch_rows picks with a register cache
   RowArgs a = {};
   a.x = x; a.codes = codes; a.gamma = gamma; a.x_clamped = x_clamped; a.thr = thr;
-  a.tmp_col = tmp_col; a.tmp_val = tmp_val; a.row_ptr = row_ptr;
+  a.tmp_col = ordered ? col_idx : tmp_col;
+  a.tmp_val = ordered ? val : tmp_val;
+  a.row_ptr = row_ptr;
   a.rows = rows; a.cols = cols; a.ld = ld; a.capacity = capacity;
-  return bf16 ? launch_rows<BF16, true>(a, s) : launch_rows<F32, true>(a, s);
+  const int rc = bf16 ? launch_rows<BF16, true>(a, s) : launch_rows<F32, true>(a, s);
+  return rc ? rc : (ordered ? 0 : 1);
 }
 
 int fp4_launch_quantize_cols(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,

@@ -187,7 +187,8 @@ def _check_occ(x: torch.Tensor, dtype: str, alpha: float):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("shape,alpha", [((256, 512), 0.99), ((100, 72), 0.97), ((64, 4096), 0.999),
-                                          ((9, 2056), 0.99), ((300, 640), 1.0), ((2, 20000), 0.95)])
+                                          ((9, 2056), 0.99), ((300, 640), 1.0), ((2, 20000), 0.95),
+                                          ((5, 6000), 0.98), ((3, 12000), 0.99), ((130, 11008), 0.99)])
 def test_occ_clamp_residual_bit_exact(shape, alpha, dtype):
     cfg = synth.CONFIGS["c1"]
     x = synth.make_activation(cfg, shape[0], shape[1], salt=shape[0])
