@@ -11,6 +11,8 @@ struct BF16 {};
 struct F32 {};
 
 constexpr int SEL_BINS = 2048;  // 11-bit digits
+constexpr int SEL_THREADS = 1024;   // per workgroup: the 64 KiB of LDS tables allow two workgroups per CU,
+                                    // so their size decides how many loads a CU has in flight
 
 // Selection state kept in the workspace between passes.
 struct SelState {
@@ -42,11 +44,11 @@ FP4_D uint32_t key_of(uint32_t raw) {   // raw: bf16 bits (low 16) or fp32 bits
 }
 
 template <class DT>
-__global__ __launch_bounds__(256) void sel_hist_kernel(const void* x, int64_t rows, int64_t cols,
+__global__ __launch_bounds__(SEL_THREADS) void sel_hist_kernel(const void* x, int64_t rows, int64_t cols,
                                                        int64_t ld, int shift, int bits, int first,
                                                        const SelState* st, unsigned long long* hist) {
   __shared__ uint32_t h[8 * SEL_BINS];   // first pass: 8 replicas; later: 4 replicas x 2 targets
-  for (int i = threadIdx.x; i < 8 * SEL_BINS; i += 256) h[i] = 0;
+  for (int i = threadIdx.x; i < 8 * SEL_BINS; i += SEL_THREADS) h[i] = 0;
   __syncthreads();
   const uint32_t mask = (1u << bits) - 1u;
   const uint32_t p0 = st->prefix[0], p1 = st->prefix[1];
@@ -79,8 +81,8 @@ __global__ __launch_bounds__(256) void sel_hist_kernel(const void* x, int64_t ro
     };
     // four loads in flight per lane: with the LDS tables limiting a CU to two workgroups, one
     // load at a time leaves the memory pipe mostly idle
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * SEL_THREADS;
+    int64_t i = (int64_t)blockIdx.x * SEL_THREADS + threadIdx.x;
     for (; i + 3 * stride < nvec; i += 4 * stride) {
       const u32x4 r0 = xv[i], r1 = xv[i + stride], r2 = xv[i + 2 * stride], r3 = xv[i + 3 * stride];
       visit_vec(r0); visit_vec(r1); visit_vec(r2); visit_vec(r3);
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(256) void sel_hist_kernel(const void* x, int64_t ro
     for (; i < nvec; i += stride) visit_vec(xv[i]);
   } else {
     const int64_t n = rows * cols;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    for (int64_t i = (int64_t)blockIdx.x * SEL_THREADS + threadIdx.x; i < n; i += (int64_t)gridDim.x * SEL_THREADS) {
       const int64_t r = i / cols, c = i - r * cols;
       if constexpr (__is_same(DT, BF16)) visit(reinterpret_cast<const uint16_t*>(x)[r * ld + c]);
       else visit(reinterpret_cast<const uint32_t*>(x)[r * ld + c]);
@@ -96,14 +98,14 @@ __global__ __launch_bounds__(256) void sel_hist_kernel(const void* x, int64_t ro
   }
   __syncthreads();
   if (first) {
-    for (int i = threadIdx.x; i < SEL_BINS; i += 256) {
+    for (int i = threadIdx.x; i < SEL_BINS; i += SEL_THREADS) {
       uint32_t v = 0;
 #pragma unroll
       for (int r = 0; r < 8; ++r) v += h[r * SEL_BINS + i];
       if (v) atomicAdd(&hist[i], (unsigned long long)v);
     }
   } else {
-    for (int i = threadIdx.x; i < 2 * SEL_BINS; i += 256) {
+    for (int i = threadIdx.x; i < 2 * SEL_BINS; i += SEL_THREADS) {
       uint32_t v = 0;
 #pragma unroll
       for (int r = 0; r < 4; ++r) v += h[r * 2 * SEL_BINS + i];
@@ -238,14 +240,15 @@ int fp4_launch_thresholds(const void* x, int bf16, int64_t rows, int64_t cols, i
   if (bf16) { digits[0] = 11; digits[1] = 5; nd = 2; }
   else { digits[0] = 11; digits[1] = 11; digits[2] = 10; nd = 3; }
   int shift = key_bits;
-  const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + 256 * 64 - 1) / (256 * 64), 1024));
+  const unsigned grid =
+      (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + SEL_THREADS * 64 - 1) / (SEL_THREADS * 64), 512));
   for (int p = 0; p < nd; ++p) {
     shift -= digits[p];
     if (bf16)
-      hipLaunchKernelGGL((sel_hist_kernel<BF16>), dim3(grid), dim3(256), 0, s, x, rows, cols, ld, shift,
+      hipLaunchKernelGGL((sel_hist_kernel<BF16>), dim3(grid), dim3(SEL_THREADS), 0, s, x, rows, cols, ld, shift,
                          digits[p], p == 0, st, hist);
     else
-      hipLaunchKernelGGL((sel_hist_kernel<F32>), dim3(grid), dim3(256), 0, s, x, rows, cols, ld, shift,
+      hipLaunchKernelGGL((sel_hist_kernel<F32>), dim3(grid), dim3(SEL_THREADS), 0, s, x, rows, cols, ld, shift,
                          digits[p], p == 0, st, hist);
     hipLaunchKernelGGL(sel_pick_kernel, dim3(1), dim3(256), 0, s, st, hist, digits[p], p == 0, p == nd - 1,
                        key_bits, thresholds);
