@@ -252,13 +252,14 @@ __global__ __launch_bounds__(1024) void find_long_rows_kernel(const int64_t* row
 // multiplied as a small dense matrix so that D is streamed once for all of them instead of once
 // per row: a workgroup takes LD_SLICE rows of D x 512 columns x LD_LB long rows, scatters those
 // rows' values for its slice into an LDS table V[slice row][long row] (zero where a row has no
-// entry), and every lane keeps LD_LB x 8 accumulators for its 8 columns while the four waves
+// entry), and every lane keeps LD_LB x 8 accumulators for its 8 columns while the eight waves
 // split the slice's rows.  Partial sums per slice go to a scratch array and are added in slice
 // order by a second kernel, so the result does not depend on scheduling.
 constexpr int LD_LB = 16;        // long rows per workgroup pass
 constexpr int LD_SLICE = 1024;   // rows of D per workgroup
 constexpr int LD_CAP = 32;       // long rows the dense path takes; the rest go row by row
 constexpr int LD_COLS = 512;     // columns per workgroup (64 lanes x 8)
+constexpr int LD_WAVES = 8;      // waves per workgroup; they split the slice's rows
 
 // Main loop and wave reduction of spmm_long_dense_kernel for NL accumulated long rows.
 template <class DT, int NL>
@@ -274,13 +275,13 @@ FP4_D void long_dense_body(float* V, const void* D, int64_t m0, int rows_here, i
   if (valid > 0) {
     constexpr int UN = NL <= 8 ? 4 : 2;   // rows in flight per wave
     int r = wave;
-    for (; r + 4 * (UN - 1) < rows_here; r += 4 * UN) {
+    for (; r + LD_WAVES * (UN - 1) < rows_here; r += LD_WAVES * UN) {
       float d[UN][8];
 #pragma unroll
-      for (int u = 0; u < UN; ++u) load8g<DT>(D, (m0 + r + 4 * u) * N + col, valid, d[u]);
+      for (int u = 0; u < UN; ++u) load8g<DT>(D, (m0 + r + LD_WAVES * u) * N + col, valid, d[u]);
 #pragma unroll
       for (int u = 0; u < UN; ++u) {
-        const f32x4* vr = reinterpret_cast<const f32x4*>(&V[(r + 4 * u) * LD_LB]);
+        const f32x4* vr = reinterpret_cast<const f32x4*>(&V[(r + LD_WAVES * u) * LD_LB]);
 #pragma unroll
         for (int q = 0; q < NL / 4; ++q) {
           const f32x4 v4 = vr[q];   // same address in every lane: an LDS broadcast
@@ -292,7 +293,7 @@ FP4_D void long_dense_body(float* V, const void* D, int64_t m0, int rows_here, i
         }
       }
     }
-    for (; r < rows_here; r += 4) {
+    for (; r < rows_here; r += LD_WAVES) {
       float d[8];
       load8g<DT>(D, (m0 + r) * N + col, valid, d);
       const f32x4* vr = reinterpret_cast<const f32x4*>(&V[r * LD_LB]);
@@ -307,37 +308,35 @@ FP4_D void long_dense_body(float* V, const void* D, int64_t m0, int rows_here, i
       }
     }
   }
-  // add the four waves' sums, four long rows at a time, in wave order
-  float* red = V;   // [4 waves][4 rows][512 columns]
+  // add the waves' sums, two long rows at a time, in wave order
+  float* red = V;   // [LD_WAVES][2 rows][512 columns] = the table's 64 KiB
+  static_assert(LD_WAVES * 2 * LD_COLS <= LD_SLICE * LD_LB, "reduction buffer fits the table");
 #pragma unroll
-  for (int q = 0; q < NL / 4; ++q) {
+  for (int q = 0; q < NL / 2; ++q) {
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float* dst = red + ((wave * 4 + i) * LD_COLS + lane * 8);
-      *reinterpret_cast<f32x4*>(dst) = f32x4{acc[q * 4 + i][0], acc[q * 4 + i][1], acc[q * 4 + i][2], acc[q * 4 + i][3]};
-      *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[q * 4 + i][4], acc[q * 4 + i][5], acc[q * 4 + i][6], acc[q * 4 + i][7]};
+    for (int i = 0; i < 2; ++i) {
+      float* dst = red + ((wave * 2 + i) * LD_COLS + lane * 8);
+      *reinterpret_cast<f32x4*>(dst) = f32x4{acc[q * 2 + i][0], acc[q * 2 + i][1], acc[q * 2 + i][2], acc[q * 2 + i][3]};
+      *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[q * 2 + i][4], acc[q * 2 + i][5], acc[q * 2 + i][6], acc[q * 2 + i][7]};
     }
     __syncthreads();
-    const int i = tid >> 6;   // long row of this quarter summed by this thread
-    if (q * 4 + i < nl && valid > 0) {
-      float sum[8];
+    // 2 rows x 512 columns = 1024 sums: two per thread
+    for (int t2 = tid; t2 < 2 * LD_COLS; t2 += LD_WAVES * 64) {
+      const int ri = t2 / LD_COLS, c = t2 % LD_COLS;
+      const int64_t gcol = (int64_t)blockIdx.x * LD_COLS + c;
+      if (q * 2 + ri < nl && gcol < N) {
+        float sum = 0.0f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) sum[e] = 0.0f;
-#pragma unroll
-      for (int w = 0; w < 4; ++w)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) sum[e] += red[(w * 4 + i) * LD_COLS + lane * 8 + e];
-      float* o = pout + (int64_t)(q * 4 + i) * N + col;
-#pragma unroll
-      for (int e = 0; e < 8; ++e)
-        if (e < valid) o[e] = sum[e];
+        for (int w = 0; w < LD_WAVES; ++w) sum += red[(w * 2 + ri) * LD_COLS + c];
+        pout[(int64_t)(q * 2 + ri) * N + gcol] = sum;
+      }
     }
   }
 }
 
 template <class DT>
-__global__ __launch_bounds__(256) void spmm_long_dense_kernel(const int64_t* row_ptr, const int32_t* col_idx,
+__global__ __launch_bounds__(LD_WAVES * 64) void spmm_long_dense_kernel(const int64_t* row_ptr, const int32_t* col_idx,
                                                               const float* val, int64_t capacity,
                                                               const int32_t* list, const int32_t* count,
                                                               const void* D, int64_t Q, int64_t N, float* part) {
@@ -349,9 +348,9 @@ __global__ __launch_bounds__(256) void spmm_long_dense_kernel(const int64_t* row
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t m0 = (int64_t)blockIdx.y * LD_SLICE;
   const int rows_here = (int)min((int64_t)LD_SLICE, Q - m0);
-  for (int i = tid; i < LD_SLICE * LD_LB; i += 256) V[i] = 0.0f;
+  for (int i = tid; i < LD_SLICE * LD_LB; i += LD_WAVES * 64) V[i] = 0.0f;
   __syncthreads();
-  for (int l = wave; l < nl; l += 4) {
+  for (int l = wave; l < nl; l += LD_WAVES) {
     const int64_t row = list[g0 + l];
     int64_t lo = row_ptr[row];
     const int64_t en = min(row_ptr[row + 1], capacity);
@@ -666,10 +665,10 @@ int fp4_launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float*
     hipLaunchKernelGGL(find_long_rows_kernel, dim3(1), dim3(1024), 0, s, row_ptr, P, capacity, list, count, list_cap);
     const dim3 dgrid((unsigned)((N + LD_COLS - 1) / LD_COLS), (unsigned)slices, LD_CAP / LD_LB);
     if (bf16)
-      hipLaunchKernelGGL((spmm_long_dense_kernel<BF16>), dgrid, dim3(256), 0, s, row_ptr, col_idx, val, capacity, list,
+      hipLaunchKernelGGL((spmm_long_dense_kernel<BF16>), dgrid, dim3(LD_WAVES * 64), 0, s, row_ptr, col_idx, val, capacity, list,
                          count, D, Q, N, part);
     else
-      hipLaunchKernelGGL((spmm_long_dense_kernel<F32>), dgrid, dim3(256), 0, s, row_ptr, col_idx, val, capacity, list,
+      hipLaunchKernelGGL((spmm_long_dense_kernel<F32>), dgrid, dim3(LD_WAVES * 64), 0, s, row_ptr, col_idx, val, capacity, list,
                          count, D, Q, N, part);
     hipLaunchKernelGGL(spmm_long_reduce_kernel, dim3((unsigned)((N + 255) / 256), LD_CAP), dim3(256), 0, s, list, count,
                        part, slices, N, R);
