@@ -271,21 +271,42 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
     const long long base = row_ok ? a.row_ptr[row] : 0;
     emit = row_ok && (a.row_ptr[row + 1] <= a.capacity);
     if constexpr (CACHED) {
+      // the scans run on three counts per register, 10 bits each (a wave's sum is at most 512)
+      constexpr int NP = (NV + 2) / 3;
+      uint32_t pk[NP], inc[NP];
+#pragma unroll
+      for (int q = 0; q < NP; ++q) {
+        pk[q] = 0;
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+          if (3 * q + j < NV) pk[q] |= ((cpk >> (4 * (3 * q + j))) & 15u) << (10 * j);
+        inc[q] = pk[q];
+      }
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+#pragma unroll
+        for (int q = 0; q < NP; ++q) {
+          const uint32_t n = (uint32_t)__shfl_up((int)inc[q], o, 64);
+          if (lane >= o) inc[q] += n;
+        }
+      }
       int excl_u[NV];
 #pragma unroll
-      for (int u = 0; u < NV; ++u) {
-        const int cu = (int)((cpk >> (4 * u)) & 15u);
-        int incl = cu;
+      for (int q = 0; q < NP; ++q) {
+        const uint32_t ex = inc[q] - pk[q];
+        const uint32_t tot = (uint32_t)__shfl((int)inc[q], 63, 64);
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-          int n = __shfl_up(incl, o, 64);
-          if (lane >= o) incl += n;
-        }
-        excl_u[u] = incl - cu;
-        if (TPR == 256) {
-          if (lane == 63) s_round[u][wave] = incl;
-        } else {
-          excl_u[u] |= __shfl(incl, 63, 64) << 16;   // the round's total rides in the high half
+        for (int j = 0; j < 3; ++j) {
+          const int u = 3 * q + j;
+          if (u < NV) {
+            excl_u[u] = (int)((ex >> (10 * j)) & 1023u);
+            const int wtot = (int)((tot >> (10 * j)) & 1023u);
+            if (TPR == 256) {
+              if (lane == 63) s_round[u][wave] = wtot;
+            } else {
+              excl_u[u] |= wtot << 16;   // the round's total rides in the high half
+            }
+          }
         }
       }
       if (TPR == 256) __syncthreads();
