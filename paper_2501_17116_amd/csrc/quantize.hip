@@ -6,7 +6,15 @@
 // 4-byte store of codes, so a wave reads 1 KiB (bf16) contiguous and writes 256 B contiguous.
 #include "fp4_common.h"
 
+#include <type_traits>
+
 namespace {
+
+template <class F>
+FP4_D void static_for4(F&& f) {
+  f(std::integral_constant<int, 0>{}); f(std::integral_constant<int, 1>{});
+  f(std::integral_constant<int, 2>{}); f(std::integral_constant<int, 3>{});
+}
 
 struct BF16 {};
 struct F32 {};
@@ -118,10 +126,10 @@ FP4_D float wave_max(float v) {
 }
 
 FP4_D uint32_t pack8(const float (&v)[8], float gamma) {
-  uint32_t w = 0;
+  float sc[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) w |= q_e2m1_code(__fmul_rn(v[e], gamma)) << (4 * e);
-  return w;
+  for (int e = 0; e < 8; ++e) sc[e] = __fmul_rn(v[e], gamma);
+  return q_e2m1_pack8(sc);
 }
 
 FP4_D void store_codes(uint8_t* dst, uint32_t w, int valid, bool word_ok) {
@@ -530,20 +538,31 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColArgs a) {
   uint32_t w[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) w[e] = 0;
+  // two rows at a time: the convert takes a pair and writes one byte (rows i, i + 1 of a column)
+  static_for4([&](auto ic) {
+    constexpr int i = decltype(ic)::value * 2;
+    float v0[8], v1[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
+    for (int e = 0; e < 8; ++e) { v0[e] = 0.0f; v1[e] = 0.0f; }
     const int64_t r = r0 + rg * 8 + i;
-    if (r < a.rows && valid > 0) {
-      float v[8];
-      load8<DT>(a.x, r * a.ld + col, valid, v);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float x = v[e];
-        if (CLAMP) x = x < lo ? lo : (x > hi ? hi : x);
-        w[e] |= q_e2m1_code(__fmul_rn(x, g[e])) << (4 * i);
-      }
+    if (valid > 0) {
+      if (r < a.rows) load8<DT>(a.x, r * a.ld + col, valid, v0);
+      if (r + 1 < a.rows) load8<DT>(a.x, (r + 1) * a.ld + col, valid, v1);
     }
-  }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float x0 = v0[e], x1 = v1[e];
+      if (CLAMP) {
+        x0 = x0 < lo ? lo : (x0 > hi ? hi : x0);
+        x1 = x1 < lo ? lo : (x1 > hi ? hi : x1);
+        if (r >= a.rows || e >= valid) x0 = 0.0f;       // nothing there: code 0, whatever the thresholds
+        if (r + 1 >= a.rows || e >= valid) x1 = 0.0f;
+      }
+      w[e] = FP4_CVT_PAIR(w[e], q_e2m1_prepare(__fmul_rn(x0, g[e])), q_e2m1_prepare(__fmul_rn(x1, g[e])), i / 2);
+    }
+  });
+#pragma unroll
+  for (int e = 0; e < 8; ++e) w[e] = q_e2m1_drop_zero_signs(w[e]);
 #pragma unroll
   for (int e = 0; e < 8; ++e) s_w[chunk * 8 + e][rg] = w[e];
   __syncthreads();
