@@ -180,6 +180,16 @@ int fp4_residual_spmm(const int64_t* row_ptr, const int32_t* col_idx, const floa
  * the CPU; lets the rounding be checked exhaustively without a GPU). */
 int fp4_host_round_codes(const float* x_host, int64_t n, uint8_t* codes_host);
 
+/* The rounding as the quantization kernels perform it on the device (App. A's rule carried out
+ * by the FP4 convert instruction, eight values per packed word): codes[i] = Q(x[i]), one code per
+ * byte, x and codes in DEVICE memory, n a multiple of 8.
+ * fp4_device_round_sweep: runs every one of the 2^32 fp32 bit patterns, in each of the eight
+ * positions of a packed word, through that routine and through the comparison chain that
+ * fp4_host_round_codes exposes, and ADDS the number of disagreements to *mismatches (device
+ * memory, 8 bytes, set it to 0 first).  About a second of GPU time. */
+int fp4_device_round_codes(const float* x, int64_t n, uint8_t* codes, void* stream);
+int fp4_device_round_sweep(unsigned long long* mismatches, void* stream);
+
 /* ---- ceilings measured on the part (for reading the rooflines; not part of the method) ----
  * fp4_probe_mfma: `workgroups` workgroups of 8 waves each run `iters` iterations of 8 FP4
  *   32x32x64 MFMAs per wave with operands taken from operand_bytes (device, >= 16 bytes): an

@@ -62,6 +62,8 @@ def lib() -> C.CDLL:
         L.fp4_dge_apply.argtypes = [vp, vp, i32, vp, i64, i64, f32, f32, vp, vp]
         L.fp4_residual_spmm.argtypes = [vp, vp, vp, i64, i64, vp, i32, i64, vp, vp, sz, vp]
         L.fp4_host_round_codes.argtypes = [vp, i64, vp]
+        L.fp4_device_round_codes.argtypes = [vp, i64, vp, vp]
+        L.fp4_device_round_sweep.argtypes = [vp, vp]
         L.fp4_probe_mfma.argtypes = [vp, i64, i32, i32, vp, vp]
         L.fp4_probe_mfma.restype = i32
         L.fp4_probe_copy.argtypes = [vp, vp, i64, vp]
@@ -72,7 +74,7 @@ def lib() -> C.CDLL:
         L.fp4_trace_gemm_end.restype = i32
         for name in ("fp4_quantize", "occ_clamp_residual", "fp4_linear_fwd", "fp4_linear_bwd_dgrad",
                      "fp4_linear_bwd_wgrad", "fp4_gemm", "fp4_unpack", "fp4_dge_apply", "fp4_residual_spmm",
-                     "fp4_host_round_codes"):
+                     "fp4_host_round_codes", "fp4_device_round_codes", "fp4_device_round_sweep"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -317,6 +319,24 @@ def fp4_host_round_codes(x_host):
     _check(lib().fp4_host_round_codes(x.ctypes.data_as(C.c_void_p), x.size, out.ctypes.data_as(C.c_void_p)),
            "fp4_host_round_codes")
     return out
+
+
+def fp4_device_round_codes(x):
+    """fp32 CUDA tensor (numel a multiple of 8) -> uint8 codes, through the quantization kernels' packing routine."""
+    import torch
+    assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()
+    out = torch.empty(x.shape, dtype=torch.uint8, device=x.device)
+    _check(lib().fp4_device_round_codes(x.data_ptr(), x.numel(), out.data_ptr(), _stream()), "fp4_device_round_codes")
+    return out
+
+
+def fp4_device_round_sweep(device="cuda:0") -> int:
+    """Number of fp32 bit patterns (times eight word positions) where the device's packing routine and its
+    comparison-chain routine disagree; 0 is the only acceptable result."""
+    import torch
+    cnt = torch.zeros(1, dtype=torch.int64, device=device)
+    _check(lib().fp4_device_round_sweep(cnt.data_ptr(), _stream()), "fp4_device_round_sweep")
+    return int(cnt.item())
 
 
 def fp4_trace_gemm_begin(max_launches: int) -> None:

@@ -723,6 +723,59 @@ extern "C" int fp4_dge_apply(const float* G, const void* W, fp4_dtype dt, const 
   return FP4_OK;
 }
 
+namespace {
+// codes of n values (n a multiple of 8), eight per thread, through the packing routine the
+// quantizers use; one code per output byte
+__global__ __launch_bounds__(256) void device_round_kernel(const float* x, int64_t n8, uint8_t* codes) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n8) return;
+  float v[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = x[8 * i + e];
+  const uint32_t w = q_e2m1_pack8(v);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) codes[8 * i + e] = (uint8_t)((w >> (4 * e)) & 15u);
+}
+
+// every fp32 bit pattern, in every position of the packed word, against the comparison-chain
+// routine (which the host tests pin to the oracle)
+__global__ __launch_bounds__(256) void device_round_sweep_kernel(unsigned long long* mismatches) {
+  const uint32_t others[8] = {0u, 0xbfc00000u, 0x40a00000u, 0xbe800000u, 0x3e800000u, 0xc0a00000u, 0x7fc00000u, 0xffc00001u};
+  unsigned long long local = 0;
+  for (uint64_t b = (uint64_t)blockIdx.x * 256 + threadIdx.x; b < (1ull << 32); b += (uint64_t)gridDim.x * 256) {
+    for (int pos = 0; pos < 8; ++pos) {
+      float v[8];
+      uint32_t ref = 0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint32_t bits = (e == pos) ? (uint32_t)b : others[(e + pos + (b >> 8)) & 7];
+        v[e] = u2f(bits);
+        ref |= q_e2m1_code(v[e]) << (4 * e);
+      }
+      local += q_e2m1_pack8(v) != ref ? 1 : 0;
+    }
+  }
+  if (local) atomicAdd(mismatches, local);
+}
+}  // namespace
+
+extern "C" int fp4_device_round_codes(const float* x, int64_t n, uint8_t* codes, void* stream) {
+  if (n < 0 || (n % 8) != 0) return FP4_ERR_SHAPE;
+  if (n == 0) return FP4_OK;
+  if (!x || !codes) return FP4_ERR_NULL;
+  hipLaunchKernelGGL(device_round_kernel, dim3((unsigned)((n / 8 + 255) / 256)), dim3(256), 0, (hipStream_t)stream, x,
+                     n / 8, codes);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
+
+extern "C" int fp4_device_round_sweep(unsigned long long* mismatches, void* stream) {
+  if (!mismatches) return FP4_ERR_NULL;
+  hipLaunchKernelGGL(device_round_sweep_kernel, dim3(4096), dim3(256), 0, (hipStream_t)stream, mismatches);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
+
 extern "C" int fp4_host_round_codes(const float* x_host, int64_t n, uint8_t* codes_host) {
   if (n < 0) return FP4_ERR_SHAPE;
   if (n && (!x_host || !codes_host)) return FP4_ERR_NULL;

@@ -94,6 +94,37 @@ def test_quantize_ties_and_tiny_values_bit_exact():
 COL_SHAPES = [(256, 64), (300, 136), (1024, 512), (34, 8), (2, 2048), (514, 72)]
 
 
+def test_device_rounding_equals_the_oracle_bit_for_bit():
+    """The packing routine the quantization kernels use (FP4 convert instruction plus the tie correction)
+    against the oracle's App. A rounding: thresholds with their neighbours, specials, random bit patterns."""
+    rng = np.random.default_rng(5)
+    pts = [0.25, 0.5, 0.75, 1, 1.25, 1.5, 1.75, 2, 2.5, 3, 3.5, 4, 5, 6, 7, 0.0]
+    edge = []
+    for p in pts:
+        for sgn in (1, -1):
+            v = np.float32(sgn * p)
+            edge += [v, np.nextafter(v, np.float32(np.inf)), np.nextafter(v, np.float32(-np.inf))]
+    edge += [np.float32(x) for x in (np.inf, -np.inf, np.nan, 1e-45, -1e-45, 1e38, -1e38, -0.0)]
+    edge = np.array(edge + [np.float32(0)] * (-len(edge) % 8), np.float32)
+    base = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0], np.float32).view(np.uint32)
+    near = (base[:, None].astype(np.int64) + np.arange(-2000, 2000)[None, :]).astype(np.uint32).ravel()
+    sets = [edge, near.view(np.float32), (near | np.uint32(0x80000000)).view(np.float32),
+            rng.integers(0, 2 ** 32, 8_000_000, dtype=np.uint64).astype(np.uint32).view(np.float32),
+            rng.uniform(-7, 7, 8_000_000).astype(np.float32)]
+    for x in sets:
+        # each value also lands in every position of a packed word
+        for shift in (0, 3):
+            xs = np.roll(x, shift)
+            got = b.fp4_device_round_codes(torch.from_numpy(xs).cuda()).cpu().numpy()
+            assert np.array_equal(got, o.q_e2m1(xs))
+
+
+def test_device_rounding_routines_agree_on_every_bit_pattern():
+    """All 2^32 fp32 patterns in all eight word positions: packing routine == comparison-chain routine
+    (the latter is pinned to the oracle on the host, exhaustively near the thresholds)."""
+    assert b.fp4_device_round_sweep() == 0
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("shape", COL_SHAPES)
 def test_quantize_cols_bit_exact(shape, dtype):
