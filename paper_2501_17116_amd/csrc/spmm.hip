@@ -156,32 +156,54 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
     }
     __syncthreads();
     const int32_t k_end = (int32_t)min(k0 + SP_KS, Q);
-    while (cur < end) {
-      if (cur >= qb + 4) { qb = cur; load_quad(); }
-      const int sel = (int)(cur - qb);
-      const int32_t c = sel == 0 ? cq[0] : sel == 1 ? cq[1] : sel == 2 ? cq[2] : cq[3];
-      if (c >= k_end) break;
-      const float v = sel == 0 ? vq[0] : sel == 1 ? vq[1] : sel == 2 ? vq[2] : vq[3];
-      ++cur;
-      const float* dr = &slab[(c - (int32_t)k0) * SP_LD];
-      // SP_RIF chunk reads in flight before the first FMA that needs one
-      static_assert(SP_XM == 15 && SP_COLS == 64, "one chunk per swizzle constant");
+    // The quad in registers always starts at the row's next entry, so its four entries are taken
+    // with static indices and all lanes of a wave reload at the same point of the loop (one
+    // wait per four entries instead of one in most iterations).  A lane that meets the slab's
+    // end inside a quad fetches the quad at its new position right away: the request is in
+    // flight while the next slab is staged.
+    bool more = cur < end;
+    while (more) {
 #pragma unroll
-      for (int g0 = 0; g0 < 16; g0 += SP_RIF) {
+      for (int i = 0; i < 4; ++i) {
+        if (cur >= end || cq[i] >= k_end) { more = false; break; }
+        ++cur;
+        const float v = vq[i];
+        const float* dr = &slab[(cq[i] - (int32_t)k0) * SP_LD];
+        // A window of SP_RIF chunk reads stays in flight: chunk g's FMAs are followed by the read
+        // of chunk g + SP_RIF into the registers they freed, in exactly this order.
+        static_assert(SP_XM == 15 && SP_COLS == 64, "one chunk per swizzle constant");
+        auto chunk = [&](int g) {
+          return *reinterpret_cast<const f32x4*>(dr + ((g & 8) ? 32 - hi_off : hi_off) + xo[g & 7]);
+        };
         f32x4 d4[SP_RIF];
 #pragma unroll
-        for (int q = 0; q < SP_RIF; ++q)
-          d4[q] = *reinterpret_cast<const f32x4*>(dr + (((g0 + q) & 8) ? 32 - hi_off : hi_off) + xo[(g0 + q) & 7]);
+        for (int q = 0; q < SP_RIF; ++q) d4[q] = chunk(q);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int q = 0; q < SP_RIF; ++q) {
-          const int j = (g0 + q) * 4;
-          acc[j + 0] = fmaf(v, d4[q].x, acc[j + 0]);
-          acc[j + 1] = fmaf(v, d4[q].y, acc[j + 1]);
-          acc[j + 2] = fmaf(v, d4[q].z, acc[j + 2]);
-          acc[j + 3] = fmaf(v, d4[q].w, acc[j + 3]);
+        for (int g = 0; g < 16; ++g) {
+          const f32x4 d = d4[g % SP_RIF];
+          acc[4 * g + 0] = fmaf(v, d.x, acc[4 * g + 0]);
+          acc[4 * g + 1] = fmaf(v, d.y, acc[4 * g + 1]);
+          acc[4 * g + 2] = fmaf(v, d.z, acc[4 * g + 2]);
+          acc[4 * g + 3] = fmaf(v, d.w, acc[4 * g + 3]);
+          if (g + SP_RIF < 16) d4[g % SP_RIF] = chunk(g + SP_RIF);
+          __builtin_amdgcn_sched_barrier(0);
         }
+        // the sums are final here: the optimizer may not sink a step's FMAs into the block where
+        // the exits of all four steps meet (it did, and kept all 16 chunks alive across it)
+#pragma unroll
+        for (int j = 0; j < SP_COLS; j += 16)
+          asm volatile("" : "+v"(acc[j]), "+v"(acc[j + 1]), "+v"(acc[j + 2]), "+v"(acc[j + 3]), "+v"(acc[j + 4]),
+                            "+v"(acc[j + 5]), "+v"(acc[j + 6]), "+v"(acc[j + 7]), "+v"(acc[j + 8]), "+v"(acc[j + 9]),
+                            "+v"(acc[j + 10]), "+v"(acc[j + 11]), "+v"(acc[j + 12]), "+v"(acc[j + 13]),
+                            "+v"(acc[j + 14]), "+v"(acc[j + 15]));
+      }
+      if (more) {
+        if (cur < end) { qb = cur; load_quad(); }
+        else more = false;
       }
     }
+    if (cur < end && cur != qb) { qb = cur; load_quad(); }
   }
   // A lane's 64 sums belong to one row of R (lanes are N floats apart); they go through LDS once
   // more so that the stores run along rows: 16 lanes x 16 B per row, four rows per instruction.
