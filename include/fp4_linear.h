@@ -13,9 +13,15 @@
  *
  * Conventions common to every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller unless a parameter
- *     says "host".  Matrices are row-major.  The library allocates nothing, keeps no
+ *     says "host".  Matrices are row-major.  The library allocates no memory, keeps no
  *     state between calls and never synchronizes: every call only enqueues kernels on
- *     `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream).  To the
+ *     caller all work of a call is ordered on `stream`.  Inside, fp4_linear_fwd and
+ *     fp4_linear_bwd_wgrad run an independent part of their kernel chain on one extra
+ *     stream per device (created at first use, default priority, kept until the process
+ *     ends), forked from and joined back into `stream` with events, which is also valid
+ *     under stream capture.  Setting the environment variable FP4_SINGLE_STREAM (any
+ *     value, read once) keeps everything on `stream`.
  *   - Return value: FP4_OK (0) or a negative fp4_status.  Arguments are validated on
  *     the host before anything is enqueued; on error nothing has been enqueued, except
  *     FP4_ERR_HIP which reports a failed launch of the call's own kernels.

@@ -1,11 +1,14 @@
 // Host side of the C ABI: argument validation, workspace carving and the kernel sequences of
-// the three layer passes (Fig. 2; Sec. 3.1; Sec. 3.2; Sec. 4.1).  Nothing here allocates,
-// synchronizes or keeps state; every buffer is the caller's.
+// the three layer passes (Fig. 2; Sec. 3.1; Sec. 3.2; Sec. 4.1).  Nothing here allocates device
+// memory or synchronizes; every buffer is the caller's.  The only state is one extra stream per
+// device (see Fork), created on first use.
 #include "fp4_common.h"
 
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <limits>
+#include <mutex>
 
 // launchers defined next to their kernels
 int fp4_launch_gemm(const uint8_t* L, const float* gl, const uint8_t* Rt, const float* gr, int64_t P,
@@ -63,6 +66,49 @@ struct Carver {
     off += align_up(count * sizeof(T), 256);
     return r;
   }
+};
+
+// A second stream per device for kernel chains that do not depend on each other (short,
+// latency-bound index kernels beside bandwidth-bound quantization passes).  Fork: the side stream
+// waits for everything enqueued on the caller's stream so far; join: the caller's stream waits
+// for the side stream.  The caller sees one stream; if the side stream or an event cannot be
+// had, everything simply stays on the caller's stream.  Default priority, non-blocking.
+class Fork {
+ public:
+  explicit Fork(hipStream_t main, bool wanted) : main_(main) {
+    if (!wanted || disabled()) return;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return;
+    {
+      std::lock_guard<std::mutex> lock(mu());
+      hipStream_t& st = streams()[dev];
+      if (!st && hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) { st = nullptr; return; }
+      side_ = st;
+    }
+    hipEvent_t ev;
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { side_ = nullptr; return; }
+    const bool ok = hipEventRecord(ev, main_) == hipSuccess && hipStreamWaitEvent(side_, ev, 0) == hipSuccess;
+    (void)hipEventDestroy(ev);   // released once it has completed
+    if (!ok) side_ = nullptr;
+  }
+  hipStream_t side() const { return side_ ? side_ : main_; }
+  int join() {
+    if (!side_) return FP4_OK;
+    hipEvent_t ev;
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) return FP4_ERR_HIP;
+    const bool ok = hipEventRecord(ev, side_) == hipSuccess && hipStreamWaitEvent(main_, ev, 0) == hipSuccess;
+    (void)hipEventDestroy(ev);
+    side_ = nullptr;
+    return ok ? FP4_OK : FP4_ERR_HIP;
+  }
+
+ private:
+  static constexpr int kMaxDev = 64;
+  static std::mutex& mu() { static std::mutex m; return m; }
+  static hipStream_t* streams() { static hipStream_t st[kMaxDev] = {}; return st; }
+  static bool disabled() { static const bool d = std::getenv("FP4_SINGLE_STREAM") != nullptr; return d; }
+  hipStream_t main_;
+  hipStream_t side_ = nullptr;
 };
 
 inline bool dtype_ok(fp4_dtype dt) { return dt == FP4_F32 || dt == FP4_BF16; }
@@ -233,18 +279,21 @@ extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_
   Carver c(reinterpret_cast<void*>(align_up((size_t)(uintptr_t)workspace, 256)));
   FwdWs w = carve_fwd(c, M, K, N, dt);
 
-  // W per output channel -> codes [N x K/2], scales kept for the DGE term of the backward pass
-  int rc = fp4_launch_quantize_cols(W, bf16, K, N, N, nullptr, w.qWt, saved->gamma_W, w.amax, s);
-  if (rc) return rc;
+  // W per output channel -> codes [N x K/2], scales kept for the DGE term of the backward pass;
+  // beside the chain that prepares A (nothing of it touches qWt, gamma_W or amax)
+  Fork fork(s, occ);
+  int rc = fp4_launch_quantize_cols(W, bf16, K, N, N, nullptr, w.qWt, saved->gamma_W, w.amax, fork.side());
+  if (rc) { (void)fork.join(); return rc; }
+  auto joined = [&](int code) { const int j = fork.join(); return code ? code : j; };
   const float* addend = nullptr;
   if (occ) {
     const int64_t cap = std::min(saved->capacity, 2 * tail_count(M * K, 0.9));  // never beyond the temporaries
     rc = fp4_launch_thresholds(A, bf16, M, K, K, k, saved->thresholds, w.occ.select, w.occ.total, s);
-    if (rc) return rc;
+    if (rc) return joined(rc);
     rc = fp4_launch_occ_count(A, bf16, M, K, K, saved->thresholds, w.occ.row_cnt, s);
-    if (rc) return rc;
+    if (rc) return joined(rc);
     rc = fp4_launch_scan_rows(w.occ.row_cnt, M, saved->row_ptr, saved->nnz, s);
-    if (rc) return rc;
+    if (rc) return joined(rc);
     rc = fp4_launch_occ_rows(A, bf16, M, K, K, saved->thresholds, w.qA, w.gA, nullptr, saved->col_idx, saved->val,
                              w.occ.tmp_col, w.occ.tmp_val, saved->row_ptr, cap, s);
     if (rc == 1) {   // streamed rows: entries unordered in the temporaries
@@ -252,22 +301,24 @@ extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_
       if (rc == 1)
         rc = fp4_launch_csr_gather(w.occ.tmp_col, w.occ.tmp_val, M, cap, saved->row_ptr, saved->col_idx, saved->val, s);
     }
-    if (rc) return rc;
+    if (rc) return joined(rc);
     // Delta_A W with the unquantized W, fp32; lands where the GEMM epilogue picks it up
     float* R = bf16 ? w.R : reinterpret_cast<float*>(Y);
     rc = fp4_launch_spmm(saved->row_ptr, saved->col_idx, saved->val, cap, M, K, W, bf16, N, R, w.sp_scratch,
                          fp4_spmm_long_list_cap(2 * tail_count(M * K, 0.9)), s);
-    if (rc) return rc;
+    if (rc) return joined(rc);
     addend = R;
   } else {
     rc = fp4_launch_quantize_rows(A, bf16, M, K, K, w.qA, w.gA, s);
-    if (rc) return rc;
+    if (rc) return joined(rc);
     if (saved->thresholds || saved->row_ptr || saved->nnz) {
       hipLaunchKernelGGL(init_no_occ_kernel, dim3((unsigned)((M + 1 + 255) / 256)), dim3(256), 0, s,
                          saved->thresholds, saved->row_ptr, M, saved->nnz);
-      FP4_CHECK_LAUNCH();
+      if (hipGetLastError() != hipSuccess) return joined(FP4_ERR_HIP);
     }
   }
+  rc = joined(FP4_OK);
+  if (rc) return rc;
   return fp4_launch_gemm(w.qA, w.gA, w.qWt, saved->gamma_W, M, N, K, addend, Y, bf16, N, nullptr, 0, 0,
                          nullptr, 0.0f, 0.0f, s);
 }
@@ -311,15 +362,20 @@ extern "C" int fp4_linear_bwd_wgrad(const void* A, const void* dY, const void* W
   Carver c(reinterpret_cast<void*>(align_up((size_t)(uintptr_t)workspace, 256)));
   WgradWs w = carve_wgrad(c, M, K, N);
   // A_c per input channel (codes [K x M/2]); dY per output channel (codes [N x M/2])
-  int rc = fp4_launch_quantize_cols(A, bf16, M, K, K, occ ? saved->thresholds : nullptr, w.qAt, w.gAk, w.amax, s);
+  // The transposition of the saved residual (short index kernels, own buffers) runs beside the
+  // two quantization passes.
+  Fork fork(s, occ);
+  int rc = FP4_OK;
+  if (occ)
+    rc = fp4_launch_csr_transpose(saved->row_ptr, saved->col_idx, saved->val, saved->nnz, M, K, saved->capacity,
+                                  w.t_ptr, w.t_idx, w.t_val, w.u_idx, w.u_val, w.t_scratch, fork.side());
+  if (!rc) rc = fp4_launch_quantize_cols(A, bf16, M, K, K, occ ? saved->thresholds : nullptr, w.qAt, w.gAk, w.amax, s);
+  if (!rc) rc = fp4_launch_quantize_cols(dY, bf16, M, N, N, nullptr, w.qdYt, w.gdYn, w.amax, s);
+  const int jrc = fork.join();
   if (rc) return rc;
-  rc = fp4_launch_quantize_cols(dY, bf16, M, N, N, nullptr, w.qdYt, w.gdYn, w.amax, s);
-  if (rc) return rc;
+  if (jrc) return jrc;
   const float* addend = nullptr;
   if (occ) {
-    rc = fp4_launch_csr_transpose(saved->row_ptr, saved->col_idx, saved->val, saved->nnz, M, K,
-                                  saved->capacity, w.t_ptr, w.t_idx, w.t_val, w.u_idx, w.u_val, w.t_scratch, s);
-    if (rc) return rc;
     rc = fp4_launch_spmm(w.t_ptr, w.t_idx, w.t_val, saved->capacity, K, M, dY, bf16, N, dW, w.sp_scratch,
                          fp4_spmm_long_list_cap(2 * tail_count(M * K, 0.9)), s);
     if (rc) return rc;
