@@ -139,18 +139,41 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
   for (int j = 0; j < 8; ++j) xo[j] = (j ^ (swz & 7)) * 4;
   const int hi_off = (swz >> 3) * 32;
 
+  // bf16 D: a wave requests its share of the next slab as soon as its own rows are done with the
+  // current one (the registers of the read window are free then), so the round trip runs while
+  // the slower waves finish instead of after the barrier.
+  constexpr bool EARLY = __is_same(DT, BF16);
+  [[maybe_unused]] u32x4 nxt[SP_KS / SP_RPP];
+  [[maybe_unused]] auto fetch_next = [&](int64_t k0n) {
+#pragma unroll
+    for (int ps = 0; ps < SP_KS / SP_RPP; ++ps) {
+      const int64_t r = k0n + ps * SP_RPP + s_row;
+      nxt[ps] = u32x4{0u, 0u, 0u, 0u};
+      if (r < Q && s_valid >= 8) nxt[ps] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(D) + r * N + s_col);
+    }
+  };
+  if constexpr (EARLY) fetch_next(0);
+
   for (int64_t k0 = 0; k0 < Q; k0 += SP_KS) {
     __syncthreads();
 #pragma unroll
     for (int ps = 0; ps < SP_KS / SP_RPP; ++ps) {
       const int r = ps * SP_RPP + s_row;
-      float d[8];
-      if (k0 + r < Q && s_valid > 0) load8g<DT>(D, (k0 + r) * N + s_col, s_valid, d);
-      else {
+      f32x4 a, b;
+      if constexpr (EARLY) {
+        const u32x4 u = nxt[ps];
+        a = f32x4{u2f(u.x << 16), u2f(u.x & 0xffff0000u), u2f(u.y << 16), u2f(u.y & 0xffff0000u)};
+        b = f32x4{u2f(u.z << 16), u2f(u.z & 0xffff0000u), u2f(u.w << 16), u2f(u.w & 0xffff0000u)};
+      } else {
+        float d[8];
+        if (k0 + r < Q && s_valid > 0) load8g<DT>(D, (k0 + r) * N + s_col, s_valid, d);
+        else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) d[e] = 0.0f;
+          for (int e = 0; e < 8; ++e) d[e] = 0.0f;
+        }
+        a = f32x4{d[0], d[1], d[2], d[3]};
+        b = f32x4{d[4], d[5], d[6], d[7]};
       }
-      f32x4 a = {d[0], d[1], d[2], d[3]}, b = {d[4], d[5], d[6], d[7]};
       *reinterpret_cast<f32x4*>(&slab[r * SP_LD + s_unit * 8]) = a;
       *reinterpret_cast<f32x4*>(&slab[r * SP_LD + s_unit * 8 + 4]) = b;
     }
@@ -204,6 +227,9 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
       }
     }
     if (cur < end && cur != qb) { qb = cur; load_quad(); }
+    if constexpr (EARLY) {
+      if (k0 + SP_KS < Q) fetch_next(k0 + SP_KS);
+    }
   }
   // A lane's 64 sums belong to one row of R (lanes are N floats apart); they go through LDS once
   // more so that the stores run along rows: 16 lanes x 16 B per row, four rows per instruction.
