@@ -67,7 +67,7 @@ def cpu_baseline(cfg):
     except Exception:
         cores = 1
     l = min(cfg.layers, key=lambda s: s.K * s.N)
-    Ms = min(l.M, 2048)   # about 10-20 s of oracle work on the host cores
+    Ms = min(l.M, 8192)   # 10-20 s of oracle work on the GPU machine's 16 host threads
     A, W, dY = synth.make_layer(cfg, l, M=Ms)
     A, W, dY = A.numpy(), W.numpy(), dY.numpy()
     t0 = time.perf_counter()
