@@ -376,3 +376,48 @@ def test_forward_is_deterministic_and_keeps_guard_bands():
     Y2, _ = b.fp4_linear_fwd(Ad, Wd, 0.99)
     assert torch.equal(Y1, Y2)
     assert torch.all(buf[0] == 7.0) and torch.all(buf[-1] == 7.0)
+
+
+def _layer_once(Ad, Wd, dYd, alpha, ctx=None, Y=None, dW=None, ws=None):
+    Y, ctx = b.fp4_linear_fwd(Ad, Wd, alpha, ctx=ctx, Y=Y, ws=ws)
+    dW = b.fp4_linear_bwd_wgrad(Ad, dYd, Wd, ctx, dW=dW, ws=ws)
+    return Y, dW
+
+
+def test_layer_on_a_user_stream_equals_the_default_stream():
+    """Forward and weight gradient fork part of their work to the library's second stream and join it
+    back: on a stream of the caller's the results must be the ones of the default stream, bit for bit."""
+    A, W, dY = synth.small_case(384, 512, 264, "bf16", seed=4)
+    Ad, Wd, dYd = dev(A, "bf16"), dev(W, "bf16"), dev(dY, "bf16")
+    Y0, dW0 = _layer_once(Ad, Wd, dYd, 0.98)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        for _ in range(3):   # back to back: every call's fork must wait for the call before it
+            Y1, dW1 = _layer_once(Ad, Wd, dYd, 0.98)
+    s.synchronize()
+    assert torch.equal(Y0, Y1) and torch.equal(dW0, dW1)
+
+
+def test_layer_in_a_captured_graph_equals_eager_on_every_replay():
+    A, W, dY = synth.small_case(256, 512, 264, "bf16", seed=6)
+    Ad, Wd, dYd = dev(A, "bf16"), dev(W, "bf16"), dev(dY, "bf16")
+    M, K = Ad.shape
+    N = Wd.shape[1]
+    ctx = b.FwdCtx(M, K, N, 0.98, Ad.device)
+    ws = b.Workspace()
+    Yg = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    dWg = torch.empty((K, N), dtype=torch.float32, device="cuda")
+    _layer_once(Ad, Wd, dYd, 0.98, ctx=ctx, Y=Yg, dW=dWg, ws=ws)   # sizes the workspace, creates the second stream
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        _layer_once(Ad, Wd, dYd, 0.98, ctx=ctx, Y=Yg, dW=dWg, ws=ws)
+    gen = torch.Generator(device="cuda").manual_seed(9)
+    for rep in range(3):
+        Ad.copy_((torch.randn(M, K, generator=gen, device="cuda") * (1 + rep)).bfloat16())
+        g.replay()
+        torch.cuda.synchronize()
+        Ye, dWe = _layer_once(Ad, Wd, dYd, 0.98)   # eager, own buffers
+        torch.cuda.synchronize()
+        assert torch.equal(Yg, Ye) and torch.equal(dWg, dWe), "replay %d" % rep
