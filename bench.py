@@ -147,7 +147,10 @@ def kernel_report(cfg, layers, b, torch, ws):
     R = torch.empty(l.M, l.N, device="cuda", dtype=torch.float32)
     t = _time(lambda: b.fp4_residual_spmm(L["ctx"].row_ptr, L["ctx"].col_idx, L["ctx"].val, l.K, L["W"], R=R, ws=ws),
               torch)
-    rep["residual_spmm(fwd)"] = {"nnz": nnz, "us": t * 1e6, "GFLOP/s": 2.0 * nnz * l.N / t / 1e9}
+    # bound by the vector ALUs (fp32 FMAs): against the published fp32 vector peak, which counts
+    # packed FMAs the kernel does not use (one FMA per lane and cycle is half of it)
+    rep["residual_spmm(fwd)"] = {"nnz": nnz, "us": t * 1e6, "GFLOP/s": 2.0 * nnz * l.N / t / 1e9, "bound": "alu",
+                                 "frac_of_fp32_vector_peak": 2.0 * nnz * l.N / t / 157.3e12}
     del R
     # what the fused pieces cost: forward with and without the outlier residual, weight gradient
     # with the DGE factor and with the straight-through estimator (dge_k = 0)
