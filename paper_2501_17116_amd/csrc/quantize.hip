@@ -605,29 +605,53 @@ int launch_cols(const ColArgs& a, hipStream_t s) {
 // ------------------------------------------------------------------------------------------
 // Stand-alone DGE pass: dW = G * min(cap, f'(W gamma_W))   (Sec. 3.1 Eq. 8; App. C.2 Eq. 22)
 // ------------------------------------------------------------------------------------------
+// A thread owns four columns (one 16-byte unit of G and dW) and walks rows four at a time with all
+// their loads in flight; the four scales stay in registers.
+constexpr int DGE_RU = 4;
+
 template <class DT>
-__global__ void dge_apply_kernel(const float* G, const void* W, const float* gamma_w, int64_t K,
-                                 int64_t N, float inv_k, float cap, int ste, float* dW) {
-  const int64_t nunits = N / 8;  // N % 8 == 0 checked by the caller
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= K * nunits) return;
-  const int64_t r = i / nunits, u = i % nunits;
-  float w[8], gq[8];
-  load8<DT>(W, r * N + u * 8, 8, w);
-  load8<F32>(G, r * N + u * 8, 8, gq);
-  const float pw = inv_k - 1.0f;
+__global__ __launch_bounds__(256) void dge_apply_kernel(const float* G, const void* W, const float* gamma_w, int64_t K,
+                                                        int64_t N, float inv_k, float cap, int ste, float* dW) {   // G may be dW
+  const int64_t c = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;   // N % 8 == 0 checked by the caller
+  if (c >= N) return;
+  float gam[4];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    float a = fabsf(__fmul_rn(w[e], gamma_w[u * 8 + e]));
-    float l, s;
-    if (a < 2.0f) { l = 0.5f * floorf(a + a); s = 4.0f; }
-    else if (a < 4.0f) { l = floorf(a); s = 2.0f; }
-    else { l = 4.0f; s = 1.0f; }
-    float t = fabsf(s * (a - l) - 1.0f);
-    float f = fminf(inv_k * __builtin_amdgcn_exp2f(pw * __builtin_amdgcn_logf(t)), cap);
-    gq[e] *= ste ? 1.0f : f;
+  for (int e = 0; e < 4; ++e) gam[e] = gamma_w[c + e];
+  const float pw = inv_k - 1.0f;
+  for (int64_t r0 = (int64_t)blockIdx.y * DGE_RU; r0 < K; r0 += (int64_t)gridDim.y * DGE_RU) {
+    f32x4 g[DGE_RU];
+    float w[DGE_RU][4];
+#pragma unroll
+    for (int i = 0; i < DGE_RU; ++i) {
+      const int64_t off = min(r0 + i, K - 1) * N + c;   // rows past the end re-read the last one
+      g[i] = *reinterpret_cast<const f32x4*>(G + off);
+      if constexpr (__is_same(DT, BF16)) {
+        const uint2 u = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(W) + off);
+        w[i][0] = u2f(u.x << 16); w[i][1] = u2f(u.x & 0xffff0000u);
+        w[i][2] = u2f(u.y << 16); w[i][3] = u2f(u.y & 0xffff0000u);
+      } else {
+        const f32x4 u = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(W) + off);
+        w[i][0] = u.x; w[i][1] = u.y; w[i][2] = u.z; w[i][3] = u.w;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < DGE_RU; ++i) {
+      if (r0 + i >= K) break;
+      float gq[4] = {g[i].x, g[i].y, g[i].z, g[i].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float a = fabsf(__fmul_rn(w[i][e], gam[e]));
+        float l, s;
+        if (a < 2.0f) { l = 0.5f * floorf(a + a); s = 4.0f; }
+        else if (a < 4.0f) { l = floorf(a); s = 2.0f; }
+        else { l = 4.0f; s = 1.0f; }
+        float t = fabsf(s * (a - l) - 1.0f);
+        float f = fminf(inv_k * __builtin_amdgcn_exp2f(pw * __builtin_amdgcn_logf(t)), cap);
+        gq[e] *= ste ? 1.0f : f;
+      }
+      *reinterpret_cast<f32x4*>(dW + (r0 + i) * N + c) = f32x4{gq[0], gq[1], gq[2], gq[3]};
+    }
   }
-  store8<F32>(dW, r * N + u * 8, 8, gq);
 }
 
 }  // namespace
@@ -709,16 +733,16 @@ extern "C" int fp4_dge_apply(const float* G, const void* W, fp4_dtype dt, const 
   if (!G || !W || !gamma_W || !dW) return FP4_ERR_NULL;
   if (dge_cap <= 0.0f) return FP4_ERR_ARG;
   if (!aligned16(G) || !aligned16(W) || !aligned16(dW)) return FP4_ERR_ARG;
-  const int64_t n = K * (N / 8);
   const float inv_k = dge_k > 0.0f ? 1.0f / dge_k : 1.0f;
   const int ste = dge_k > 0.0f ? 0 : 1;  // k <= 0: straight-through estimator, f' = 1
   const float cap = dge_cap;
+  const dim3 grid((unsigned)((N / 4 + 255) / 256), (unsigned)std::min<int64_t>((K + DGE_RU - 1) / DGE_RU, 65535));
   if (dt == FP4_BF16)
-    hipLaunchKernelGGL((dge_apply_kernel<BF16>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
-                       (hipStream_t)stream, G, W, gamma_W, K, N, inv_k, cap, ste, dW);
+    hipLaunchKernelGGL((dge_apply_kernel<BF16>), grid, dim3(256), 0, (hipStream_t)stream, G, W, gamma_W, K, N, inv_k,
+                       cap, ste, dW);
   else
-    hipLaunchKernelGGL((dge_apply_kernel<F32>), dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
-                       (hipStream_t)stream, G, W, gamma_W, K, N, inv_k, cap, ste, dW);
+    hipLaunchKernelGGL((dge_apply_kernel<F32>), grid, dim3(256), 0, (hipStream_t)stream, G, W, gamma_W, K, N, inv_k,
+                       cap, ste, dW);
   FP4_CHECK_LAUNCH();
   return FP4_OK;
 }
