@@ -441,6 +441,8 @@ int launch_rows(const RowArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 64, 8>), dim3((unsigned)((a.rows + 3) / 4)), dim3(256), 0, s, a);
   } else if (nunits <= 256 * 4) {
     hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 256, 4>), dim3((unsigned)a.rows), dim3(256), 0, s, a);
+  } else if (nunits <= 256 * 6) {
+    hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 256, 6>), dim3((unsigned)a.rows), dim3(256), 0, s, a);
   } else if (nunits <= 256 * 8) {
     hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 256, 8>), dim3((unsigned)a.rows), dim3(256), 0, s, a);
   } else {
