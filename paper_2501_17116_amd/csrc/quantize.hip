@@ -437,6 +437,8 @@ int launch_rows(const RowArgs& a, hipStream_t s) {
   // one wave per row while the row fits 64 lanes x 8 units, else the whole workgroup
   if (nunits <= 64 * 2) {
     hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 64, 2>), dim3((unsigned)((a.rows + 3) / 4)), dim3(256), 0, s, a);
+  } else if (nunits <= 64 * 4) {
+    hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 64, 4>), dim3((unsigned)((a.rows + 3) / 4)), dim3(256), 0, s, a);
   } else if (nunits <= 64 * 8) {
     hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 64, 8>), dim3((unsigned)((a.rows + 3) / 4)), dim3(256), 0, s, a);
   } else if (nunits <= 256 * 4) {

@@ -44,7 +44,9 @@ def assert_close(got: torch.Tensor, ref: np.ndarray, out_dtype: str, what: str):
 # ------------------------------------------------------------------------------------------
 # quantization
 # ------------------------------------------------------------------------------------------
-ROW_SHAPES = [(7, 64), (16, 10), (33, 520), (64, 4096), (5, 9000), (3, 20000), (1, 2), (130, 1024)]
+# one shape at least for every variant of the row kernel (1 wave or 1 workgroup per row x units per thread)
+ROW_SHAPES = [(7, 64), (16, 10), (33, 520), (64, 4096), (5, 9000), (3, 20000), (1, 2), (130, 1024), (29, 2048),
+              (37, 1544), (6, 11008), (4, 14000)]
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -219,7 +221,8 @@ def _check_occ(x: torch.Tensor, dtype: str, alpha: float):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("shape,alpha", [((256, 512), 0.99), ((100, 72), 0.97), ((64, 4096), 0.999),
                                           ((9, 2056), 0.99), ((300, 640), 1.0), ((2, 20000), 0.95),
-                                          ((5, 6000), 0.98), ((3, 12000), 0.99), ((130, 11008), 0.99)])
+                                          ((5, 6000), 0.98), ((3, 12000), 0.99), ((130, 11008), 0.99),
+                                          ((37, 1544), 0.98), ((29, 2048), 0.99), ((4, 14000), 0.99)])
 def test_occ_clamp_residual_bit_exact(shape, alpha, dtype):
     cfg = synth.CONFIGS["c1"]
     x = synth.make_activation(cfg, shape[0], shape[1], salt=shape[0])
