@@ -10,6 +10,7 @@ namespace {
 struct BF16 {};
 struct F32 {};
 
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr int SEL_BINS = 2048;  // 11-bit digits
 constexpr int SEL_THREADS = 1024;   // per workgroup: the 64 KiB of LDS tables allow two workgroups per CU,
                                     // so their size decides how many loads a CU has in flight
@@ -119,25 +120,42 @@ __global__ __launch_bounds__(SEL_THREADS) void sel_hist_kernel(const void* x, in
 __global__ __launch_bounds__(256) void sel_pick_kernel(SelState* st, unsigned long long* hist, int bits,
                                                        int first, int last, int key_bits,
                                                        float* thresholds) {
-  __shared__ unsigned long long part[256];
+  constexpr int PER = SEL_BINS / 256;   // bins a thread owns when all SEL_BINS are in use
+  __shared__ unsigned long long s_w[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nb = 1 << bits;
   const int per = (nb + 255) / 256;
   for (int s = 0; s < 2; ++s) {
     const unsigned long long* hsrc = hist + (first ? 0 : s * SEL_BINS);
+    unsigned long long v[PER];
     unsigned long long sum = 0;
-    for (int j = 0; j < per; ++j) {
-      int b = threadIdx.x * per + j;
-      if (b < nb) sum += hsrc[b];
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const int b = tid * per + j;
+      v[j] = (j < per && b < nb) ? hsrc[b] : 0;
+      sum += v[j];
     }
-    part[threadIdx.x] = sum;
+    // inclusive prefix of the threads' sums: the thread whose range [excl, incl) holds the rank
+    // owns the bin (the last thread, should the rank lie beyond the total)
+    unsigned long long incl = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const unsigned long long up = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += up;
+    }
+    if (lane == 63) s_w[wave] = incl;
     __syncthreads();
-    if (threadIdx.x == 0) {
-      unsigned long long r = st->rank[s], cum = 0;
-      int t = 0;
-      while (t < 255 && cum + part[t] <= r) { cum += part[t]; ++t; }
-      int b = t * per;
-      const int bend = min(nb, b + per);
-      while (b < bend - 1 && cum + hsrc[b] <= r) { cum += hsrc[b]; ++b; }
+    for (int w = 0; w < wave; ++w) incl += s_w[w];
+    const unsigned long long r = st->rank[s];
+    const unsigned long long excl = incl - sum;
+    if ((excl <= r && r < incl) || (tid == 255 && r >= incl)) {
+      unsigned long long cum = excl;
+      int j = 0;
+      const int jend = min(per, nb - tid * per);   // bins of this thread that exist (may be <= 0)
+#pragma unroll
+      for (int q = 0; q < PER - 1; ++q)
+        if (j == q && q < jend - 1 && cum + v[q] <= r) { cum += v[q]; ++j; }
+      const int b = min(tid * per + j, nb - 1);
       st->rank[s] = r - cum;
       st->prefix[s] = (st->prefix[s] << bits) | (uint32_t)b;
       if (last) {
@@ -154,7 +172,7 @@ __global__ __launch_bounds__(256) void sel_pick_kernel(SelState* st, unsigned lo
     }
     __syncthreads();
   }
-  for (int i = threadIdx.x; i < 2 * SEL_BINS; i += 256) hist[i] = 0;
+  for (int i = tid; i < 2 * SEL_BINS; i += 256) hist[i] = 0;
 }
 
 // ---- CSR finalisation ---------------------------------------------------------------------
@@ -169,11 +187,22 @@ __global__ __launch_bounds__(1024) void scan_counts_kernel(const int32_t* cnt, i
   __syncthreads();
   for (int64_t base = 0; base < n; base += 16 * 1024) {
     const int64_t i0 = base + (int64_t)threadIdx.x * 16;
+    int32_t c[16];
+    if (i0 + 16 <= n) {   // 64 aligned bytes: four loads in flight instead of sixteen guarded ones in a row
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const i32x4 t = reinterpret_cast<const i32x4*>(cnt + i0)[q];
+        c[4 * q] = t.x; c[4 * q + 1] = t.y; c[4 * q + 2] = t.z; c[4 * q + 3] = t.w;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) c[j] = i0 + j < n ? cnt[i0 + j] : 0;
+    }
     long long v[16];
     long long sum = 0;
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
-      sum += i0 + j < n ? cnt[i0 + j] : 0;
+      sum += c[j];
       v[j] = sum;   // inclusive inside the thread
     }
     long long incl = sum;   // inclusive over the wave

@@ -270,30 +270,52 @@ __global__ __launch_bounds__(SP_ROWS) void spmm_tile_kernel(const int64_t* __res
 // split between the two long-row kernels below does not depend on timing.
 __global__ __launch_bounds__(1024) void find_long_rows_kernel(const int64_t* row_ptr, int64_t P, int64_t capacity,
                                                               int32_t* list, int32_t* count, int32_t list_cap) {
-  __shared__ int s_w[16];
+  // 16 x 1024 rows per turn: all their row_ptr loads in flight at once, then one scan over the
+  // 16 x 16 (round, wave) counts instead of a barrier-separated step per 1024 rows
+  __shared__ int s_cnt[16 * 16];   // [round][wave] counts, then their exclusive prefix in that order
   __shared__ int s_base;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  if (threadIdx.x == 0) s_base = 0;
-  __syncthreads();
-  for (int64_t r0 = 0; r0 < P; r0 += 1024) {
-    const int64_t row = r0 + threadIdx.x;
-    const bool is_long = row < P && min(row_ptr[row + 1], capacity) - row_ptr[row] > LONG_ROW;
-    const unsigned long long m = __ballot(is_long);
-    if (lane == 0) s_w[wave] = __popcll(m);
-    __syncthreads();
-    int before = s_base;
-    for (int w = 0; w < wave; ++w) before += s_w[w];
-    const int pos = before + __popcll(m & ((1ull << lane) - 1ull));
-    if (is_long && pos < list_cap) list[pos] = (int32_t)row;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      int t = 0;
-      for (int w = 0; w < 16; ++w) t += s_w[w];
-      s_base += t;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) s_base = 0;
+  for (int64_t r0 = 0; r0 < P; r0 += 16 * 1024) {
+    uint32_t flags = 0;
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const int64_t row = r0 + it * 1024 + tid;
+      const bool is_long = row < P && min(row_ptr[row + 1], capacity) - row_ptr[row] > LONG_ROW;
+      flags |= (is_long ? 1u : 0u) << it;
+    }
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const unsigned long long m = __ballot((flags >> it) & 1u);
+      if (lane == 0) s_cnt[it * 16 + wave] = __popcll(m);
+    }
+    __syncthreads();   // counts complete (and s_base of the turn before)
+    if (wave == 0) {   // exclusive prefix over the 256 counts, four per lane
+      int c[4], sum = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { c[j] = s_cnt[lane * 4 + j]; sum += c[j]; }
+      int incl = sum;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += up;
+      }
+      int run = s_base + incl - sum;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) { s_cnt[lane * 4 + j] = run; run += c[j]; }
+      if (lane == 63) s_base = run;
     }
     __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      const bool is_long = (flags >> it) & 1u;
+      const unsigned long long m = __ballot(is_long);
+      const int pos = s_cnt[it * 16 + wave] + __popcll(m & ((1ull << lane) - 1ull));
+      if (is_long && pos < list_cap) list[pos] = (int32_t)(r0 + it * 1024 + tid);
+    }
+    __syncthreads();   // s_cnt is rewritten in the next turn
   }
-  if (threadIdx.x == 0) *count = s_base;
+  if (tid == 0) *count = s_base;
 }
 
 // The first LD_CAP long rows (outlier channels of the transposed residual: nearly dense) are
