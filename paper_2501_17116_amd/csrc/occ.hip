@@ -125,16 +125,24 @@ __global__ __launch_bounds__(256) void sel_pick_kernel(SelState* st, unsigned lo
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int nb = 1 << bits;
   const int per = (nb + 255) / 256;
+  // both targets' bins and ranks are requested before either scan starts
+  unsigned long long vv[2][PER], rr[2];
+#pragma unroll
   for (int s = 0; s < 2; ++s) {
     const unsigned long long* hsrc = hist + (first ? 0 : s * SEL_BINS);
-    unsigned long long v[PER];
-    unsigned long long sum = 0;
+    rr[s] = st->rank[s];
 #pragma unroll
     for (int j = 0; j < PER; ++j) {
       const int b = tid * per + j;
-      v[j] = (j < per && b < nb) ? hsrc[b] : 0;
-      sum += v[j];
+      vv[s][j] = (j < per && b < nb) ? hsrc[b] : 0;
     }
+  }
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    unsigned long long (&v)[PER] = vv[s];
+    unsigned long long sum = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) sum += v[j];
     // inclusive prefix of the threads' sums: the thread whose range [excl, incl) holds the rank
     // owns the bin (the last thread, should the rank lie beyond the total)
     unsigned long long incl = sum;
@@ -146,7 +154,7 @@ __global__ __launch_bounds__(256) void sel_pick_kernel(SelState* st, unsigned lo
     if (lane == 63) s_w[wave] = incl;
     __syncthreads();
     for (int w = 0; w < wave; ++w) incl += s_w[w];
-    const unsigned long long r = st->rank[s];
+    const unsigned long long r = rr[s];
     const unsigned long long excl = incl - sum;
     if ((excl <= r && r < incl) || (tid == 255 && r >= incl)) {
       unsigned long long cum = excl;
