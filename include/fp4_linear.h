@@ -21,7 +21,9 @@
  *     stream per device (created at first use, default priority, kept until the process
  *     ends), forked from and joined back into `stream` with events, which is also valid
  *     under stream capture.  Setting the environment variable FP4_SINGLE_STREAM (any
- *     value, read once) keeps everything on `stream`.
+ *     value, read once) keeps everything on `stream`; do so when several streams of one
+ *     device are being captured at the same time, since a stream can join only one
+ *     capture and the extra stream is shared by all calls on a device.
  *   - Return value: FP4_OK (0) or a negative fp4_status.  Arguments are validated on
  *     the host before anything is enqueued; on error nothing has been enqueued, except
  *     FP4_ERR_HIP which reports a failed launch of the call's own kernels.
