@@ -297,6 +297,41 @@ def test_residual_spmm():
         assert_close(R, csr.to_dense() @ D.numpy().astype(np.float64), "f32", "spmm")
 
 
+def test_residual_spmm_random_shapes():
+    """Seeded sweep of ragged shapes and densities: rows whose entry counts sit on either side of a multiple of
+    four (the kernel walks a row four entries at a time), rows ending on a slab boundary, empty rows and empty
+    matrices, a last row that ends exactly at the end of the arrays, several 1024-row blocks."""
+    rng = np.random.default_rng(2024)
+    cases = [(1, 1, 8), (3, 4, 8), (5, 513, 72), (64, 512, 64), (65, 1030, 136), (1100, 96, 200), (2100, 40, 8),
+             (17, 2049, 264), (1, 3000, 16), (1030, 1537, 72)]
+    for ci, (P, Q, N) in enumerate(cases):
+        for dtype in ("bf16", "f32"):
+            dens = [0.0, 0.02, 0.3, 1.0][(ci + (dtype == "f32")) % 4]
+            per_row = rng.binomial(min(Q, 2048), dens, size=P) if dens < 1.0 else np.full(P, min(Q, 2048))
+            if P > 2:
+                per_row[1] = 0
+                per_row[2] = min(Q, 4)
+            row_ptr = np.zeros(P + 1, np.int64)
+            np.cumsum(per_row, out=row_ptr[1:])
+            nnz = int(row_ptr[-1])
+            cols = np.concatenate([np.sort(rng.choice(Q, size=k, replace=False)) for k in per_row] +
+                                  [np.zeros(0, np.int64)]).astype(np.int32)
+            vals = rng.standard_normal(nnz).astype(np.float32)
+            D = synth._finish(torch.from_numpy(rng.standard_normal((Q, N)).astype(np.float32)), dtype)
+            # no slack behind the last entry: a quad read must not run past the arrays
+            ci_d = torch.from_numpy(cols).cuda() if nnz else torch.zeros(0, dtype=torch.int32, device="cuda")
+            cv_d = torch.from_numpy(vals).cuda() if nnz else torch.zeros(0, dtype=torch.float32, device="cuda")
+            R = b.fp4_residual_spmm(torch.from_numpy(row_ptr).cuda(), ci_d, cv_d, Q, dev(D, dtype))
+            dense = np.zeros((P, Q))
+            rows = np.repeat(np.arange(P), per_row)
+            dense[rows, cols] = vals
+            ref = dense @ D.numpy().astype(np.float64)
+            g = R.cpu().numpy().astype(np.float64)
+            # sums of up to 2048 fp32 products: against the sum of the magnitudes
+            scale = np.abs(dense) @ np.abs(D.numpy().astype(np.float64))
+            assert np.all(np.abs(g - ref) <= 3e-5 * scale + 1e-30), "case %d %s" % (ci, dtype)
+
+
 # ------------------------------------------------------------------------------------------
 # DGE
 # ------------------------------------------------------------------------------------------
