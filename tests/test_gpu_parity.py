@@ -363,6 +363,9 @@ LAYER_CASES = [
     ("tiny", 32, 32, 32, "f32", 0.9),
     ("long", 2304, 64, 96, "bf16", 0.97),     # an outlier channel: a transposed residual row > 2048 entries
     ("wide", 64, 16416, 32, "bf16", 0.98),    # more input channels than the transpose's LDS tables hold
+    # several 1024-row blocks and several LDS slabs in both residual products, all of them ragged
+    ("blocks", 1120, 1056, 160, "bf16", 0.98),
+    ("blocks", 1056, 608, 96, "f32", 0.95),
 ]
 
 
