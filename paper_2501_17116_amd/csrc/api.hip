@@ -25,6 +25,7 @@ int fp4_launch_occ_rows(const void* x, int bf16, int64_t rows, int64_t cols, int
 int fp4_launch_quantize_cols(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
                              const float* clamp_thr, uint8_t* codes_t, float* gamma, uint32_t* amax_scratch,
                              hipStream_t s);
+int64_t fp4_quantize_cols_scratch_words(int64_t rows, int64_t cols);
 size_t fp4_select_scratch_bytes();
 int fp4_launch_thresholds(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, int64_t k,
                           float* thresholds, void* scratch, unsigned long long* total, hipStream_t s);
@@ -143,7 +144,7 @@ FwdWs carve_fwd(Carver& c, int64_t M, int64_t K, int64_t N, fp4_dtype dt) {
   w.qA = c.take<uint8_t>((size_t)(M * K / 2));
   w.gA = c.take<float>((size_t)M);
   w.qWt = c.take<uint8_t>((size_t)(N * K / 2));
-  w.amax = c.take<uint32_t>((size_t)N);
+  w.amax = c.take<uint32_t>((size_t)fp4_quantize_cols_scratch_words(K, N));
   // sized for the densest residual the entry points accept (alpha > 0.5 -> fewer than M*K entries);
   // the workspace query does not know alpha, so it provides for alpha >= 0.9
   w.occ = carve_occ(c, M, 2 * tail_count(M * K, 0.9));
@@ -173,7 +174,7 @@ WgradWs carve_wgrad(Carver& c, int64_t M, int64_t K, int64_t N) {
   w.gAk = c.take<float>((size_t)K);
   w.qdYt = c.take<uint8_t>((size_t)(N * M / 2));
   w.gdYn = c.take<float>((size_t)N);
-  w.amax = c.take<uint32_t>((size_t)std::max(K, N));
+  w.amax = c.take<uint32_t>((size_t)fp4_quantize_cols_scratch_words(M, std::max(K, N)));
   const int64_t cap = 2 * tail_count(M * K, 0.9);
   w.t_ptr = c.take<int64_t>((size_t)(K + 1));
   w.t_idx = c.take<int32_t>((size_t)cap);
@@ -210,7 +211,7 @@ extern "C" size_t fp4_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, f
   if (M < 0 || K < 0 || N < 0 || !dtype_ok(dt)) return 0;
   Carver c(nullptr);
   switch (op) {
-    case FP4_OP_QUANTIZE: c.take<uint32_t>((size_t)K); break;  // column absmax
+    case FP4_OP_QUANTIZE: c.take<uint32_t>((size_t)fp4_quantize_cols_scratch_words(M, K)); break;  // partial column maxima
     case FP4_OP_OCC: carve_occ(c, M, 2 * tail_count(M * K, 0.9)); break;
     case FP4_OP_FWD: carve_fwd(c, M, K, N, dt); break;
     case FP4_OP_DGRAD: carve_dgrad(c, M, K, N); break;

@@ -456,8 +456,8 @@ int launch_rows(const RowArgs& a, hipStream_t s) {
 
 // ------------------------------------------------------------------------------------------
 // Column-wise: one scale per column, codes transposed [cols x rows/2].
-// Pass A: column absmax of the (clamped) tensor, atomically maxed as uint bits (non-negative
-// floats order like unsigned integers).  Pass B: 256-row x 64-column tiles; a thread takes
+// Pass A: column absmax of the (clamped) tensor per block of 128 rows, as uint bits (non-negative
+// floats order like unsigned integers), folded over the row blocks when the scales are formed.  Pass B: 256-row x 64-column tiles; a thread takes
 // 8 consecutive rows of 8 consecutive columns, packs each column's 8 codes into one word,
 // and the tile is transposed through LDS so every column leaves as one 128-byte run.
 // ------------------------------------------------------------------------------------------
@@ -465,15 +465,10 @@ struct ColArgs {
   const void* x;
   uint8_t* codes_t;
   float* gamma;          // out [cols]
-  uint32_t* amax_bits;   // scratch [cols]
+  uint32_t* amax_bits;   // scratch [ceil(rows / CA_ROWS)][cols]: partial column maxima per row block
   const float* thr;      // clamp thresholds or null
   int64_t rows, cols, ld;
 };
-
-__global__ void fill_u32_kernel(uint32_t* p, int64_t n, uint32_t v) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = v;
-}
 
 constexpr int CA_ROWS = 128;  // rows per workgroup in the absmax pass
 
@@ -506,18 +501,35 @@ __global__ __launch_bounds__(256) void col_absmax_kernel(ColArgs a) {
 #pragma unroll
   for (int e = 0; e < 8; ++e) s_m[wave][lane][e] = m[e];
   __syncthreads();
+  // one row of partial maxima per row block (plain stores; a small fold follows): hundreds of
+  // workgroups maxing the same words with device-wide atomics cost 10-18 us per tensor
   if (wave == 0 && valid > 0) {
+    uint32_t* const prow = a.amax_bits + (int64_t)blockIdx.y * a.cols;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       float mm = fmaxf(fmaxf(s_m[0][lane][e], s_m[1][lane][e]), fmaxf(s_m[2][lane][e], s_m[3][lane][e]));
-      if (e < valid && mm > 0.0f) atomicMax(&a.amax_bits[unit * 8 + e], f2u(mm));
+      if (e < valid) prow[unit * 8 + e] = f2u(mm);
     }
   }
 }
 
-__global__ void amax_to_gamma_kernel(const uint32_t* amax_bits, float* gamma, int64_t n) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) gamma[i] = absmax_to_gamma(u2f(amax_bits[i]));
+// gamma[c] from the g partial rows of column maxima (bit patterns of non-negative floats order
+// like unsigned integers)
+__global__ __launch_bounds__(256) void amax_to_gamma_kernel(const uint32_t* part, int64_t g, float* gamma, int64_t n) {
+  const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (c >= n) return;
+  uint32_t m[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) m[j] = 0;
+  int64_t i = 0;
+  for (; i + 15 < g; i += 16) {   // sixteen loads in flight
+#pragma unroll
+    for (int j = 0; j < 16; ++j) m[j] = max(m[j], part[(i + j) * n + c]);
+  }
+  for (; i < g; ++i) m[0] = max(m[0], part[i * n + c]);
+#pragma unroll
+  for (int j = 1; j < 16; ++j) m[0] = max(m[0], m[j]);
+  gamma[c] = absmax_to_gamma(u2f(m[0]));
 }
 
 constexpr int CT_ROWS = 256;
@@ -592,13 +604,12 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColArgs a) {
 
 template <class DT, bool CLAMP>
 int launch_cols(const ColArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((a.cols + 255) / 256)), dim3(256), 0, s, a.amax_bits, a.cols, 0u);
   const int64_t nunits = (a.cols + 7) / 8;
-  hipLaunchKernelGGL((col_absmax_kernel<DT, CLAMP>),
-                     dim3((unsigned)((nunits + 63) / 64), (unsigned)((a.rows + CA_ROWS - 1) / CA_ROWS)),
-                     dim3(256), 0, s, a);
-  hipLaunchKernelGGL(amax_to_gamma_kernel, dim3((unsigned)((a.cols + 255) / 256)), dim3(256), 0, s,
-                     a.amax_bits, a.gamma, a.cols);
+  const int64_t rblocks = (a.rows + CA_ROWS - 1) / CA_ROWS;
+  hipLaunchKernelGGL((col_absmax_kernel<DT, CLAMP>), dim3((unsigned)((nunits + 63) / 64), (unsigned)rblocks), dim3(256),
+                     0, s, a);
+  hipLaunchKernelGGL(amax_to_gamma_kernel, dim3((unsigned)((a.cols + 255) / 256)), dim3(256), 0, s, a.amax_bits,
+                     rblocks, a.gamma, a.cols);
   hipLaunchKernelGGL((quantize_cols_kernel<DT, CLAMP>),
                      dim3((unsigned)((a.cols + CT_COLS - 1) / CT_COLS), (unsigned)((a.rows + CT_ROWS - 1) / CT_ROWS)),
                      dim3(256), 0, s, a);
@@ -661,6 +672,9 @@ __global__ __launch_bounds__(256) void dge_apply_kernel(const float* G, const vo
 }  // namespace
 
 // ---- internal launchers used by the layer entry points --------------------------------------
+// words of scratch fp4_launch_quantize_cols needs
+int64_t fp4_quantize_cols_scratch_words(int64_t rows, int64_t cols) { return (rows + CA_ROWS - 1) / CA_ROWS * cols; }
+
 int fp4_launch_quantize_rows(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
                              uint8_t* codes, float* gamma, hipStream_t s) {
   if (rows == 0 || cols == 0) return FP4_OK;
