@@ -83,7 +83,13 @@ class Fork {
     {
       std::lock_guard<std::mutex> lock(mu());
       hipStream_t& st = streams()[dev];
-      if (!st && hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) { st = nullptr; return; }
+      if (!st) {
+        // not while the caller's stream is being captured: creating a stream is no stream
+        // operation and may not be legal inside a capture; such a call stays on one stream
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (main_ && (hipStreamIsCapturing(main_, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone)) return;
+        if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) { st = nullptr; return; }
+      }
       side_ = st;
     }
     hipEvent_t ev;

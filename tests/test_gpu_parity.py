@@ -462,3 +462,41 @@ def test_layer_in_a_captured_graph_equals_eager_on_every_replay():
         Ye, dWe = _layer_once(Ad, Wd, dYd, 0.98)   # eager, own buffers
         torch.cuda.synchronize()
         assert torch.equal(Yg, Ye) and torch.equal(dWg, dWe), "replay %d" % rep
+
+
+_CAPTURE_FIRST = r"""
+import sys, torch
+sys.path.insert(0, %r)
+from paper_2501_17116_amd import binding as b, synth
+A, W, dY = synth.small_case(256, 512, 264, "bf16", seed=8)
+Ad, Wd, dYd = A.cuda().bfloat16(), W.cuda().bfloat16(), dY.cuda().bfloat16()
+M, K = Ad.shape; N = Wd.shape[1]
+ctx = b.FwdCtx(M, K, N, 0.98, Ad.device)
+ws = b.Workspace()
+ws.get(max(b.workspace_bytes(b.FP4_OP_FWD, M, K, N, b._dt(Ad)), b.workspace_bytes(b.FP4_OP_WGRAD, M, K, N, b._dt(Ad))))
+Yg = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+dWg = torch.empty((K, N), dtype=torch.float32, device="cuda")
+torch.cuda.synchronize()
+g = torch.cuda.CUDAGraph()
+with torch.cuda.graph(g):          # the library's very first call in this process
+    b.fp4_linear_fwd(Ad, Wd, 0.98, ctx=ctx, Y=Yg, ws=ws)
+    b.fp4_linear_bwd_wgrad(Ad, dYd, Wd, ctx, dW=dWg, ws=ws)
+for rep in range(2):
+    g.replay()
+    torch.cuda.synchronize()
+Ye, ctx2 = b.fp4_linear_fwd(Ad, Wd, 0.98)
+dWe = b.fp4_linear_bwd_wgrad(Ad, dYd, Wd, ctx2)
+torch.cuda.synchronize()
+assert torch.equal(Yg, Ye) and torch.equal(dWg, dWe)
+print("capture-first ok")
+"""
+
+
+def test_first_call_of_a_process_inside_a_capture():
+    """The second stream cannot be created during a capture: that call stays on one stream and must still be right."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", _CAPTURE_FIRST % root], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and "capture-first ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
