@@ -20,7 +20,8 @@
  *     fp4_linear_bwd_wgrad run an independent part of their kernel chain on one extra
  *     stream per device (created at first use, default priority, kept until the process
  *     ends), forked from and joined back into `stream` with events, which is also valid
- *     under stream capture.  Setting the environment variable FP4_SINGLE_STREAM (any
+ *     under stream capture (a call made inside a capture before that stream exists stays
+ *     on `stream` alone).  Setting the environment variable FP4_SINGLE_STREAM (any
  *     value, read once) keeps everything on `stream`; do so when several streams of one
  *     device are being captured at the same time, since a stream can join only one
  *     capture and the extra stream is shared by all calls on a device.
