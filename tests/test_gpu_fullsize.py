@@ -2,7 +2,8 @@
 masters, OCC alpha = 0.99, DGE k = 5) in the launch configuration bench.py times, checked on
 sampled outputs the oracle can compute one by one; the same on a layer of the 1.3B-shaped
 configuration (8192 tokens, 5504 -> 2048: a contraction length that is not a multiple of the
-GEMM's K step) and on the heavy-tailed (Student-t) configuration at a reduced token count.
+GEMM's K step), on the heavy-tailed (Student-t) configuration at a reduced token count, and on the
+widest layer (4096 -> 12288) at half the tokens.
 Thresholds, scales, the residual count and the sampled rows' codes / CSR entries are bit-exact;
 sampled Y, dA, dW rows within tolerance."""
 import numpy as np
@@ -28,7 +29,7 @@ def _close(got, ref, bf16, scale):
     assert not bad.any(), (int(bad.sum()), g[bad][:3], ref[bad][:3])
 
 
-CASES = [("c3", "o", None), ("c2", "down", None), ("c4", "ffn", 2048)]
+CASES = [("c3", "o", None), ("c2", "down", None), ("c4", "ffn", 2048), ("c3", "qkv", 8192)]
 
 
 @pytest.mark.parametrize("cfg_name,layer_name,tokens", CASES)
