@@ -15,16 +15,9 @@
  *   - All tensor pointers are DEVICE pointers owned by the caller unless a parameter
  *     says "host".  Matrices are row-major.  The library allocates no memory, keeps no
  *     state between calls and never synchronizes: every call only enqueues kernels on
- *     `stream` (a hipStream_t passed as void*; NULL = the default stream).  To the
- *     caller all work of a call is ordered on `stream`.  Inside, fp4_linear_fwd and
- *     fp4_linear_bwd_wgrad run an independent part of their kernel chain on one extra
- *     stream per device (created at first use, default priority, kept until the process
- *     ends), forked from and joined back into `stream` with events, which is also valid
- *     under stream capture (a call made inside a capture before that stream exists stays
- *     on `stream` alone).  Setting the environment variable FP4_SINGLE_STREAM (any
- *     value, read once) keeps everything on `stream`; do so when several streams of one
- *     device are being captured at the same time, since a stream can join only one
- *     capture and the extra stream is shared by all calls on a device.
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream), and on no
+ *     other stream, so every entry point may be called while `stream` is being captured
+ *     into a graph.
  *   - Return value: FP4_OK (0) or a negative fp4_status.  Arguments are validated on
  *     the host before anything is enqueued; on error nothing has been enqueued, except
  *     FP4_ERR_HIP which reports a failed launch of the call's own kernels.
@@ -44,7 +37,11 @@
  *   - Every GEMM contracts over an axis whose length is a multiple of 32.
  *   - Workspaces: query with fp4_workspace_bytes(); contents on entry are ignored and
  *     on exit undefined.  Two calls may share a workspace only if stream order
- *     serializes them.
+ *     serializes them.  The query does not know alpha: it provides for residual
+ *     densities up to 20 %, i.e. alpha >= 0.9 (the paper uses 0.97 .. 0.999, Sec. 4.3).
+ *     An alpha in (0.5, 0.9) is refused with FP4_ERR_ARG; outside (0.5, 1] likewise.
+ *   - Residual capacity: the library never writes beyond `capacity` entries and never
+ *     uses more than the workspaces provide for, whatever larger capacity is passed.
  */
 #ifndef FP4_LINEAR_H
 #define FP4_LINEAR_H
@@ -62,7 +59,8 @@ typedef enum {
   FP4_ERR_SHAPE = -2,     /* a dimension <= 0 where not allowed, odd packed length,
                              contraction length not a multiple of 32, ld too small        */
   FP4_ERR_DTYPE = -3,     /* unknown fp4_dtype / fp4_axis / op                            */
-  FP4_ERR_ARG = -4,       /* alpha outside (0.5, 1], dge_cap <= 0, misaligned pointer     */
+  FP4_ERR_ARG = -4,       /* alpha outside [0.9, 1] (see below), dge_cap <= 0, misaligned
+                             pointer                                                      */
   FP4_ERR_WORKSPACE = -5, /* workspace NULL or smaller than fp4_workspace_bytes()         */
   FP4_ERR_CAPACITY = -6,  /* residual buffers smaller than 2*floor((1-alpha)*rows*cols)   */
   FP4_ERR_HIP = -7        /* a kernel launch failed (hipGetLastError)                     */
@@ -183,42 +181,6 @@ int fp4_dge_apply(const float* G, const void* W, fp4_dtype dt, const float* gamm
 int fp4_residual_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val,
                       int64_t P, int64_t Q, const void* D, fp4_dtype dt, int64_t N,
                       float* R, void* workspace, size_t workspace_bytes, void* stream);
-
-/* Host-side evaluation of the library's own rounding routine: codes[i] = Q(x[i]) for
- * n fp32 values in HOST memory (the same inline function the kernels use, compiled for
- * the CPU; lets the rounding be checked exhaustively without a GPU). */
-int fp4_host_round_codes(const float* x_host, int64_t n, uint8_t* codes_host);
-
-/* The rounding as the quantization kernels perform it on the device (App. A's rule carried out
- * by the FP4 convert instruction, eight values per packed word): codes[i] = Q(x[i]), one code per
- * byte, x and codes in DEVICE memory, n a multiple of 8.
- * fp4_device_round_sweep: runs every one of the 2^32 fp32 bit patterns, in each of the eight
- * positions of a packed word, through that routine and through the comparison chain that
- * fp4_host_round_codes exposes, and ADDS the number of disagreements to *mismatches (device
- * memory, 8 bytes, set it to 0 first).  About a second of GPU time. */
-int fp4_device_round_codes(const float* x, int64_t n, uint8_t* codes, void* stream);
-int fp4_device_round_sweep(unsigned long long* mismatches, void* stream);
-
-/* ---- ceilings measured on the part (for reading the rooflines; not part of the method) ----
- * fp4_probe_mfma: `workgroups` workgroups of 8 waves each run `iters` iterations of 8 FP4
- *   32x32x64 MFMAs per wave with operands taken from operand_bytes (device, >= 16 bytes): an
- *   issue loop without memory traffic.  FLOP = workgroups * 8 * iters * 8 * 131072.  The rate
- *   depends on the operand data (random codes draw more power than constant ones).
- *   sink: device, workgroups * 512 floats.
- * fp4_probe_copy: dst[0..nbytes) = src[0..nbytes), 16 bytes per lane (streaming copy). */
-int fp4_probe_mfma(const void* operand_bytes, int64_t nbytes, int workgroups, int iters, float* sink,
-                   void* stream);
-int fp4_probe_copy(const void* src, void* dst, int64_t nbytes, void* stream);
-
-/* ---- measurement helper (host-side state, off by default; not thread-safe) ----
- * Between fp4_trace_gemm_begin(n) and fp4_trace_gemm_end() every launch of the FP4 GEMM
- * kernel, from any entry point, is bracketed by a pair of HIP events recorded on the
- * launch's own stream (at most n launches; later ones are not recorded).
- * fp4_trace_gemm_end waits for the recorded launches, writes their durations in
- * milliseconds, in launch order, to ms_host[0..capacity) (HOST memory) and returns the
- * number of launches recorded (>= 0) or a negative fp4_status. */
-int fp4_trace_gemm_begin(int max_launches);
-int fp4_trace_gemm_end(float* ms_host, int capacity);
 
 #ifdef __cplusplus
 }

@@ -123,27 +123,39 @@ def occ_capacity(rows: int, cols: int, alpha: float) -> int:
 
 
 class Workspace:
-    """A growable device byte buffer handed to the entry points as their workspace."""
+    """A growable device byte buffer handed to the entry points as their workspace.
+
+    One Workspace serves calls that stream order serializes (the ABI's workspace rule): use one
+    per stream.  Growing keeps the outgrown buffers alive until release(), because kernels
+    enqueued earlier may still be running in them and torch's allocator knows nothing of
+    streams other than the one a tensor was allocated on."""
 
     def __init__(self, device="cuda"):
         self.device = device
         self.buf = torch.empty(0, dtype=torch.uint8, device=device)
+        self._outgrown = []
 
     def get(self, nbytes: int) -> torch.Tensor:
         if self.buf.numel() < nbytes:
+            if self.buf.numel():
+                self._outgrown.append(self.buf)
             self.buf = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         return self.buf
 
+    def release(self) -> None:
+        """Drop outgrown buffers; call after the streams that used them have been synchronized."""
+        self._outgrown.clear()
 
-_default_ws: Optional[Workspace] = None
+
+_default_ws = {}   # (device index, stream handle) -> Workspace: never shared between streams
 
 
 def _ws(nbytes: int, ws: Optional[Workspace]) -> torch.Tensor:
-    global _default_ws
     if ws is None:
-        if _default_ws is None:
-            _default_ws = Workspace()
-        ws = _default_ws
+        key = (torch.cuda.current_device(), torch.cuda.current_stream().cuda_stream)
+        ws = _default_ws.get(key)
+        if ws is None:
+            ws = _default_ws[key] = Workspace()
     return ws.get(nbytes)
 
 

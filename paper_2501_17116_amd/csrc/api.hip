@@ -1,14 +1,12 @@
 // Host side of the C ABI: argument validation, workspace carving and the kernel sequences of
 // the three layer passes (Fig. 2; Sec. 3.1; Sec. 3.2; Sec. 4.1).  Nothing here allocates device
-// memory or synchronizes; every buffer is the caller's.  The only state is one extra stream per
-// device (see Fork), created on first use.
+// memory or synchronizes; every buffer is the caller's, every kernel goes to the caller's stream,
+// and the library keeps no state between calls.
 #include "fp4_common.h"
 
 #include <algorithm>
 #include <cmath>
-#include <cstdlib>
 #include <limits>
-#include <mutex>
 
 // launchers defined next to their kernels
 int fp4_launch_gemm(const uint8_t* L, const float* gl, const uint8_t* Rt, const float* gr, int64_t P,
@@ -69,59 +67,13 @@ struct Carver {
   }
 };
 
-// A second stream per device for kernel chains that do not depend on each other (short,
-// latency-bound index kernels beside bandwidth-bound quantization passes).  Fork: the side stream
-// waits for everything enqueued on the caller's stream so far; join: the caller's stream waits
-// for the side stream.  The caller sees one stream; if the side stream or an event cannot be
-// had, everything simply stays on the caller's stream.  Default priority, non-blocking.
-class Fork {
- public:
-  explicit Fork(hipStream_t main, bool wanted) : main_(main) {
-    if (!wanted || disabled()) return;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDev) return;
-    {
-      std::lock_guard<std::mutex> lock(mu());
-      hipStream_t& st = streams()[dev];
-      if (!st) {
-        // not while the caller's stream is being captured: creating a stream is no stream
-        // operation and may not be legal inside a capture; such a call stays on one stream
-        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-        if (main_ && (hipStreamIsCapturing(main_, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone)) return;
-        if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) { st = nullptr; return; }
-      }
-      side_ = st;
-    }
-    hipEvent_t ev;
-    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) { side_ = nullptr; return; }
-    const bool ok = hipEventRecord(ev, main_) == hipSuccess && hipStreamWaitEvent(side_, ev, 0) == hipSuccess;
-    (void)hipEventDestroy(ev);   // released once it has completed
-    if (!ok) side_ = nullptr;
-  }
-  hipStream_t side() const { return side_ ? side_ : main_; }
-  int join() {
-    if (!side_) return FP4_OK;
-    hipEvent_t ev;
-    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) return FP4_ERR_HIP;
-    const bool ok = hipEventRecord(ev, side_) == hipSuccess && hipStreamWaitEvent(main_, ev, 0) == hipSuccess;
-    (void)hipEventDestroy(ev);
-    side_ = nullptr;
-    return ok ? FP4_OK : FP4_ERR_HIP;
-  }
-
- private:
-  static constexpr int kMaxDev = 64;
-  static std::mutex& mu() { static std::mutex m; return m; }
-  static hipStream_t* streams() { static hipStream_t st[kMaxDev] = {}; return st; }
-  static bool disabled() { static const bool d = std::getenv("FP4_SINGLE_STREAM") != nullptr; return d; }
-  hipStream_t main_;
-  hipStream_t side_ = nullptr;
-};
-
 inline bool dtype_ok(fp4_dtype dt) { return dt == FP4_F32 || dt == FP4_BF16; }
 inline size_t esize(fp4_dtype dt) { return dt == FP4_BF16 ? 2 : 4; }
 
 int64_t tail_count(int64_t n, double alpha) { return (int64_t)std::floor((1.0 - alpha) * (double)n); }
+// Residual entries the workspaces provide for: the workspace query does not know alpha, so it
+// sizes for alpha >= 0.9 (density up to 20 %); a smaller alpha is refused with FP4_ERR_ARG.
+int64_t provisioned_entries(int64_t rows, int64_t cols) { return 2 * tail_count(rows * cols, 0.9); }
 
 struct OccTemps {
   void* select;
@@ -153,9 +105,9 @@ FwdWs carve_fwd(Carver& c, int64_t M, int64_t K, int64_t N, fp4_dtype dt) {
   w.amax = c.take<uint32_t>((size_t)fp4_quantize_cols_scratch_words(K, N));
   // sized for the densest residual the entry points accept (alpha > 0.5 -> fewer than M*K entries);
   // the workspace query does not know alpha, so it provides for alpha >= 0.9
-  w.occ = carve_occ(c, M, 2 * tail_count(M * K, 0.9));
+  w.occ = carve_occ(c, M, provisioned_entries(M, K));
   w.R = dt == FP4_BF16 ? c.take<float>((size_t)(M * N)) : nullptr;
-  w.sp_scratch = c.take<int32_t>((size_t)fp4_spmm_scratch_words(fp4_spmm_long_list_cap(2 * tail_count(M * K, 0.9)), K, N));
+  w.sp_scratch = c.take<int32_t>((size_t)fp4_spmm_scratch_words(fp4_spmm_long_list_cap(provisioned_entries(M, K)), K, N));
   return w;
 }
 
@@ -181,7 +133,7 @@ WgradWs carve_wgrad(Carver& c, int64_t M, int64_t K, int64_t N) {
   w.qdYt = c.take<uint8_t>((size_t)(N * M / 2));
   w.gdYn = c.take<float>((size_t)N);
   w.amax = c.take<uint32_t>((size_t)fp4_quantize_cols_scratch_words(M, std::max(K, N)));
-  const int64_t cap = 2 * tail_count(M * K, 0.9);
+  const int64_t cap = provisioned_entries(M, K);
   w.t_ptr = c.take<int64_t>((size_t)(K + 1));
   w.t_idx = c.take<int32_t>((size_t)cap);
   w.t_val = c.take<float>((size_t)cap);
@@ -218,7 +170,7 @@ extern "C" size_t fp4_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, f
   Carver c(nullptr);
   switch (op) {
     case FP4_OP_QUANTIZE: c.take<uint32_t>((size_t)fp4_quantize_cols_scratch_words(M, K)); break;  // partial column maxima
-    case FP4_OP_OCC: carve_occ(c, M, 2 * tail_count(M * K, 0.9)); break;
+    case FP4_OP_OCC: carve_occ(c, M, provisioned_entries(M, K)); break;
     case FP4_OP_FWD: carve_fwd(c, M, K, N, dt); break;
     case FP4_OP_DGRAD: carve_dgrad(c, M, K, N); break;
     case FP4_OP_WGRAD: carve_wgrad(c, M, K, N); break;
@@ -244,11 +196,11 @@ extern "C" int occ_clamp_residual(const void* x, fp4_dtype dt, int64_t rows, int
   if (!aligned16(x) || (ld % 8) != 0 || (codes && !aligned16(codes)) || (x_clamped && !aligned16(x_clamped)))
     return FP4_ERR_ARG;
   if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_OCC, rows, cols, 0, dt)) return FP4_ERR_WORKSPACE;
-  if (2 * k > 2 * tail_count(rows * cols, 0.9)) return FP4_ERR_WORKSPACE;  // alpha below 0.9 not provisioned
+  if (2 * k > provisioned_entries(rows, cols)) return FP4_ERR_ARG;  // alpha below 0.9 is not provisioned
   hipStream_t s = (hipStream_t)stream;
   Carver c(reinterpret_cast<void*>(align_up((size_t)(uintptr_t)workspace, 256)));
-  OccTemps t = carve_occ(c, rows, 2 * tail_count(rows * cols, 0.9));
-  capacity = std::min(capacity, 2 * tail_count(rows * cols, 0.9));  // never beyond the temporaries
+  OccTemps t = carve_occ(c, rows, provisioned_entries(rows, cols));
+  capacity = std::min(capacity, provisioned_entries(rows, cols));  // never beyond the temporaries
   int rc = fp4_launch_thresholds(x, dt == FP4_BF16, rows, cols, ld, k, thresholds, t.select, t.total, s);
   if (rc) return rc;
   rc = fp4_launch_occ_count(x, dt == FP4_BF16, rows, cols, ld, thresholds, t.row_cnt, s);
@@ -278,7 +230,7 @@ extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_
     if (!saved->thresholds || !saved->row_ptr || !saved->nnz) return FP4_ERR_NULL;
     if (saved->capacity < 2 * k) return FP4_ERR_CAPACITY;
     if (saved->capacity > 0 && (!saved->col_idx || !saved->val)) return FP4_ERR_NULL;
-    if (2 * k > 2 * tail_count(M * K, 0.9)) return FP4_ERR_WORKSPACE;
+    if (2 * k > provisioned_entries(M, K)) return FP4_ERR_ARG;   // alpha below 0.9 is not provisioned
   }
   if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_FWD, M, K, N, dt)) return FP4_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
@@ -286,21 +238,18 @@ extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_
   Carver c(reinterpret_cast<void*>(align_up((size_t)(uintptr_t)workspace, 256)));
   FwdWs w = carve_fwd(c, M, K, N, dt);
 
-  // W per output channel -> codes [N x K/2], scales kept for the DGE term of the backward pass;
-  // beside the chain that prepares A (nothing of it touches qWt, gamma_W or amax)
-  Fork fork(s, occ);
-  int rc = fp4_launch_quantize_cols(W, bf16, K, N, N, nullptr, w.qWt, saved->gamma_W, w.amax, fork.side());
-  if (rc) { (void)fork.join(); return rc; }
-  auto joined = [&](int code) { const int j = fork.join(); return code ? code : j; };
+  // W per output channel -> codes [N x K/2], scales kept for the DGE term of the backward pass
+  int rc = fp4_launch_quantize_cols(W, bf16, K, N, N, nullptr, w.qWt, saved->gamma_W, w.amax, s);
+  if (rc) return rc;
   const float* addend = nullptr;
   if (occ) {
-    const int64_t cap = std::min(saved->capacity, 2 * tail_count(M * K, 0.9));  // never beyond the temporaries
+    const int64_t cap = std::min(saved->capacity, provisioned_entries(M, K));  // never beyond the temporaries
     rc = fp4_launch_thresholds(A, bf16, M, K, K, k, saved->thresholds, w.occ.select, w.occ.total, s);
-    if (rc) return joined(rc);
+    if (rc) return rc;
     rc = fp4_launch_occ_count(A, bf16, M, K, K, saved->thresholds, w.occ.row_cnt, s);
-    if (rc) return joined(rc);
+    if (rc) return rc;
     rc = fp4_launch_scan_rows(w.occ.row_cnt, M, saved->row_ptr, saved->nnz, s);
-    if (rc) return joined(rc);
+    if (rc) return rc;
     rc = fp4_launch_occ_rows(A, bf16, M, K, K, saved->thresholds, w.qA, w.gA, nullptr, saved->col_idx, saved->val,
                              w.occ.tmp_col, w.occ.tmp_val, saved->row_ptr, cap, s);
     if (rc == 1) {   // streamed rows: entries unordered in the temporaries
@@ -308,24 +257,22 @@ extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_
       if (rc == 1)
         rc = fp4_launch_csr_gather(w.occ.tmp_col, w.occ.tmp_val, M, cap, saved->row_ptr, saved->col_idx, saved->val, s);
     }
-    if (rc) return joined(rc);
+    if (rc) return rc;
     // Delta_A W with the unquantized W, fp32; lands where the GEMM epilogue picks it up
     float* R = bf16 ? w.R : reinterpret_cast<float*>(Y);
     rc = fp4_launch_spmm(saved->row_ptr, saved->col_idx, saved->val, cap, M, K, W, bf16, N, R, w.sp_scratch,
-                         fp4_spmm_long_list_cap(2 * tail_count(M * K, 0.9)), s);
-    if (rc) return joined(rc);
+                         fp4_spmm_long_list_cap(provisioned_entries(M, K)), s);
+    if (rc) return rc;
     addend = R;
   } else {
     rc = fp4_launch_quantize_rows(A, bf16, M, K, K, w.qA, w.gA, s);
-    if (rc) return joined(rc);
+    if (rc) return rc;
     if (saved->thresholds || saved->row_ptr || saved->nnz) {
       hipLaunchKernelGGL(init_no_occ_kernel, dim3((unsigned)((M + 1 + 255) / 256)), dim3(256), 0, s,
                          saved->thresholds, saved->row_ptr, M, saved->nnz);
-      if (hipGetLastError() != hipSuccess) return joined(FP4_ERR_HIP);
+      if (hipGetLastError() != hipSuccess) return FP4_ERR_HIP;
     }
   }
-  rc = joined(FP4_OK);
-  if (rc) return rc;
   return fp4_launch_gemm(w.qA, w.gA, w.qWt, saved->gamma_W, M, N, K, addend, Y, bf16, N, nullptr, 0, 0,
                          nullptr, 0.0f, 0.0f, s);
 }
@@ -362,29 +309,25 @@ extern "C" int fp4_linear_bwd_wgrad(const void* A, const void* dY, const void* W
   // The residual is in play when the forward pass saved one (capacity > 0 with its arrays).
   const bool occ = saved->capacity > 0 && saved->row_ptr && saved->col_idx && saved->val && saved->nnz &&
                    saved->thresholds;
-  if (occ && saved->capacity > 2 * tail_count(M * K, 0.9)) return FP4_ERR_WORKSPACE;
   if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_WGRAD, M, K, N, dt)) return FP4_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   const int bf16 = dt == FP4_BF16;
   Carver c(reinterpret_cast<void*>(align_up((size_t)(uintptr_t)workspace, 256)));
   WgradWs w = carve_wgrad(c, M, K, N);
-  // A_c per input channel (codes [K x M/2]); dY per output channel (codes [N x M/2])
-  // The transposition of the saved residual (short index kernels, own buffers) runs beside the
-  // two quantization passes.
-  Fork fork(s, occ);
+  // as the forward pass: entries beyond what the workspaces provide for cannot exist
+  const int64_t cap = occ ? std::min(saved->capacity, provisioned_entries(M, K)) : 0;
   int rc = FP4_OK;
   if (occ)
-    rc = fp4_launch_csr_transpose(saved->row_ptr, saved->col_idx, saved->val, saved->nnz, M, K, saved->capacity,
-                                  w.t_ptr, w.t_idx, w.t_val, w.u_idx, w.u_val, w.t_scratch, fork.side());
+    rc = fp4_launch_csr_transpose(saved->row_ptr, saved->col_idx, saved->val, saved->nnz, M, K, cap,
+                                  w.t_ptr, w.t_idx, w.t_val, w.u_idx, w.u_val, w.t_scratch, s);
+  // A_c per input channel (codes [K x M/2]); dY per output channel (codes [N x M/2])
   if (!rc) rc = fp4_launch_quantize_cols(A, bf16, M, K, K, occ ? saved->thresholds : nullptr, w.qAt, w.gAk, w.amax, s);
   if (!rc) rc = fp4_launch_quantize_cols(dY, bf16, M, N, N, nullptr, w.qdYt, w.gdYn, w.amax, s);
-  const int jrc = fork.join();
   if (rc) return rc;
-  if (jrc) return jrc;
   const float* addend = nullptr;
   if (occ) {
-    rc = fp4_launch_spmm(w.t_ptr, w.t_idx, w.t_val, saved->capacity, K, M, dY, bf16, N, dW, w.sp_scratch,
-                         fp4_spmm_long_list_cap(2 * tail_count(M * K, 0.9)), s);
+    rc = fp4_launch_spmm(w.t_ptr, w.t_idx, w.t_val, cap, K, M, dY, bf16, N, dW, w.sp_scratch,
+                         fp4_spmm_long_list_cap(provisioned_entries(M, K)), s);
     if (rc) return rc;
     addend = dW;
   }

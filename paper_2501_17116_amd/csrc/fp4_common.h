@@ -82,6 +82,22 @@ FP4_D uint32_t q_e2m1_pack8(const float (&v)[8]) {
   w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, q_e2m1_prepare(v[6]), q_e2m1_prepare(v[7]), 1.0f, 3);
   return q_e2m1_drop_zero_signs(w);
 }
+
+// DGE factor min(cap, f'(x)) of one weight (Sec. 3.1 Eq. 8):
+//   f'(x) = (1/k) |2(a-l)/delta - 1|^(1/k-1), a = |w * gamma|, [l, l+delta] the E2M1 interval
+//   holding a: delta = .5 below 2, 1 below 4, 2 above (a rounding hair above 6 keeps [4, 6]).
+// inv_k = 1/k, pw = 1/k - 1.  t == 0 with pw < 0: log2 = -inf -> exp2(+inf) = inf -> cap.
+// pw == 0 (k = 1) is taken out: 0 * log2(0) would be NaN, and |t|^0 = 1 everywhere.
+FP4_D float dge_factor(float w, float gamma, float pw, float inv_k, float cap) {
+  const float a = fabsf(__fmul_rn(w, gamma));
+  float l, s;
+  if (a < 2.0f) { l = 0.5f * floorf(a + a); s = 4.0f; }
+  else if (a < 4.0f) { l = floorf(a); s = 2.0f; }
+  else { l = 4.0f; s = 1.0f; }
+  const float t = fabsf(s * (a - l) - 1.0f);
+  const float e = pw == 0.0f ? 1.0f : __builtin_amdgcn_exp2f(pw * __builtin_amdgcn_logf(t));
+  return fminf(inv_k * e, cap);
+}
 #endif  // __HIPCC__
 
 // gamma = fl32(6 / amax); 1 for amax == 0 or a non-finite quotient.

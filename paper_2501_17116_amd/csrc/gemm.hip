@@ -13,6 +13,7 @@
 // is a multiple of 1/4 and bounded by 36, so the fp32 accumulator is exact for any contraction
 // length below 2^22/36 and does not depend on summation order.
 #include "fp4_common.h"
+#include "fp4_measure.h"
 
 #include <algorithm>
 #include <utility>
@@ -67,19 +68,6 @@ FP4_D uint32_t pack_bf16x2(float a, float b) {
   union { bf16x2_t h; uint32_t u; } c;
   c.h = h;
   return c.u;
-}
-
-FP4_D float dge_factor(float w, float gamma, float inv_k_minus_1, float inv_k, float cap) {
-  // f'(x) = (1/k) |2(a-l)/delta - 1|^(1/k-1), a = |w * gamma|, [l, l+delta] the E2M1
-  // interval holding a: delta = .5 below 2, 1 below 4, 2 above.
-  float a = fabsf(__fmul_rn(w, gamma));
-  float l, s;
-  if (a < 2.0f) { l = 0.5f * floorf(a + a); s = 4.0f; }
-  else if (a < 4.0f) { l = floorf(a); s = 2.0f; }
-  else { l = 4.0f; s = 1.0f; }
-  float t = fabsf(s * (a - l) - 1.0f);
-  float f = inv_k * __builtin_amdgcn_exp2f(inv_k_minus_1 * __builtin_amdgcn_logf(t));
-  return fminf(f, cap);   // t == 0 -> log2 = -inf -> exp2(+inf) = inf -> cap
 }
 
 // OUT_BF16: output dtype; DGE: multiply by the DGE factor of W (dtype W_BF16).
@@ -428,6 +416,20 @@ __global__ void fp4_unpack_kernel(const uint8_t* codes, int64_t nbytes, uint8_t*
   }
 }
 
+// Compute units of the device the launch goes to (one persistent workgroup each).  Looked up once
+// per device; concurrent first calls write the same value.
+int compute_units_of_current_device() {
+  static int cached[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  int n = cached[dev];
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+    cached[dev] = n;
+  }
+  return n;
+}
+
 // Optional per-launch timing of the GEMM kernel (off unless fp4_trace_gemm_begin was called).
 struct GemmTrace {
   std::vector<hipEvent_t> ev;  // start/stop pairs
@@ -451,12 +453,7 @@ int fp4_launch_gemm(const uint8_t* L, const float* gl, const uint8_t* Rt, const 
   g.tiles_q = (int)((Q + BN - 1) / BN);
   const bool dge = W != nullptr && dge_k > 0.0f;
   const int total = g.tiles_p * g.tiles_q;
-  static int n_cu = 0;
-  if (n_cu == 0) {
-    int dev = 0;
-    (void)hipGetDevice(&dev);
-    if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 8) n_cu = 256;
-  }
+  const int n_cu = compute_units_of_current_device();
   const dim3 grid(std::min(((total + 7) / 8) * 8, (n_cu / 8) * 8)), block(NTHREADS);
   const bool traced = g_trace.on && 2 * g_trace.used + 1 < (int)g_trace.ev.size();
   if (traced) (void)hipEventRecord(g_trace.ev[2 * g_trace.used], stream);

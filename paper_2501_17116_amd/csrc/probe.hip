@@ -3,6 +3,7 @@
 // from a caller buffer because the sustained matrix-core rate of this part depends on the data:
 // with random codes the chip settles at a lower clock than with constant operands.
 #include "fp4_common.h"
+#include "fp4_measure.h"
 
 typedef int i32x8p __attribute__((ext_vector_type(8)));
 typedef float f32x16p __attribute__((ext_vector_type(16)));

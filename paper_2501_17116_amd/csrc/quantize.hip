@@ -5,6 +5,7 @@
 // Work unit: 8 consecutive elements of a row = one 16-byte load of bf16 (two of fp32) and one
 // 4-byte store of codes, so a wave reads 1 KiB (bf16) contiguous and writes 256 B contiguous.
 #include "fp4_common.h"
+#include "fp4_measure.h"
 
 #include <type_traits>
 
@@ -655,14 +656,7 @@ __global__ __launch_bounds__(256) void dge_apply_kernel(const float* G, const vo
       float gq[4] = {g[i].x, g[i].y, g[i].z, g[i].w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        float a = fabsf(__fmul_rn(w[i][e], gam[e]));
-        float l, s;
-        if (a < 2.0f) { l = 0.5f * floorf(a + a); s = 4.0f; }
-        else if (a < 4.0f) { l = floorf(a); s = 2.0f; }
-        else { l = 4.0f; s = 1.0f; }
-        float t = fabsf(s * (a - l) - 1.0f);
-        float f = fminf(inv_k * __builtin_amdgcn_exp2f(pw * __builtin_amdgcn_logf(t)), cap);
-        gq[e] *= ste ? 1.0f : f;
+        gq[e] *= ste ? 1.0f : dge_factor(w[i][e], gam[e], pw, inv_k, cap);
       }
       *reinterpret_cast<f32x4*>(dW + (r0 + i) * N + c) = f32x4{gq[0], gq[1], gq[2], gq[3]};
     }

@@ -22,7 +22,8 @@ def L():
 
 
 def _declared_symbols():
-    src = open(os.path.join(ROOT, "include", "fp4_linear.h")).read()
+    src = "".join(open(os.path.join(ROOT, "include", h)).read()
+                  for h in sorted(os.listdir(os.path.join(ROOT, "include"))) if h.endswith(".h"))
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     names = re.findall(r"\b(?:int|size_t|int64_t|const char\*)\s+(\w+)\s*\(", src)
     return sorted(set(names))

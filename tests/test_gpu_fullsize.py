@@ -1,9 +1,9 @@
-"""GPU parity at benchmark size: one LLaMA-7B-shaped layer (16384 tokens, 4096 -> 4096, bf16
+"""GPU parity at benchmark size: all four layers of the LLaMA-7B-shaped block (16384 tokens, bf16
 masters, OCC alpha = 0.99, DGE k = 5) in the launch configuration bench.py times, checked on
 sampled outputs the oracle can compute one by one; the same on a layer of the 1.3B-shaped
 configuration (8192 tokens, 5504 -> 2048: a contraction length that is not a multiple of the
-GEMM's K step), on the heavy-tailed (Student-t) configuration at a reduced token count, and on the
-widest layer (4096 -> 12288) at half the tokens.
+GEMM's K step) and on the heavy-tailed (Student-t) 13B-shaped configuration: its 13824 -> 5120
+layer at 16384 tokens and alpha = 0.999, the two others at reduced token counts.
 Thresholds, scales, the residual count and the sampled rows' codes / CSR entries are bit-exact;
 sampled Y, dA, dW rows within tolerance."""
 import numpy as np
@@ -29,12 +29,19 @@ def _close(got, ref, bf16, scale):
     assert not bad.any(), (int(bad.sum()), g[bad][:3], ref[bad][:3])
 
 
-CASES = [("c3", "o", None), ("c2", "down", None), ("c4", "ffn", 2048), ("c3", "qkv", 8192)]
+# (workload, layer, tokens or None = the workload's own, alpha or None = the workload's own)
+CASES = [("c3", "o", None, None), ("c2", "down", None, None), ("c4", "ffn", 2048, None),
+         ("c3", "qkv", None, None), ("c3", "gate_up", None, None), ("c3", "down", None, None),
+         ("c4", "down", None, 0.999), ("c4", "qkv", 4096, 0.999)]
 
 
-@pytest.mark.parametrize("cfg_name,layer_name,tokens", CASES)
-def test_full_size_layer_sampled(cfg_name, layer_name, tokens):
+@pytest.mark.parametrize("cfg_name,layer_name,tokens,alpha", CASES)
+def test_full_size_layer_sampled(cfg_name, layer_name, tokens, alpha):
+    import dataclasses
     cfg = synth.CONFIGS[cfg_name]
+    if alpha is not None:
+        cfg = dataclasses.replace(cfg, alpha=alpha)
+    print("full-size case", cfg_name, layer_name, tokens, cfg.alpha, flush=True)
     shape = [l for l in cfg.layers if l.name == layer_name][0]
     A, W, dY = synth.make_layer(cfg, shape) if tokens is None else synth.make_layer(cfg, shape, M=tokens)
     M, K, N = A.shape[0], shape.K, shape.N

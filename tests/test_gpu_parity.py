@@ -230,6 +230,54 @@ def test_occ_clamp_residual_bit_exact(shape, alpha, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,cols,ld,alpha", [(16, 10, 16, 0.9), (33, 74, 80, 0.97), (9, 2050, 2056, 0.99),
+                                                 (40, 520, 1024, 0.98), (3, 20002, 20008, 0.95),
+                                                 (5, 9002, 9008, 0.99), (64, 4096, 4104, 0.999)])
+def test_occ_raw_abi_ragged_cols_and_padded_rows(rows, cols, ld, alpha, dtype):
+    """cols not a multiple of 8 and ld > cols through the C ABI itself: the selection's element-wise
+    walk, the ragged last unit of every row under OCC, x_clamped with a leading dimension, and
+    guard columns that must stay untouched."""
+    import ctypes as C
+    cfg = synth.CONFIGS["c1"]
+    x = synth._finish(synth.make_activation(cfg, rows, ld, salt=rows + cols), dtype)
+    x[:, cols:] = 1e6                                   # padding must not reach thresholds, scales or entries
+    xd = dev(x, dtype)
+    tdt = xd.dtype
+    cap = b.occ_capacity(rows, cols, alpha)
+    thr = torch.empty(2, dtype=torch.float32, device="cuda")
+    codes = torch.full((rows, cols // 2), 0xEE, dtype=torch.uint8, device="cuda")
+    gamma = torch.empty(rows, dtype=torch.float32, device="cuda")
+    xc = torch.full((rows, ld), 7.0, dtype=tdt, device="cuda")
+    row_ptr = torch.empty(rows + 1, dtype=torch.int64, device="cuda")
+    col_idx = torch.empty(max(cap, 1), dtype=torch.int32, device="cuda")
+    val = torch.empty(max(cap, 1), dtype=torch.float32, device="cuda")
+    nnz = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ws = torch.empty(b.workspace_bytes(b.FP4_OP_OCC, rows, cols, 0, b._dt(xd)), dtype=torch.uint8, device="cuda")
+    P = lambda t: C.c_void_p(t.data_ptr())
+    st = b.lib().occ_clamp_residual(P(xd), b._dt(xd), rows, cols, ld, C.c_double(alpha), P(thr), P(codes), P(gamma),
+                                    P(xc), P(row_ptr), P(col_idx), P(val), cap, P(nnz), P(ws), ws.numel(),
+                                    b._stream())
+    assert st == 0
+    torch.cuda.synchronize()
+    xn = x[:, :cols].contiguous().numpy()
+    lo, hi = o.occ_thresholds(xn, alpha)
+    t = thr.cpu().numpy()
+    assert t[0] == lo and t[1] == hi, (t, lo, hi)
+    xcr, csr = o.occ_clamp_residual(xn, lo, hi)
+    n = int(nnz.item())
+    assert n == csr.val.size <= cap
+    assert np.array_equal(row_ptr.cpu().numpy(), csr.row_ptr)
+    assert np.array_equal(col_idx.cpu().numpy()[:n], csr.col_idx)
+    assert np.array_equal(val.cpu().numpy()[:n].view(np.uint32), csr.val.view(np.uint32))
+    xch = xc.float().cpu().numpy()
+    assert np.array_equal(xch[:, :cols], xcr)
+    assert np.all(xch[:, cols:] == 7.0)                 # guard columns untouched
+    rc, rg = o.quantize_rows(xcr)
+    assert np.array_equal(gamma.cpu().numpy().view(np.uint32), rg.view(np.uint32))
+    assert np.array_equal(host_codes(codes), rc)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_occ_with_ties_one_sided_and_constant(dtype):
     g = torch.Generator().manual_seed(3)
     x = torch.randint(0, 5, (64, 128), generator=g).float()          # heavy ties, all non-negative
@@ -352,6 +400,38 @@ def test_dge_apply(dtype):
     assert torch.equal(ste.cpu(), G)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("k,cap", [(1.0, 3.0), (3.0, 2.0), (7.0, 5.0), (2.0, 0.4), (0.5, 3.0), (5.0, 1e9)])
+def test_dge_apply_other_k_and_cap(k, cap, dtype):
+    """Eq. 8 away from the defaults: k = 1 (f' = 1 everywhere, interval midpoints included), k below 1
+    (f' -> 0 at a midpoint), a cap below 1/k (active everywhere) and a cap that is never active except
+    at exact midpoints."""
+    g = torch.Generator().manual_seed(int(10 * k) + 3)
+    K, N = 136, 72
+    W = synth._finish(torch.randn(K, N, generator=g) * 0.02, dtype)
+    W[:18, 0] = torch.tensor([6, .25, .5, .75, 1, 1.25, 2.5, 3, 3.5, 5, 0, 2.516, 2.484, -5, -0.25, 4.99, 1.75, -1.25])
+    G = torch.randn(K, N, generator=g)
+    _, gw = o.quantize_cols(W.numpy())
+    fp = o.dge_fprime(o.scaled_weights(W.numpy(), gw), k, cap)
+    assert np.isfinite(fp).all()
+    ref = G.numpy().astype(np.float64) * fp
+    got = b.fp4_dge_apply(G.cuda(), dev(W, dtype), torch.from_numpy(gw).cuda(), k, cap)
+    g64 = got.cpu().numpy().astype(np.float64)
+    assert np.isfinite(g64).all()
+    assert np.all(np.abs(g64 - ref) <= 1e-5 * np.abs(ref) + 1e-12)
+
+
+@pytest.mark.parametrize("k,cap", [(1.0, 3.0), (3.0, 2.0), (7.0, 5.0)])
+def test_layer_wgrad_other_k_and_cap(k, cap):
+    """The DGE factor fused in the weight-gradient epilogue at other (k, cap), planted midpoints included."""
+    A, W, dY = synth.small_case(288, 160, 264, "bf16", seed=int(k))
+    W[:14, 0] = torch.tensor([6, .25, .75, 1.25, 1.75, 2.5, 3.5, 5, -5, -2.5, 1, 2, 3, 4.]).to(torch.bfloat16).float()
+    Ad, Wd, dYd = dev(A, "bf16"), dev(W, "bf16"), dev(dY, "bf16")
+    _, ctx = b.fp4_linear_fwd(Ad, Wd, 0.98)
+    dW = b.fp4_linear_bwd_wgrad(Ad, dYd, Wd, ctx, k, cap)
+    assert_close(dW, o.fp4_linear_bwd_wgrad(A.numpy(), dY.numpy(), W.numpy(), 0.98, k, cap), "f32", "dW")
+
+
 # ------------------------------------------------------------------------------------------
 # the layer: forward, dgrad, wgrad
 # ------------------------------------------------------------------------------------------
@@ -366,6 +446,9 @@ LAYER_CASES = [
     # several 1024-row blocks and several LDS slabs in both residual products, all of them ragged
     ("blocks", 1120, 1056, 160, "bf16", 0.98),
     ("blocks", 1056, 608, 96, "f32", 0.95),
+    ("sparse", 512, 1024, 264, "bf16", 0.999),   # the sparsest operating point of Sec. 4.3 (0.2 % residual)
+    ("sparse", 96, 2048, 72, "f32", 0.999),
+    ("dense", 256, 256, 136, "bf16", 0.9),       # the densest residual the workspaces provide for
 ]
 
 
@@ -426,15 +509,14 @@ def _layer_once(Ad, Wd, dYd, alpha, ctx=None, Y=None, dW=None, ws=None):
 
 
 def test_layer_on_a_user_stream_equals_the_default_stream():
-    """Forward and weight gradient fork part of their work to the library's second stream and join it
-    back: on a stream of the caller's the results must be the ones of the default stream, bit for bit."""
+    """On a stream of the caller's the results must be the ones of the default stream, bit for bit."""
     A, W, dY = synth.small_case(384, 512, 264, "bf16", seed=4)
     Ad, Wd, dYd = dev(A, "bf16"), dev(W, "bf16"), dev(dY, "bf16")
     Y0, dW0 = _layer_once(Ad, Wd, dYd, 0.98)
     torch.cuda.synchronize()
     s = torch.cuda.Stream()
     with torch.cuda.stream(s):
-        for _ in range(3):   # back to back: every call's fork must wait for the call before it
+        for _ in range(3):   # back to back, sharing one workspace in stream order
             Y1, dW1 = _layer_once(Ad, Wd, dYd, 0.98)
     s.synchronize()
     assert torch.equal(Y0, Y1) and torch.equal(dW0, dW1)
@@ -449,7 +531,7 @@ def test_layer_in_a_captured_graph_equals_eager_on_every_replay():
     ws = b.Workspace()
     Yg = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     dWg = torch.empty((K, N), dtype=torch.float32, device="cuda")
-    _layer_once(Ad, Wd, dYd, 0.98, ctx=ctx, Y=Yg, dW=dWg, ws=ws)   # sizes the workspace, creates the second stream
+    _layer_once(Ad, Wd, dYd, 0.98, ctx=ctx, Y=Yg, dW=dWg, ws=ws)   # sizes the workspace
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
@@ -493,7 +575,7 @@ print("capture-first ok")
 
 
 def test_first_call_of_a_process_inside_a_capture():
-    """The second stream cannot be created during a capture: that call stays on one stream and must still be right."""
+    """The library keeps no state, so its very first call in a process may be made under stream capture."""
     import os
     import subprocess
     import sys
