@@ -152,6 +152,21 @@ def occ_thresholds(x: np.ndarray, alpha: float) -> Tuple[np.float32, np.float32]
     return F32(v[k]), F32(v[n - 1 - k])
 
 
+def occ_thresholds_per_token(x: np.ndarray, alpha: float) -> Tuple[np.ndarray, np.ndarray]:
+    """Second reading of the clamp's scope (Sec. 3.2 never names the axis the quantile is taken
+    over): one (lo, hi) pair per token, the order statistics of that row alone, with
+    k = floor((1 - alpha) * cols) elements allowed in each tail of every row.  Same two-sided,
+    no-interpolation definition as occ_thresholds; the residual density stays 2(1-alpha) and
+    every row gets at most 2k entries.  Returns (lo [R], hi [R]) fp32."""
+    x = np.asarray(x, dtype=F32)
+    cols = x.shape[1]
+    k = occ_tail_count(cols, alpha)
+    if not (0 <= 2 * k < cols):
+        raise ValueError("need 0 <= 2*floor((1-alpha)*cols) < cols")
+    v = np.sort(x, axis=1, kind="stable")
+    return v[:, k].astype(F32), v[:, cols - 1 - k].astype(F32)
+
+
 class Csr(NamedTuple):
     row_ptr: np.ndarray  # int64 [R+1]
     col_idx: np.ndarray  # int32 [nnz], ascending inside each row
@@ -167,14 +182,17 @@ class Csr(NamedTuple):
 
 def occ_clamp_residual(x: np.ndarray, lo: np.float32, hi: np.float32) -> Tuple[np.ndarray, Csr]:
     """Y_c = clamp(Y, lo, hi); Delta = Y - Y_c kept where the clamp changed the value
-    (Sec. 3.2).  val = fl32(x - threshold)."""
+    (Sec. 3.2).  val = fl32(x - threshold).  lo, hi: scalars (per-tensor thresholds) or one
+    value per row (per-token thresholds)."""
     x = np.asarray(x, dtype=F32)
-    lo = F32(lo)
-    hi = F32(hi)
+    lo = np.asarray(lo, dtype=F32)
+    hi = np.asarray(hi, dtype=F32)
+    if lo.ndim == 1:
+        lo, hi = lo[:, None], hi[:, None]
     below = x < lo
     above = x > hi
     xc = np.where(below, lo, np.where(above, hi, x)).astype(F32)
-    res = np.where(below, x - lo, np.where(above, x - hi, F32(0))).astype(F32)
+    res = np.where(below, (x - lo).astype(F32), np.where(above, (x - hi).astype(F32), F32(0))).astype(F32)
     mask = below | above
     rows, cols = np.nonzero(mask)            # row-major order: ascending cols in a row
     row_ptr = np.zeros(x.shape[0] + 1, dtype=np.int64)
@@ -270,7 +288,7 @@ def scaled_weights(W: np.ndarray, gamma_w: np.ndarray) -> np.ndarray:
 # The linear layer: forward, dgrad, wgrad
 # ----------------------------------------------------------------------------------
 class FwdState(NamedTuple):
-    lo: np.float32
+    lo: np.float32        # scalars (per-tensor thresholds) or vectors over tokens (per-token)
     hi: np.float32
     csr: Csr
     gamma_a: np.ndarray
@@ -279,20 +297,33 @@ class FwdState(NamedTuple):
     codes_wt: np.ndarray  # [N, K]
 
 
+def _thresholds(A: np.ndarray, alpha: float, scope: str):
+    if scope == "tensor":
+        return occ_thresholds(A, alpha)
+    if scope == "token":
+        return occ_thresholds_per_token(A, alpha)
+    raise ValueError(scope)
+
+
 def fp4_linear_fwd(A: np.ndarray, W: np.ndarray, alpha: float, out_dtype: str = "f32",
-                   rows: Optional[np.ndarray] = None) -> Tuple[np.ndarray, FwdState]:
+                   rows: Optional[np.ndarray] = None, scope: str = "tensor") -> Tuple[np.ndarray, FwdState]:
     """Y = dequant(Q(A_c) Q(W)) + Delta_A W   (Fig. 2; Sec. 3.2; App. C.2).
 
     A_c is A clamped at the per-tensor thresholds and quantized token-wise, W is
     quantized per output channel, the residual uses the unquantized W in fp64.
     `rows` restricts the output to a subset of tokens (thresholds and column scales
-    still come from the full tensors) so large shapes can be checked by sampling."""
+    still come from the full tensors) so large shapes can be checked by sampling.
+    scope = "token" takes the per-token reading of the thresholds (then lo, hi in the
+    returned state are vectors over all tokens)."""
     A = np.asarray(A, dtype=F32)
     W = np.asarray(W, dtype=F32)
-    lo, hi = occ_thresholds(A, alpha)
+    lo, hi = _thresholds(A, alpha, scope)
     codes_wt, gamma_w = quantize_cols(W)
     A_sel = A if rows is None else A[rows]
-    Ac, csr = occ_clamp_residual(A_sel, lo, hi)
+    if scope == "token" and rows is not None:
+        Ac, csr = occ_clamp_residual(A_sel, lo[rows], hi[rows])
+    else:
+        Ac, csr = occ_clamp_residual(A_sel, lo, hi)
     codes_a, gamma_a = quantize_rows(Ac)
     Y = dequant_gemm(codes_a, gamma_a, codes_wt, gamma_w)
     if csr.val.size:
@@ -314,7 +345,7 @@ def fp4_linear_bwd_dgrad(dY: np.ndarray, W: np.ndarray, out_dtype: str = "f32",
 
 def fp4_linear_bwd_wgrad(A: np.ndarray, dY: np.ndarray, W: np.ndarray, alpha: float,
                          dge_k: float = 5.0, dge_cap: float = 3.0,
-                         rows: Optional[np.ndarray] = None) -> np.ndarray:
+                         rows: Optional[np.ndarray] = None, scope: str = "tensor") -> np.ndarray:
     """dW = (A^T dY) (.) f'(W_scaled)   (Sec. 3.1 Eq. 3-6; App. C.2 Eq. 22).
 
     A^T dY is an FP4 GEMM contracting over tokens: clamped A scaled per input channel,
@@ -324,7 +355,7 @@ def fp4_linear_bwd_wgrad(A: np.ndarray, dY: np.ndarray, W: np.ndarray, alpha: fl
     A = np.asarray(A, dtype=F32)
     dY = np.asarray(dY, dtype=F32)
     W = np.asarray(W, dtype=F32)
-    lo, hi = occ_thresholds(A, alpha)
+    lo, hi = _thresholds(A, alpha, scope)
     Ac, csr = occ_clamp_residual(A, lo, hi)
     if rows is not None:
         Ac_sel = Ac[:, rows]
@@ -358,14 +389,15 @@ def fidelity(x: np.ndarray, xq: np.ndarray) -> Tuple[float, float, float]:
     return cos, mse, snr
 
 
-def dequantized_activation(x: np.ndarray, alpha: Optional[float], compensate: bool) -> np.ndarray:
+def dequantized_activation(x: np.ndarray, alpha: Optional[float], compensate: bool,
+                           scope: str = "tensor") -> np.ndarray:
     """Reconstruction of an activation tensor after token-wise FP4 quantization, with
     optional clamp and optional residual added back (the three rows of Table 1)."""
     x = np.asarray(x, dtype=F32)
     if alpha is None:
         xc, res = x, None
     else:
-        lo, hi = occ_thresholds(x, alpha)
+        lo, hi = _thresholds(x, alpha, scope)
         xc, csr = occ_clamp_residual(x, lo, hi)
         res = csr.to_dense() if compensate else None
     codes, gamma = quantize_rows(xc)

@@ -45,11 +45,17 @@ def fprime(x, k, cap):
             return cap if t == 0 else min(cap, (1 / k) * t ** (1 / k - 1))
 
 
-def brute_layer(A, W, dY, alpha, k, cap):
+def brute_layer(A, W, dY, alpha, k, cap, scope="tensor"):
     M, K = len(A), len(A[0])
     N = len(W[0])
-    lo, hi = thresholds([v for r in A for v in r], alpha)
-    Ac = [[min(max(v, lo), hi) for v in r] for r in A]
+    if scope == "tensor":
+        lo, hi = thresholds([v for r in A for v in r], alpha)
+        Ac = [[min(max(v, lo), hi) for v in r] for r in A]
+    else:   # one pair of order statistics per token
+        Ac = []
+        for r in A:
+            lo, hi = thresholds(list(r), alpha)
+            Ac.append([min(max(v, lo), hi) for v in r])
     dA_res = [[f32(F32(A[i][c]) - F32(Ac[i][c])) if A[i][c] != Ac[i][c] else 0.0 for c in range(K)]
               for i in range(M)]
     # forward
@@ -94,6 +100,21 @@ def test_tiny_layers_from_the_equations():
         assert np.allclose(dW, dWb, rtol=1e-6, atol=1e-12)
         if alpha < 1.0:
             assert st.csr.val.size == 2 * o.occ_tail_count(M * K, alpha) > 0
+
+
+def test_tiny_layers_from_the_equations_per_token_thresholds():
+    for seed, (M, K, N), alpha in ((0, (6, 16, 5), 0.9), (1, (8, 24, 7), 0.95), (2, (3, 10, 4), 1.0)):
+        A, W, dY = _case(seed, M, K, N)
+        Yb, dAb, dWb = brute_layer(A.tolist(), W.tolist(), dY.tolist(), alpha, 5.0, 3.0, scope="token")
+        Y, st = o.fp4_linear_fwd(A, W, alpha, "f32", scope="token")
+        dW = o.fp4_linear_bwd_wgrad(A, dY, W, alpha, 5.0, 3.0, scope="token")
+        assert np.allclose(Y, Yb, rtol=1e-6, atol=1e-9)
+        assert np.allclose(dW, dWb, rtol=1e-6, atol=1e-12)
+        if alpha < 1.0:
+            assert np.all(np.diff(st.csr.row_ptr) == 2 * o.occ_tail_count(K, alpha))
+        rows = np.array([0, M - 1])
+        Ys, _ = o.fp4_linear_fwd(A, W, alpha, "f32", rows=rows, scope="token")
+        assert np.array_equal(Y[rows], Ys)
 
 
 def test_row_sampling_matches_full_evaluation():

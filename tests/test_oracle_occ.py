@@ -119,3 +119,61 @@ def test_clamping_alone_helps_when_tokens_are_wide():
             for a, c in ((None, False), (0.999, False), (0.999, True), (0.99, True), (0.97, True))]
     for prev, nxt in zip(rows, rows[1:]):
         assert nxt[0] > prev[0] and nxt[1] < prev[1] and nxt[2] > prev[2], (prev, nxt)
+
+
+# ---- per-token thresholds (the second reading of the clamp's scope) ------------------------------
+def test_per_token_thresholds_are_each_rows_order_statistics():
+    rng = np.random.default_rng(7)
+    for (R, Ccols), alpha in (((5, 200), 0.97), ((3, 1000), 0.99), ((4, 64), 0.9), ((2, 4096), 0.999)):
+        x = rng.standard_t(3, size=(R, Ccols)).astype(F32)
+        x[0, rng.integers(0, Ccols, Ccols // 8)] = F32(-0.25)       # ties in one row
+        lo, hi = o.occ_thresholds_per_token(x, alpha)
+        k = o.occ_tail_count(Ccols, alpha)
+        assert lo.shape == hi.shape == (R,) and lo.dtype == F32
+        for r in range(R):
+            s_ = sorted(x[r].tolist())
+            assert float(lo[r]) == s_[k] and float(hi[r]) == s_[Ccols - 1 - k]
+            assert (x[r] < lo[r]).sum() <= k < (x[r] <= lo[r]).sum()
+            assert (x[r] > hi[r]).sum() <= k < (x[r] >= hi[r]).sum()
+            # a one-row tensor: both readings are the same thing
+            l1, h1 = o.occ_thresholds(x[r:r + 1], alpha)
+            assert l1 == lo[r] and h1 == hi[r]
+    with pytest.raises(ValueError):
+        o.occ_thresholds_per_token(np.zeros((2, 8), F32), 0.4)
+
+
+def test_per_token_clamp_hand_example_and_structure():
+    x = np.array([[-9, 1, 2, 30, 0, 4], [100, -50, 7, 8, 9, 10]], F32)
+    lo, hi = o.occ_thresholds_per_token(x, 0.8)          # k = floor(0.2 * 6) = 1 per tail and row
+    assert lo.tolist() == [0, 7] and hi.tolist() == [4, 10]
+    xc, csr = o.occ_clamp_residual(x, lo, hi)
+    assert xc.tolist() == [[0, 1, 2, 4, 0, 4], [10, 7, 7, 8, 9, 10]]
+    assert csr.row_ptr.tolist() == [0, 2, 4]
+    assert csr.col_idx.tolist() == [0, 3, 0, 1] and csr.val.tolist() == [-9, 26, 90, -57]
+    rng = np.random.default_rng(8)
+    x = rng.normal(size=(64, 512)).astype(F32)
+    x[:, 9] *= 25
+    for alpha in (0.999, 0.99, 0.97):
+        k = o.occ_tail_count(512, alpha)
+        lo, hi = o.occ_thresholds_per_token(x, alpha)
+        xc, csr = o.occ_clamp_residual(x, lo, hi)
+        assert np.all(np.diff(csr.row_ptr) == 2 * k)         # continuous data: every row exactly 2k entries
+        assert np.array_equal(xc.min(axis=1), lo) and np.array_equal(xc.max(axis=1), hi)
+        rec = xc.astype(np.float64) + csr.to_dense()
+        ulp = np.spacing(np.abs(csr.to_dense()).astype(F32)).astype(np.float64)
+        assert np.all(np.abs(rec - x) <= 0.5 * ulp)
+        assert np.all(csr.val != 0)
+    lo, hi = o.occ_thresholds_per_token(x, 1.0)
+    xc, csr = o.occ_clamp_residual(x, lo, hi)
+    assert np.array_equal(xc, x) and csr.val.size == 0
+
+
+def test_per_token_reading_keeps_the_order_of_table_1():
+    rng = np.random.default_rng(3)
+    x = rng.normal(size=(64, 4096)).astype(F32)
+    idx = rng.integers(0, 4096, size=64)
+    x[np.arange(64), idx] = 40.0 * np.sign(x[np.arange(64), idx])
+    rows = [o.fidelity(x, o.dequantized_activation(x, a, c, scope="token"))
+            for a, c in ((None, False), (0.999, False), (0.999, True), (0.99, True), (0.97, True))]
+    for prev, nxt in zip(rows, rows[1:]):
+        assert nxt[0] > prev[0] and nxt[1] < prev[1] and nxt[2] > prev[2], (prev, nxt)
