@@ -79,7 +79,8 @@ typedef enum {
   FP4_OP_FWD = 2,
   FP4_OP_DGRAD = 3,
   FP4_OP_WGRAD = 4,
-  FP4_OP_SPMM = 5      /* (M=P rows of S, K=Q, N)                                        */
+  FP4_OP_SPMM = 5,     /* (M=P rows of S, K=Q, N)                                        */
+  FP4_OP_PREPARE = 6   /* fp4_prepare_weights (M ignored)                                 */
 } fp4_op;
 
 /* What the forward pass leaves for the weight-gradient pass (Sec. 3.1 needs the
@@ -137,6 +138,33 @@ int occ_clamp_residual(const void* x, fp4_dtype dt, int64_t rows, int64_t cols, 
 int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
                    double alpha, void* Y, const fp4_fwd_ctx* saved,
                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* The two quantizations of W that a training step needs (Sec. 4.1: scales live on the
+ * non-contracted axis of each GEMM, so the forward pass and the activation gradient each need
+ * their own).  W only changes at an optimizer step: with several micro-batches per step the
+ * caller prepares them once per weight version and passes them to the *_cached entry points,
+ * which then launch no quantization of W.  All members are caller-allocated device buffers. */
+typedef struct {
+  uint8_t* qWt;      /* [N x K/2] codes per output channel, transposed: forward's right operand */
+  float*   gamma_W;  /* [N]       their scales (the ones the DGE factor uses)                   */
+  uint8_t* qWk;      /* [K x N/2] codes per input channel: the activation gradient's operand    */
+  float*   gamma_Wk; /* [K]       their scales                                                  */
+} fp4_weight_cache;
+
+/* Fills *wq from W [K x N] (K, N multiples of 32).  Bit-identical to what fp4_linear_fwd and
+ * fp4_linear_bwd_dgrad compute internally.  Workspace: fp4_workspace_bytes(FP4_OP_PREPARE, 0, K, N, dt). */
+int fp4_prepare_weights(const void* W, fp4_dtype dt, int64_t K, int64_t N, const fp4_weight_cache* wq,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* fp4_linear_fwd / fp4_linear_bwd_dgrad with W's quantizations taken from *wq (read only).  The
+ * forward still needs the unquantized W for the residual product.  saved->gamma_W receives a copy of
+ * wq->gamma_W unless it is the same pointer.  Workspaces as for the plain entry points. */
+int fp4_linear_fwd_cached(const void* A, const void* W, const fp4_weight_cache* wq, fp4_dtype dt,
+                          int64_t M, int64_t K, int64_t N, double alpha, void* Y, const fp4_fwd_ctx* saved,
+                          void* workspace, size_t workspace_bytes, void* stream);
+int fp4_linear_bwd_dgrad_cached(const void* dY, const fp4_weight_cache* wq, fp4_dtype dt,
+                                int64_t M, int64_t K, int64_t N, void* dA,
+                                void* workspace, size_t workspace_bytes, void* stream);
 
 /* Activation gradient: dA = dY W^T as an FP4 GEMM contracting over output channels,
  * dY scaled per token and W per input channel (scales on the non-contracted axes,

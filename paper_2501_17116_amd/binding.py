@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libfp4mi.so")
 
 FP4_F32, FP4_BF16 = 0, 1
 FP4_AXIS_ROW, FP4_AXIS_COL = 0, 1
-FP4_OP_QUANTIZE, FP4_OP_OCC, FP4_OP_FWD, FP4_OP_DGRAD, FP4_OP_WGRAD, FP4_OP_SPMM = range(6)
+FP4_OP_QUANTIZE, FP4_OP_OCC, FP4_OP_FWD, FP4_OP_DGRAD, FP4_OP_WGRAD, FP4_OP_SPMM, FP4_OP_PREPARE = range(7)
 
 _lib = None
 
@@ -33,6 +33,10 @@ class fp4_fwd_ctx(C.Structure):
     _fields_ = [("gamma_W", C.c_void_p), ("thresholds", C.c_void_p), ("row_ptr", C.c_void_p),
                 ("col_idx", C.c_void_p), ("val", C.c_void_p), ("capacity", C.c_int64),
                 ("nnz", C.c_void_p)]
+
+
+class fp4_weight_cache(C.Structure):
+    _fields_ = [("qWt", C.c_void_p), ("gamma_W", C.c_void_p), ("qWk", C.c_void_p), ("gamma_Wk", C.c_void_p)]
 
 
 def lib() -> C.CDLL:
@@ -57,6 +61,12 @@ def lib() -> C.CDLL:
         L.fp4_linear_bwd_dgrad.argtypes = [vp, vp, i32, i64, i64, i64, vp, vp, sz, vp]
         L.fp4_linear_bwd_wgrad.argtypes = [vp, vp, vp, i32, i64, i64, i64, C.POINTER(fp4_fwd_ctx), f32, f32,
                                            vp, vp, sz, vp]
+        L.fp4_prepare_weights.argtypes = [vp, i32, i64, i64, C.POINTER(fp4_weight_cache), vp, sz, vp]
+        L.fp4_linear_fwd_cached.argtypes = [vp, vp, C.POINTER(fp4_weight_cache), i32, i64, i64, i64, f64, vp,
+                                            C.POINTER(fp4_fwd_ctx), vp, sz, vp]
+        L.fp4_linear_bwd_dgrad_cached.argtypes = [vp, C.POINTER(fp4_weight_cache), i32, i64, i64, i64, vp, vp, sz, vp]
+        for name in ("fp4_prepare_weights", "fp4_linear_fwd_cached", "fp4_linear_bwd_dgrad_cached"):
+            getattr(L, name).restype = i32
         L.fp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, i32, i64, vp]
         L.fp4_unpack.argtypes = [vp, i64, i64, vp, vp]
         L.fp4_dge_apply.argtypes = [vp, vp, i32, vp, i64, i64, f32, f32, vp, vp]
@@ -233,6 +243,63 @@ def fp4_linear_fwd(A: torch.Tensor, W: torch.Tensor, alpha: float, ctx: Optional
     _check(lib().fp4_linear_fwd(_ptr(A), _ptr(W), _dt(A), M, K, N, float(alpha), _ptr(Y), C.byref(ctx.c),
                                 _ptr(w), w.numel(), _stream()), "fp4_linear_fwd")
     return Y, ctx
+
+
+class WeightCache:
+    """Device buffers for W's two quantizations (forward's per-output-channel, dgrad's per-input-channel)."""
+
+    def __init__(self, K: int, N: int, device="cuda"):
+        self.K, self.N = K, N
+        self.qWt = torch.empty((N, K // 2), dtype=torch.uint8, device=device)
+        self.gamma_W = torch.empty(N, dtype=torch.float32, device=device)
+        self.qWk = torch.empty((K, N // 2), dtype=torch.uint8, device=device)
+        self.gamma_Wk = torch.empty(K, dtype=torch.float32, device=device)
+        self.c = fp4_weight_cache(self.qWt.data_ptr(), self.gamma_W.data_ptr(), self.qWk.data_ptr(),
+                                  self.gamma_Wk.data_ptr())
+
+
+def fp4_prepare_weights(W: torch.Tensor, wq: Optional[WeightCache] = None, ws: Optional[Workspace] = None) -> WeightCache:
+    _dev_check(W)
+    K, N = W.shape
+    if wq is None:
+        wq = WeightCache(K, N, W.device)
+    w = _ws(workspace_bytes(FP4_OP_PREPARE, 0, K, N, _dt(W)), ws)
+    _check(lib().fp4_prepare_weights(_ptr(W), _dt(W), K, N, C.byref(wq.c), _ptr(w), w.numel(), _stream()),
+           "fp4_prepare_weights")
+    return wq
+
+
+def fp4_linear_fwd_cached(A: torch.Tensor, W: torch.Tensor, wq: WeightCache, alpha: float,
+                          ctx: Optional[FwdCtx] = None, Y: Optional[torch.Tensor] = None,
+                          ws: Optional[Workspace] = None):
+    _dev_check(A, W, Y)
+    M, K = A.shape
+    K2, N = W.shape
+    if K2 != K or A.dtype != W.dtype or (wq.K, wq.N) != (K, N):
+        raise ValueError("A [M,K], W [K,N] and the weight cache must agree")
+    if ctx is None:
+        ctx = FwdCtx(M, K, N, alpha, A.device)
+    if Y is None:
+        Y = torch.empty((M, N), dtype=A.dtype, device=A.device)
+    w = _ws(workspace_bytes(FP4_OP_FWD, M, K, N, _dt(A)), ws)
+    _check(lib().fp4_linear_fwd_cached(_ptr(A), _ptr(W), C.byref(wq.c), _dt(A), M, K, N, float(alpha), _ptr(Y),
+                                       C.byref(ctx.c), _ptr(w), w.numel(), _stream()), "fp4_linear_fwd_cached")
+    return Y, ctx
+
+
+def fp4_linear_bwd_dgrad_cached(dY: torch.Tensor, wq: WeightCache, dA: Optional[torch.Tensor] = None,
+                                ws: Optional[Workspace] = None) -> torch.Tensor:
+    _dev_check(dY, dA)
+    M, N = dY.shape
+    K = wq.K
+    if wq.N != N:
+        raise ValueError("dY [M,N] and the weight cache must agree in N")
+    if dA is None:
+        dA = torch.empty((M, K), dtype=dY.dtype, device=dY.device)
+    w = _ws(workspace_bytes(FP4_OP_DGRAD, M, K, N, _dt(dY)), ws)
+    _check(lib().fp4_linear_bwd_dgrad_cached(_ptr(dY), C.byref(wq.c), _dt(dY), M, K, N, _ptr(dA), _ptr(w),
+                                             w.numel(), _stream()), "fp4_linear_bwd_dgrad_cached")
+    return dA
 
 
 def fp4_linear_bwd_dgrad(dY: torch.Tensor, W: torch.Tensor, dA: Optional[torch.Tensor] = None,

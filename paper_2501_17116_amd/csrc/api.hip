@@ -35,7 +35,7 @@ int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, con
                              int32_t* t_idx, float* t_val, int32_t* u_idx, float* u_val, int32_t* scratch,
                              hipStream_t s);
 int64_t fp4_spmm_long_list_cap(int64_t capacity);
-int64_t fp4_csr_transpose_scratch_words(int64_t Q);
+int64_t fp4_csr_transpose_scratch_words(int64_t P, int64_t Q);
 int fp4_launch_order_rows(const int64_t* row_ptr, int64_t rows, int64_t nidx, int64_t capacity,
                           const int32_t* u_idx, const float* u_val, int32_t* idx, float* val, hipStream_t s);
 int64_t fp4_spmm_scratch_words(int64_t list_cap, int64_t Q, int64_t N);
@@ -139,7 +139,7 @@ WgradWs carve_wgrad(Carver& c, int64_t M, int64_t K, int64_t N) {
   w.t_val = c.take<float>((size_t)cap);
   w.u_idx = c.take<int32_t>((size_t)cap);
   w.u_val = c.take<float>((size_t)cap);
-  w.t_scratch = c.take<int32_t>((size_t)fp4_csr_transpose_scratch_words(K));
+  w.t_scratch = c.take<int32_t>((size_t)fp4_csr_transpose_scratch_words(M, K));
   w.sp_scratch = c.take<int32_t>((size_t)fp4_spmm_scratch_words(fp4_spmm_long_list_cap(cap), M, N));
   return w;
 }
@@ -174,6 +174,7 @@ extern "C" size_t fp4_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, f
     case FP4_OP_FWD: carve_fwd(c, M, K, N, dt); break;
     case FP4_OP_DGRAD: carve_dgrad(c, M, K, N); break;
     case FP4_OP_WGRAD: carve_wgrad(c, M, K, N); break;
+    case FP4_OP_PREPARE: c.take<uint32_t>((size_t)fp4_quantize_cols_scratch_words(K, N)); break;
     case FP4_OP_SPMM: c.take<int32_t>((size_t)fp4_spmm_scratch_words(M + 2, K, N)); break;   // long-row list: at most M rows
     default: return 0;
   }
@@ -216,9 +217,19 @@ extern "C" int occ_clamp_residual(const void* x, fp4_dtype dt, int64_t rows, int
   return rc;
 }
 
-extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
-                              double alpha, void* Y, const fp4_fwd_ctx* saved, void* workspace,
-                              size_t workspace_bytes, void* stream) {
+namespace {
+__global__ void copy_f32_kernel(const float* src, float* dst, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
+bool cache_ok(const fp4_weight_cache* wq) {
+  return wq && wq->qWt && wq->gamma_W && wq->qWk && wq->gamma_Wk && aligned16(wq->qWt) && aligned16(wq->qWk);
+}
+
+// Forward pass; wq == nullptr: W is quantized here, into the workspace and saved->gamma_W.
+int fwd_impl(const void* A, const void* W, const fp4_weight_cache* wq, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
+             double alpha, void* Y, const fp4_fwd_ctx* saved, void* workspace, size_t workspace_bytes, void* stream) {
   if (!dtype_ok(dt)) return FP4_ERR_DTYPE;
   if (M <= 0 || K <= 0 || N <= 0 || (K % 32) != 0 || (N % 8) != 0) return FP4_ERR_SHAPE;
   if (!(alpha > 0.5) || !(alpha <= 1.0)) return FP4_ERR_ARG;
@@ -238,9 +249,20 @@ extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_
   Carver c(reinterpret_cast<void*>(align_up((size_t)(uintptr_t)workspace, 256)));
   FwdWs w = carve_fwd(c, M, K, N, dt);
 
-  // W per output channel -> codes [N x K/2], scales kept for the DGE term of the backward pass
-  int rc = fp4_launch_quantize_cols(W, bf16, K, N, N, nullptr, w.qWt, saved->gamma_W, w.amax, s);
-  if (rc) return rc;
+  // W per output channel -> codes [N x K/2], scales kept for the DGE term of the backward pass;
+  // from the cache when the caller prepared one (W does not change between micro-batches)
+  int rc = FP4_OK;
+  const uint8_t* qWt = w.qWt;
+  if (wq) {
+    qWt = wq->qWt;
+    if (saved->gamma_W != wq->gamma_W) {
+      hipLaunchKernelGGL(copy_f32_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, wq->gamma_W, saved->gamma_W, N);
+      if (hipGetLastError() != hipSuccess) return FP4_ERR_HIP;
+    }
+  } else {
+    rc = fp4_launch_quantize_cols(W, bf16, K, N, N, nullptr, w.qWt, saved->gamma_W, w.amax, s);
+    if (rc) return rc;
+  }
   const float* addend = nullptr;
   if (occ) {
     const int64_t cap = std::min(saved->capacity, provisioned_entries(M, K));  // never beyond the temporaries
@@ -273,17 +295,17 @@ extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_
       if (hipGetLastError() != hipSuccess) return FP4_ERR_HIP;
     }
   }
-  return fp4_launch_gemm(w.qA, w.gA, w.qWt, saved->gamma_W, M, N, K, addend, Y, bf16, N, nullptr, 0, 0,
+  return fp4_launch_gemm(w.qA, w.gA, qWt, saved->gamma_W, M, N, K, addend, Y, bf16, N, nullptr, 0, 0,
                          nullptr, 0.0f, 0.0f, s);
 }
 
-extern "C" int fp4_linear_bwd_dgrad(const void* dY, const void* W, fp4_dtype dt, int64_t M, int64_t K,
-                                    int64_t N, void* dA, void* workspace, size_t workspace_bytes,
-                                    void* stream) {
+// Activation gradient; wq == nullptr: W is quantized per input channel here.
+int dgrad_impl(const void* dY, const void* W, const fp4_weight_cache* wq, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
+               void* dA, void* workspace, size_t workspace_bytes, void* stream) {
   if (!dtype_ok(dt)) return FP4_ERR_DTYPE;
   if (M <= 0 || K <= 0 || N <= 0 || (N % 32) != 0 || (K % 8) != 0) return FP4_ERR_SHAPE;
-  if (!dY || !W || !dA) return FP4_ERR_NULL;
-  if (!aligned16(dY) || !aligned16(W) || !aligned16(dA)) return FP4_ERR_ARG;
+  if (!dY || (!W && !wq) || !dA) return FP4_ERR_NULL;
+  if (!aligned16(dY) || (W && !aligned16(W)) || !aligned16(dA)) return FP4_ERR_ARG;
   if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_DGRAD, M, K, N, dt)) return FP4_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   const int bf16 = dt == FP4_BF16;
@@ -291,10 +313,63 @@ extern "C" int fp4_linear_bwd_dgrad(const void* dY, const void* W, fp4_dtype dt,
   DgradWs w = carve_dgrad(c, M, K, N);
   int rc = fp4_launch_quantize_rows(dY, bf16, M, N, N, w.qdY, w.gdY, s);   // per token
   if (rc) return rc;
-  rc = fp4_launch_quantize_rows(W, bf16, K, N, N, w.qW, w.gWk, s);         // per input channel
+  const uint8_t* qW = w.qW;
+  const float* gWk = w.gWk;
+  if (wq) {
+    qW = wq->qWk;
+    gWk = wq->gamma_Wk;
+  } else {
+    rc = fp4_launch_quantize_rows(W, bf16, K, N, N, w.qW, w.gWk, s);       // per input channel
+    if (rc) return rc;
+  }
+  return fp4_launch_gemm(w.qdY, w.gdY, qW, gWk, M, K, N, nullptr, dA, bf16, K, nullptr, 0, 0, nullptr, 0.0f, 0.0f, s);
+}
+}  // namespace
+
+extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
+                              double alpha, void* Y, const fp4_fwd_ctx* saved, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  return fwd_impl(A, W, nullptr, dt, M, K, N, alpha, Y, saved, workspace, workspace_bytes, stream);
+}
+
+extern "C" int fp4_linear_fwd_cached(const void* A, const void* W, const fp4_weight_cache* wq, fp4_dtype dt,
+                                     int64_t M, int64_t K, int64_t N, double alpha, void* Y,
+                                     const fp4_fwd_ctx* saved, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+  if (!wq) return FP4_ERR_NULL;
+  if (!cache_ok(wq)) return wq->qWt && wq->gamma_W && wq->qWk && wq->gamma_Wk ? FP4_ERR_ARG : FP4_ERR_NULL;
+  return fwd_impl(A, W, wq, dt, M, K, N, alpha, Y, saved, workspace, workspace_bytes, stream);
+}
+
+extern "C" int fp4_prepare_weights(const void* W, fp4_dtype dt, int64_t K, int64_t N, const fp4_weight_cache* wq,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+  if (!dtype_ok(dt)) return FP4_ERR_DTYPE;
+  if (K <= 0 || N <= 0 || (K % 32) != 0 || (N % 32) != 0) return FP4_ERR_SHAPE;
+  if (!W || !wq) return FP4_ERR_NULL;
+  if (!cache_ok(wq)) return wq->qWt && wq->gamma_W && wq->qWk && wq->gamma_Wk ? FP4_ERR_ARG : FP4_ERR_NULL;
+  if (!aligned16(W)) return FP4_ERR_ARG;
+  if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_PREPARE, 0, K, N, dt)) return FP4_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const int bf16 = dt == FP4_BF16;
+  uint32_t* amax = reinterpret_cast<uint32_t*>(align_up((size_t)(uintptr_t)workspace, 256));
+  int rc = fp4_launch_quantize_cols(W, bf16, K, N, N, nullptr, wq->qWt, wq->gamma_W, amax, s);   // forward's operand
   if (rc) return rc;
-  return fp4_launch_gemm(w.qdY, w.gdY, w.qW, w.gWk, M, K, N, nullptr, dA, bf16, K, nullptr, 0, 0, nullptr,
-                         0.0f, 0.0f, s);
+  return fp4_launch_quantize_rows(W, bf16, K, N, N, wq->qWk, wq->gamma_Wk, s);                   // dgrad's operand
+}
+
+extern "C" int fp4_linear_bwd_dgrad(const void* dY, const void* W, fp4_dtype dt, int64_t M, int64_t K,
+                                    int64_t N, void* dA, void* workspace, size_t workspace_bytes,
+                                    void* stream) {
+  if (!W) return FP4_ERR_NULL;
+  return dgrad_impl(dY, W, nullptr, dt, M, K, N, dA, workspace, workspace_bytes, stream);
+}
+
+extern "C" int fp4_linear_bwd_dgrad_cached(const void* dY, const fp4_weight_cache* wq, fp4_dtype dt, int64_t M,
+                                           int64_t K, int64_t N, void* dA, void* workspace,
+                                           size_t workspace_bytes, void* stream) {
+  if (!wq) return FP4_ERR_NULL;
+  if (!cache_ok(wq)) return wq->qWt && wq->gamma_W && wq->qWk && wq->gamma_Wk ? FP4_ERR_ARG : FP4_ERR_NULL;
+  return dgrad_impl(dY, nullptr, wq, dt, M, K, N, dA, workspace, workspace_bytes, stream);
 }
 
 extern "C" int fp4_linear_bwd_wgrad(const void* A, const void* dY, const void* W, fp4_dtype dt, int64_t M,

@@ -161,15 +161,165 @@ struct RowArgs {
   float* tmp_val;
   const int64_t* row_ptr;  // OCC: [rows + 1] first entry slot of every row (counted beforehand)
   int64_t rows, cols, ld, capacity;
+  // per-token thresholds (TOKEN variants): found inside the kernel, row by row
+  float* thr_out;          // [rows][2] {lo, hi} of every row
+  int32_t* row_cnt;        // [rows] entries the row produced; they start at slot row * stride_e
+  int64_t tail_k;          // elements allowed in each tail of a row
+  int64_t stride_e;        // entry slots reserved per row (2 tail_k)
 };
 
-template <class DT, bool OCC, int TPR, int NV>
+// ------------------------------------------------------------------------------------------
+// Per-token order statistics (Sec. 3.2 with the quantile taken over each token's channels):
+// lo = the row's (k+1)-th smallest element, hi = its (k+1)-th largest, exactly, by radix selection
+// on order-preserving integer keys, eight bits per pass (two passes for bf16 data, four for
+// fp32), on the row as it sits in the registers of its TPR threads.  The histogram of a pass lives
+// in LDS, replicated by lane so that the few exponent values real data uses do not serialize the
+// atomics; after the first pass only the elements inside the two bins that hold the targets take
+// part.  All counts are exact, so the result does not depend on the order of the atomics.
+// ------------------------------------------------------------------------------------------
+constexpr int TS_WORDS = 2048;   // LDS words per row: 256 bins x 8 replicas, or 2 targets x 256 bins x 4 replicas
+
+template <int TPR>
+FP4_D void row_sync() {
+  if constexpr (TPR == 256) {
+    __syncthreads();
+  } else {   // one wave per row: its LDS operations complete in order; only the compiler must not reorder them
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+}
+
+// 32-bit order key of an fp32 pattern; for bf16 data the pattern is the value widened (low half
+// zero) and only the key's upper 16 bits matter (the lower ones are the same for equal values).
+FP4_D uint32_t order_key32(uint32_t bits) { return bits ^ ((uint32_t)((int32_t)bits >> 31) | 0x80000000u); }
+
+template <class DT, int TPR, int NV>
+FP4_D void select_row_thresholds(const Raw8<DT> (&cache)[NV], bool row_ok, int t, int64_t cols, int64_t nunits,
+                                 int64_t tail_k, uint32_t* hist /* this row's TS_WORDS */, uint32_t* s_sel /* [>= 8] */,
+                                 float& lo, float& hi) {
+  constexpr int KEY_BITS = __is_same(DT, BF16) ? 16 : 32;
+  constexpr int PASSES = KEY_BITS / 8;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t rank[2] = {(uint32_t)tail_k, (uint32_t)(cols - 1 - tail_k)};   // 0-based from below
+  uint32_t prefix[2] = {0u, 0u};                                           // key bits fixed so far, right-aligned
+#pragma unroll 1
+  for (int p = 0; p < PASSES; ++p) {
+    for (int i = t; i < TS_WORDS / 4; i += TPR) reinterpret_cast<u32x4*>(hist)[i] = u32x4{0u, 0u, 0u, 0u};
+    row_sync<TPR>();
+    const int dshift = 32 - 8 * (p + 1);    // digit = (key >> dshift) & 255
+    const int pshift = 32 - 8 * p;          // bits above the digit
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+      const int64_t unit = (int64_t)u * TPR + t;
+      const int valid = (row_ok && unit < nunits) ? (int)min((int64_t)8, cols - unit * 8) : 0;
+      uint32_t bits[8];
+      if constexpr (__is_same(DT, BF16)) {
+        bits[0] = cache[u].r.x << 16; bits[1] = cache[u].r.x & 0xffff0000u;
+        bits[2] = cache[u].r.y << 16; bits[3] = cache[u].r.y & 0xffff0000u;
+        bits[4] = cache[u].r.z << 16; bits[5] = cache[u].r.z & 0xffff0000u;
+        bits[6] = cache[u].r.w << 16; bits[7] = cache[u].r.w & 0xffff0000u;
+      } else {
+        bits[0] = f2u(cache[u].a.x); bits[1] = f2u(cache[u].a.y); bits[2] = f2u(cache[u].a.z); bits[3] = f2u(cache[u].a.w);
+        bits[4] = f2u(cache[u].b.x); bits[5] = f2u(cache[u].b.y); bits[6] = f2u(cache[u].b.z); bits[7] = f2u(cache[u].b.w);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (e < valid) {
+          const uint32_t key = order_key32(bits[e]);
+          const uint32_t d = (key >> dshift) & 255u;
+          if (p == 0) {
+            atomicAdd(&hist[d * 8 + (lane & 7)], 1u);
+          } else {
+            const uint32_t above = key >> pshift;
+            if (above == prefix[0]) atomicAdd(&hist[d * 4 + (lane & 3)], 1u);
+            if (above == prefix[1]) atomicAdd(&hist[1024 + d * 4 + (lane & 3)], 1u);
+          }
+        }
+      }
+    }
+    row_sync<TPR>();
+    // the bin that holds each target's rank: exclusive prefix of the bin counts over the row's threads
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      constexpr int BPT = 256 / TPR;   // bins per thread: 4 (one wave) or 1 (the workgroup)
+      uint32_t c[BPT], sum = 0;
+#pragma unroll
+      for (int j = 0; j < BPT; ++j) {
+        const int b = t * BPT + j;
+        if (p == 0) {
+          const u32x4 q0 = reinterpret_cast<const u32x4*>(hist)[b * 2], q1 = reinterpret_cast<const u32x4*>(hist)[b * 2 + 1];
+          c[j] = q0.x + q0.y + q0.z + q0.w + q1.x + q1.y + q1.z + q1.w;
+        } else {
+          const u32x4 q0 = reinterpret_cast<const u32x4*>(hist)[s * 256 + b];
+          c[j] = q0.x + q0.y + q0.z + q0.w;
+        }
+        sum += c[j];
+      }
+      uint32_t incl = sum;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t up = (uint32_t)__shfl_up((int)incl, o, 64);
+        if (lane >= o) incl += up;
+      }
+      if constexpr (TPR == 256) {
+        if (lane == 63) s_sel[4 + wave] = incl;
+        __syncthreads();
+        for (int w = 0; w < wave; ++w) incl += s_sel[4 + w];
+      }
+      const uint32_t r = rank[s];
+      uint32_t excl = incl - sum;
+      const bool mine = excl <= r && r < incl;   // exactly one thread of the row (the counts add up to > r)
+      uint32_t found_bin = 0, found_rank = 0;
+      if (mine) {
+        int j = 0;
+#pragma unroll
+        for (int q = 0; q < BPT - 1; ++q)
+          if (j == q && excl + c[q] <= r) { excl += c[q]; ++j; }
+        found_bin = (uint32_t)(t * BPT + j);
+        found_rank = r - excl;
+      }
+      if constexpr (TPR == 256) {
+        if (mine) { s_sel[0] = found_bin; s_sel[1] = found_rank; }
+        __syncthreads();
+        found_bin = s_sel[0]; found_rank = s_sel[1];
+        __syncthreads();   // s_sel is rewritten for the other target / the next pass
+      } else {
+        const unsigned long long m = __ballot(mine);
+        const int src = m ? __builtin_ctzll(m) : 0;
+        found_bin = (uint32_t)__shfl((int)found_bin, src, 64);
+        found_rank = (uint32_t)__shfl((int)found_rank, src, 64);
+      }
+      rank[s] = found_rank;
+      prefix[s] = (prefix[s] << 8) | found_bin;
+    }
+    row_sync<TPR>();   // everyone has read the histogram before it is cleared again
+  }
+  // the prefixes are now the full keys (upper 16 bits for bf16 data): decode
+  uint32_t k0 = prefix[0], k1 = prefix[1];
+  if constexpr (__is_same(DT, BF16)) {
+    // upper half of the 32-bit key of a widened bf16 value; the lower half of the key of a
+    // negative value is all ones, of a non-negative one all zeros
+    k0 = (k0 << 16) | ((k0 & 0x8000u) ? 0u : 0xffffu);
+    k1 = (k1 << 16) | ((k1 & 0x8000u) ? 0u : 0xffffu);
+  }
+  lo = u2f(f32_from_order_key(k0));
+  hi = u2f(f32_from_order_key(k1));
+}
+
+// TOKEN: the thresholds are the row's own order statistics, found here (the row is in registers
+// anyway), so the tensor is read exactly once; a row's entries go to its own run of stride_e slots
+// and the row's entry count to row_cnt (the caller compacts).
+template <class DT, bool OCC, int TPR, int NV, bool TOKEN = false>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
   constexpr int RPB = 256 / TPR;
   constexpr bool CACHED = NV > 0;
+  static_assert(!TOKEN || (OCC && CACHED), "per-token thresholds need the row in registers");
   __shared__ float s_max[4];
   __shared__ int s_cnt[4];
   __shared__ int s_round[CACHED ? NV : 1][4];
+  __shared__ __attribute__((aligned(16))) uint32_t s_hist[TOKEN ? RPB * TS_WORDS : 4];
+  __shared__ uint32_t s_sel[8];
 
   const int tid = threadIdx.x;
   const int t = tid % TPR;
@@ -182,7 +332,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
   const int64_t xoff = row * a.ld;
 
   float lo = 0.0f, hi = 0.0f;
-  if (OCC) { lo = a.thr[0]; hi = a.thr[1]; }
+  if (OCC && !TOKEN) { lo = a.thr[0]; hi = a.thr[1]; }
 
   Raw8<DT> cache[CACHED ? NV : 1];
   float amax = 0.0f;
@@ -206,6 +356,11 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
       const int64_t unit = (int64_t)u * TPR + t;
       const int valid = (row_ok && unit < nunits) ? (int)min((int64_t)8, a.cols - unit * 8) : 0;
       load_raw8<DT>(a.x, xoff + unit * 8, valid, cache[u]);   // valid <= 0 reads nothing and yields zeros
+    }
+    if constexpr (TOKEN) {
+      select_row_thresholds<DT, TPR, NV>(cache, row_ok, t, a.cols, nunits, a.tail_k,
+                                         s_hist + (TPR == 256 ? 0 : wave * TS_WORDS), s_sel, lo, hi);
+      if (row_ok && t == 0) { a.thr_out[2 * row] = lo; a.thr_out[2 * row + 1] = hi; }
     }
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
@@ -277,8 +432,14 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
   int64_t upos[CACHED ? NV : 1];
   bool emit = false;
   if (OCC) {
-    const long long base = row_ok ? a.row_ptr[row] : 0;
-    emit = row_ok && (a.row_ptr[row + 1] <= a.capacity);
+    long long base;
+    if constexpr (TOKEN) {
+      base = row * a.stride_e;
+      emit = row_ok;
+    } else {
+      base = row_ok ? a.row_ptr[row] : 0;
+      emit = row_ok && (a.row_ptr[row + 1] <= a.capacity);
+    }
     if constexpr (CACHED) {
       // the scans run on three counts per register, 10 bits each (a wave's sum is at most 512)
       constexpr int NP = (NV + 2) / 3;
@@ -333,6 +494,9 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
         }
         upos[u] = base + before + ex;
         before += total;
+      }
+      if constexpr (TOKEN) {
+        if (row_ok && t == 0) a.row_cnt[row] = before;
       }
     } else {
       int incl = cnt;
@@ -453,6 +617,38 @@ int launch_rows(const RowArgs& a, hipStream_t s) {
   }
   FP4_CHECK_LAUNCH();
   return FP4_OK;
+}
+
+// Per-token thresholds: rows up to 16384 elements (the register-cached variants).
+template <class DT>
+int launch_rows_token(const RowArgs& a, hipStream_t s) {
+  const int64_t nunits = (a.cols + 7) / 8;
+  const dim3 g4((unsigned)((a.rows + 3) / 4)), g1((unsigned)a.rows), b(256);
+  if (nunits <= 64 * 2) hipLaunchKernelGGL((quantize_rows_kernel<DT, true, 64, 2, true>), g4, b, 0, s, a);
+  else if (nunits <= 64 * 4) hipLaunchKernelGGL((quantize_rows_kernel<DT, true, 64, 4, true>), g4, b, 0, s, a);
+  else if (nunits <= 64 * 8) hipLaunchKernelGGL((quantize_rows_kernel<DT, true, 64, 8, true>), g4, b, 0, s, a);
+  else if (nunits <= 256 * 4) hipLaunchKernelGGL((quantize_rows_kernel<DT, true, 256, 4, true>), g1, b, 0, s, a);
+  else if (nunits <= 256 * 6) hipLaunchKernelGGL((quantize_rows_kernel<DT, true, 256, 6, true>), g1, b, 0, s, a);
+  else if (nunits <= 256 * 8) hipLaunchKernelGGL((quantize_rows_kernel<DT, true, 256, 8, true>), g1, b, 0, s, a);
+  else return FP4_ERR_SHAPE;
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
+
+// Rows whose entries sit at row * stride (cnt[row] of them each) -> compact CSR arrays.  One wave per row.
+__global__ __launch_bounds__(256) void compact_rows_kernel(const int32_t* tmp_col, const float* tmp_val, const int32_t* cnt,
+                                                           int64_t stride, const int64_t* row_ptr, int64_t rows,
+                                                           int64_t capacity, int32_t* col_idx, float* val) {
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const int64_t dst = row_ptr[row];
+  const int n = cnt[row];
+  if (dst + n > capacity) return;
+  for (int i = lane; i < n; i += 64) {
+    col_idx[dst + i] = tmp_col[row * stride + i];
+    val[dst + i] = tmp_val[row * stride + i];
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -705,6 +901,30 @@ int fp4_launch_occ_rows(const void* x, int bf16, int64_t rows, int64_t cols, int
   a.rows = rows; a.cols = cols; a.ld = ld; a.capacity = capacity;
   const int rc = bf16 ? launch_rows<BF16, true>(a, s) : launch_rows<F32, true>(a, s);
   return rc ? rc : (ordered ? 0 : 1);
+}
+
+// Per-token variant of the fused pass: thresholds found per row (thr_out [rows][2]), entries to
+// (tmp_col, tmp_val) at row * 2 tail_k, counts to row_cnt.  Rows up to 16384 elements.
+int fp4_launch_occ_rows_token(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, int64_t tail_k,
+                              float* thr_out, uint8_t* codes, float* gamma, void* x_clamped, int32_t* tmp_col,
+                              float* tmp_val, int32_t* row_cnt, hipStream_t s) {
+  if (rows == 0 || cols == 0) return FP4_OK;
+  RowArgs a = {};
+  a.x = x; a.codes = codes; a.gamma = gamma; a.x_clamped = x_clamped;
+  a.tmp_col = tmp_col; a.tmp_val = tmp_val;
+  a.rows = rows; a.cols = cols; a.ld = ld; a.capacity = INT64_MAX;
+  a.thr_out = thr_out; a.row_cnt = row_cnt; a.tail_k = tail_k; a.stride_e = 2 * tail_k;
+  return bf16 ? launch_rows_token<BF16>(a, s) : launch_rows_token<F32>(a, s);
+}
+
+int fp4_launch_compact_rows(const int32_t* tmp_col, const float* tmp_val, const int32_t* row_cnt, int64_t stride,
+                            const int64_t* row_ptr, int64_t rows, int64_t capacity, int32_t* col_idx, float* val,
+                            hipStream_t s) {
+  if (rows == 0) return FP4_OK;
+  hipLaunchKernelGGL(compact_rows_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, tmp_col, tmp_val, row_cnt,
+                     stride, row_ptr, rows, capacity, col_idx, val);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
 }
 
 int fp4_launch_quantize_cols(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,

@@ -19,6 +19,7 @@
 #include "fp4_common.h"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace {
 
@@ -567,65 +568,120 @@ __global__ __launch_bounds__(256) void csr_transpose_fill_kernel(const int64_t* 
   }
 }
 
-// ---- transpose without global atomics (column range fits the LDS table) ---------------------
-// The rows are cut into at most TB_MAX blocks.  Pass 1: every block's column counts, cb[block][col].
-// Pass 2: per column, exclusive scan of the counts over the blocks (in place) and the column
-// total.  Pass 3 (after the scan of the totals into t_ptr): a block places its entries at
-// t_ptr[col] + cb[block][col] + rank inside the block (LDS atomics).
-constexpr int TB_MAX = 256;
-__global__ __launch_bounds__(256) void csr_block_count_kernel(const int64_t* row_ptr, const int32_t* col_idx,
-                                                              int64_t rows, int64_t rows_per_block, int64_t Q,
-                                                              int64_t capacity, int32_t* cb) {
-  __shared__ int32_t h[CNT_LDS];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
-  const int64_t r1 = min(r0 + rows_per_block, rows);
-  for (int i = threadIdx.x; i < Q; i += 256) h[i] = 0;
-  __syncthreads();
-  for (int64_t row = r0 + wave; row < r1; row += 4) {
-    const int64_t b = row_ptr[row], e = min(row_ptr[row + 1], capacity);
-    for (int64_t i = b + lane; i < e; i += 64) atomicAdd(&h[col_idx[i]], 1);
+// ---- transpose as a stable counting sort on the column (column range fits the LDS masks) ---------
+// The rows are cut into blocks of 64.  Inside a block, column c's entries are described by a 64-bit
+// mask of the rows that hold one (built with LDS atomic ORs: the result does not depend on their
+// order).  Pass 1 writes the population count of every mask, cnt8[block][c].  Pass 2 scans those
+// counts over the blocks of each column (exclusive, ex[block][c]) and leaves the column totals.
+// After the scan of the totals into t_ptr, pass 3 rebuilds the masks and places entry (r, c) at
+//   t_ptr[c] + ex[block][c] + popcount(mask[c] below bit r - r0),
+// i.e. behind every entry of the column from an earlier row: the transposed matrix comes out with
+// ascending indices inside every segment, without global atomics and without an ordering pass.
+constexpr int MB_ROWS = 64;          // rows per block = bits per mask
+constexpr int MB_MAXQ = 16384;       // columns whose masks (8 bytes each) fit 128 KiB of LDS
+
+// first (entry offset, row) bookkeeping shared by pass 1 and pass 3: s_rp[0..64] = clipped row starts
+FP4_D void mb_load_rows(const int64_t* row_ptr, int64_t rows, int64_t capacity, int64_t r0, long long* s_rp) {
+  if (threadIdx.x <= MB_ROWS) {
+    const int64_t r = min(r0 + (int64_t)threadIdx.x, rows);
+    s_rp[threadIdx.x] = min(row_ptr[r], capacity);
   }
-  __syncthreads();
-  int32_t* out = cb + (int64_t)blockIdx.x * Q;
-  for (int i = threadIdx.x; i < Q; i += 256) out[i] = h[i];
+}
+// row (0..63) of entry e of the block: the last i with s_rp[i] <= e
+FP4_D int mb_row_of(const long long* s_rp, long long e) {
+  int lo = 0, hi = MB_ROWS;   // invariant: s_rp[lo] <= e < s_rp[hi]
+#pragma unroll
+  for (int it = 0; it < 6; ++it) {
+    const int mid = (lo + hi) >> 1;
+    if (s_rp[mid] <= e) lo = mid; else hi = mid;
+  }
+  return lo;
 }
 
-__global__ __launch_bounds__(64) void csr_block_scan_kernel(int32_t* cb, int nblocks, int64_t Q, int32_t* cnt) {
-  const int64_t c = (int64_t)blockIdx.x * 64 + threadIdx.x;
-  if (c >= Q) return;
-  int32_t run = 0;
-  for (int b0 = 0; b0 < nblocks; b0 += 16) {   // 16 independent loads at a time
-    int32_t v[16];
+template <int QMAX>   // columns the LDS masks are laid out for (the launcher picks the smallest that fits)
+__global__ __launch_bounds__(256) void csr_mask_count_kernel(const int64_t* row_ptr, const int32_t* col_idx,
+                                                             int64_t rows, int64_t Q, int64_t capacity,
+                                                             uint8_t* cnt8) {
+  __shared__ uint32_t mb_mask[2 * QMAX];   // rows 0..31 of the block in word 2c, rows 32..63 in word 2c + 1
+  __shared__ long long s_rp[MB_ROWS + 1];
+  const int64_t r0 = (int64_t)blockIdx.x * MB_ROWS;
+  for (int i = threadIdx.x; i < 2 * Q; i += 256) mb_mask[i] = 0;
+  mb_load_rows(row_ptr, rows, capacity, r0, s_rp);
+  __syncthreads();
+  const long long b = s_rp[0], e = s_rp[MB_ROWS];
+  for (long long i = b + threadIdx.x; i < e; i += 256) {
+    const int r = mb_row_of(s_rp, i);
+    atomicOr(&mb_mask[2 * col_idx[i] + (r >> 5)], 1u << (r & 31));
+  }
+  __syncthreads();
+  uint8_t* out = cnt8 + (int64_t)blockIdx.x * Q;
+  for (int c = threadIdx.x; c < Q; c += 256) out[c] = (uint8_t)(__popc(mb_mask[2 * c]) + __popc(mb_mask[2 * c + 1]));
+}
+
+// 64 columns per workgroup; the four waves split the blocks into quarters: sum, exchange, rescan.
+__global__ __launch_bounds__(256) void csr_mask_scan_kernel(const uint8_t* cnt8, int nblocks, int64_t Q,
+                                                            uint32_t* ex, int32_t* cnt) {
+  __shared__ uint32_t s_q[4][64];
+  const int lane = threadIdx.x & 63, quarter = threadIdx.x >> 6;
+  const int64_t c = (int64_t)blockIdx.x * 64 + lane;
+  const int per = (nblocks + 3) / 4;
+  const int b0 = quarter * per, b1 = min(nblocks, b0 + per);
+  uint32_t sum = 0;
+  if (c < Q) {
+    int bi = b0;
+    for (; bi + 15 < b1; bi += 16) {   // sixteen independent loads at a time
+      uint32_t v[16];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) v[j] = b0 + j < nblocks ? cb[(int64_t)(b0 + j) * Q + c] : 0;
+      for (int j = 0; j < 16; ++j) v[j] = cnt8[(int64_t)(bi + j) * Q + c];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      if (b0 + j < nblocks) cb[(int64_t)(b0 + j) * Q + c] = run;
-      run += v[j];
+      for (int j = 0; j < 16; ++j) sum += v[j];
     }
+    for (; bi < b1; ++bi) sum += cnt8[(int64_t)bi * Q + c];
   }
-  cnt[c] = run;
+  s_q[quarter][lane] = sum;
+  __syncthreads();
+  if (c >= Q) return;
+  uint32_t run = 0;
+  for (int q = 0; q < quarter; ++q) run += s_q[q][lane];
+  if (quarter == 3) cnt[c] = (int32_t)(run + sum);
+  int bi = b0;
+  for (; bi + 15 < b1; bi += 16) {
+    uint32_t v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v[j] = cnt8[(int64_t)(bi + j) * Q + c];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) { ex[(int64_t)(bi + j) * Q + c] = run; run += v[j]; }
+  }
+  for (; bi < b1; ++bi) { ex[(int64_t)bi * Q + c] = run; run += cnt8[(int64_t)bi * Q + c]; }
 }
 
-__global__ __launch_bounds__(256) void csr_block_fill_kernel(const int64_t* row_ptr, const int32_t* col_idx,
-                                                             const float* val, int64_t rows, int64_t rows_per_block,
-                                                             int64_t Q, int64_t capacity, const int64_t* t_ptr,
-                                                             const int32_t* cb, int32_t* u_idx, float* u_val) {
-  __shared__ int32_t h[CNT_LDS];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t r0 = (int64_t)blockIdx.x * rows_per_block;
-  const int64_t r1 = min(r0 + rows_per_block, rows);
-  const int32_t* base = cb + (int64_t)blockIdx.x * Q;
-  for (int i = threadIdx.x; i < Q; i += 256) h[i] = base[i];
+template <int QMAX>
+__global__ __launch_bounds__(256) void csr_mask_fill_kernel(const int64_t* row_ptr, const int32_t* col_idx,
+                                                            const float* val, int64_t rows, int64_t Q,
+                                                            int64_t capacity, const int64_t* t_ptr,
+                                                            const uint32_t* ex, int32_t* t_idx, float* t_val) {
+  __shared__ uint32_t mb_mask[2 * QMAX];
+  __shared__ long long s_rp[MB_ROWS + 1];
+  const int64_t r0 = (int64_t)blockIdx.x * MB_ROWS;
+  for (int i = threadIdx.x; i < 2 * Q; i += 256) mb_mask[i] = 0;
+  mb_load_rows(row_ptr, rows, capacity, r0, s_rp);
   __syncthreads();
-  for (int64_t row = r0 + wave; row < r1; row += 4) {
-    const int64_t b = row_ptr[row], e = min(row_ptr[row + 1], capacity);
-    for (int64_t i = b + lane; i < e; i += 64) {
-      const int32_t c = col_idx[i];
-      const int64_t pos = t_ptr[c] + atomicAdd(&h[c], 1);
-      u_idx[pos] = (int32_t)row;
-      u_val[pos] = val[i];
+  const long long b = s_rp[0], e = s_rp[MB_ROWS];
+  for (long long i = b + threadIdx.x; i < e; i += 256) {
+    const int r = mb_row_of(s_rp, i);
+    atomicOr(&mb_mask[2 * col_idx[i] + (r >> 5)], 1u << (r & 31));
+  }
+  __syncthreads();
+  const uint32_t* exb = ex + (int64_t)blockIdx.x * Q;
+  for (long long i = b + threadIdx.x; i < e; i += 256) {
+    const int r = mb_row_of(s_rp, i);
+    const int32_t c = col_idx[i];
+    const uint32_t lo = mb_mask[2 * c], hi = mb_mask[2 * c + 1];
+    const uint32_t below = r < 32 ? __popc(lo & ((1u << r) - 1u)) : __popc(lo) + __popc(hi & ((1u << (r - 32)) - 1u));
+    const int64_t pos = t_ptr[c] + exb[c] + below;
+    if (pos < capacity) {
+      t_idx[pos] = (int32_t)(r0 + r);
+      t_val[pos] = val[i];
     }
   }
 }
@@ -756,34 +812,53 @@ int fp4_launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float*
   return FP4_OK;
 }
 
-// int32 words of scratch the transpose needs: cnt[Q], cursor[Q], block counts [TB_MAX][Q]
-// (the last only while the column range fits the LDS table).
-int64_t fp4_csr_transpose_scratch_words(int64_t Q) { return 2 * Q + (Q <= CNT_LDS ? (int64_t)TB_MAX * Q : 0); }
+int fp4_launch_scan_rows(const int32_t* row_cnt, int64_t rows, int64_t* row_ptr, int64_t* nnz, hipStream_t s);
 
-// u_idx/u_val: unordered staging, capacity entries each
+// int32 words of scratch the transpose of a P x Q matrix needs.  Mask path (Q <= MB_MAXQ):
+// cnt[Q], ex[blocks][Q] (uint32), cnt8[blocks][Q] (bytes).  Otherwise: cnt[Q], cursor[Q].
+int64_t fp4_csr_transpose_scratch_words(int64_t P, int64_t Q) {
+  if (Q > MB_MAXQ) return 2 * Q;
+  const int64_t blocks = (P + MB_ROWS - 1) / MB_ROWS;
+  return Q + 64 + blocks * Q + (blocks * Q + 3) / 4 + 64;
+}
+
+// u_idx/u_val: unordered staging, capacity entries each (only the path for very wide matrices uses it)
 int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, const float* val,
                              const int64_t* nnz, int64_t P, int64_t Q, int64_t capacity, int64_t* t_ptr,
                              int32_t* t_idx, float* t_val, int32_t* u_idx, float* u_val, int32_t* scratch,
                              hipStream_t s) {
   int32_t* cnt = scratch;
-  int32_t* cursor = scratch + Q;
-  if (Q <= CNT_LDS) {
-    int32_t* cb = scratch + 2 * Q;
-    const int64_t rpb = std::max<int64_t>(64, (P + TB_MAX - 1) / TB_MAX);
-    const int nblocks = (int)std::max<int64_t>(1, (P + rpb - 1) / rpb);
-    hipLaunchKernelGGL(csr_block_count_kernel, dim3(nblocks), dim3(256), 0, s, row_ptr, col_idx, P, rpb, Q, capacity, cb);
-    hipLaunchKernelGGL(csr_block_scan_kernel, dim3((unsigned)((Q + 63) / 64)), dim3(64), 0, s, cb, nblocks, Q, cnt);
-    hipLaunchKernelGGL(scan_counts32_kernel, dim3(1), dim3(1024), 0, s, cnt, Q, t_ptr);
-    hipLaunchKernelGGL(csr_block_fill_kernel, dim3(nblocks), dim3(256), 0, s, row_ptr, col_idx, val, P, rpb, Q, capacity,
-                       t_ptr, cb, u_idx, u_val);
-  } else {
-    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((2 * Q + 255) / 256)), dim3(256), 0, s, scratch, 2 * Q, 0);
-    const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((capacity + 4095) / 4096, 2048));
-    hipLaunchKernelGGL(csr_count_cols_kernel, dim3(grid), dim3(256), 0, s, col_idx, nnz, capacity, Q, cnt);
-    hipLaunchKernelGGL(scan_counts32_kernel, dim3(1), dim3(1024), 0, s, cnt, Q, t_ptr);
-    hipLaunchKernelGGL(csr_transpose_fill_kernel, dim3((unsigned)((P + 3) / 4)), dim3(256), 0, s, row_ptr, col_idx, val,
-                       P, capacity, t_ptr, cursor, u_idx, u_val);
+  if (Q <= MB_MAXQ) {
+    const int nblocks = (int)std::max<int64_t>(1, (P + MB_ROWS - 1) / MB_ROWS);
+    uint32_t* ex = reinterpret_cast<uint32_t*>(scratch + Q + 64);
+    uint8_t* cnt8 = reinterpret_cast<uint8_t*>(ex + (int64_t)nblocks * Q);
+    auto count = [&](auto qmax) {
+      hipLaunchKernelGGL((csr_mask_count_kernel<decltype(qmax)::value>), dim3(nblocks), dim3(256), 0, s, row_ptr, col_idx,
+                         P, Q, capacity, cnt8);
+    };
+    auto fill = [&](auto qmax) {
+      hipLaunchKernelGGL((csr_mask_fill_kernel<decltype(qmax)::value>), dim3(nblocks), dim3(256), 0, s, row_ptr, col_idx,
+                         val, P, Q, capacity, t_ptr, ex, t_idx, t_val);
+    };
+    using Q4 = std::integral_constant<int, 4096>;
+    using Q8 = std::integral_constant<int, 8192>;
+    using Q16 = std::integral_constant<int, MB_MAXQ>;
+    if (Q <= 4096) count(Q4{}); else if (Q <= 8192) count(Q8{}); else count(Q16{});
+    hipLaunchKernelGGL(csr_mask_scan_kernel, dim3((unsigned)((Q + 63) / 64)), dim3(256), 0, s, cnt8, nblocks, Q, ex, cnt);
+    FP4_CHECK_LAUNCH();
+    const int rc = fp4_launch_scan_rows(cnt, Q, t_ptr, nullptr, s);
+    if (rc) return rc;
+    if (Q <= 4096) fill(Q4{}); else if (Q <= 8192) fill(Q8{}); else fill(Q16{});
+    FP4_CHECK_LAUNCH();
+    return FP4_OK;
   }
+  int32_t* cursor = scratch + Q;
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((2 * Q + 255) / 256)), dim3(256), 0, s, scratch, 2 * Q, 0);
+  const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((capacity + 4095) / 4096, 2048));
+  hipLaunchKernelGGL(csr_count_cols_kernel, dim3(grid), dim3(256), 0, s, col_idx, nnz, capacity, Q, cnt);
+  hipLaunchKernelGGL(scan_counts32_kernel, dim3(1), dim3(1024), 0, s, cnt, Q, t_ptr);
+  hipLaunchKernelGGL(csr_transpose_fill_kernel, dim3((unsigned)((P + 3) / 4)), dim3(256), 0, s, row_ptr, col_idx, val,
+                     P, capacity, t_ptr, cursor, u_idx, u_val);
   if (capacity > 0 && P <= (int64_t)BM_WORDS * 32)
     hipLaunchKernelGGL(csr_bitmap_sort_kernel, dim3((unsigned)Q), dim3(256), (size_t)((P + 31) / 32) * 8, s, t_ptr, P,
                        capacity, u_idx, u_val, t_idx, t_val);

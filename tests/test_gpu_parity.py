@@ -387,9 +387,10 @@ def test_residual_spmm_random_shapes():
 def test_dge_apply(dtype):
     g = torch.Generator().manual_seed(13)
     K, N = 200, 264
-    W = synth._finish(torch.randn(K, N, generator=g) * 0.02, dtype)
+    W = torch.randn(K, N, generator=g) * 0.02
     # plant scaled weights on grid points, midpoints and the cap boundary (gamma = 1 column)
     W[:16, 0] = torch.tensor([6, .25, .5, .75, 1, 1.25, 2.5, 3, 3.5, 5, 0, 2.516, 2.484, -5, -0.25, 4.99])
+    W = synth._finish(W, dtype)     # after planting: host and device must hold the same master values
     G = torch.randn(K, N, generator=g)
     _, gw = o.quantize_cols(W.numpy())
     ref = G.numpy().astype(np.float64) * o.dge_fprime(o.scaled_weights(W.numpy(), gw), 5.0, 3.0)
@@ -408,8 +409,9 @@ def test_dge_apply_other_k_and_cap(k, cap, dtype):
     at exact midpoints."""
     g = torch.Generator().manual_seed(int(10 * k) + 3)
     K, N = 136, 72
-    W = synth._finish(torch.randn(K, N, generator=g) * 0.02, dtype)
+    W = torch.randn(K, N, generator=g) * 0.02
     W[:18, 0] = torch.tensor([6, .25, .5, .75, 1, 1.25, 2.5, 3, 3.5, 5, 0, 2.516, 2.484, -5, -0.25, 4.99, 1.75, -1.25])
+    W = synth._finish(W, dtype)     # after planting: host and device must hold the same master values
     G = torch.randn(K, N, generator=g)
     _, gw = o.quantize_cols(W.numpy())
     fp = o.dge_fprime(o.scaled_weights(W.numpy(), gw), k, cap)
@@ -446,9 +448,9 @@ LAYER_CASES = [
     # several 1024-row blocks and several LDS slabs in both residual products, all of them ragged
     ("blocks", 1120, 1056, 160, "bf16", 0.98),
     ("blocks", 1056, 608, 96, "f32", 0.95),
-    ("sparse", 512, 1024, 264, "bf16", 0.999),   # the sparsest operating point of Sec. 4.3 (0.2 % residual)
-    ("sparse", 96, 2048, 72, "f32", 0.999),
-    ("dense", 256, 256, 136, "bf16", 0.9),       # the densest residual the workspaces provide for
+    ("sparse", 512, 1024, 288, "bf16", 0.999),   # the sparsest operating point of Sec. 4.3 (0.2 % residual)
+    ("sparse", 96, 2048, 96, "f32", 0.999),
+    ("dense", 256, 256, 160, "bf16", 0.9),       # the densest residual the workspaces provide for
 ]
 
 
@@ -489,6 +491,31 @@ def test_layer_forward_backward(name, M, K, N, dtype, alpha):
         assert_close(dW, o.fp4_linear_bwd_wgrad(A.numpy(), dY.numpy(), W.numpy(), alpha, 5.0, 3.0), "f32", "dW")
         G = b.fp4_linear_bwd_wgrad(Ad, dYd, Wd, ctx, 0.0, 3.0)
         assert_close(G, o.fp4_linear_bwd_wgrad(A.numpy(), dY.numpy(), W.numpy(), alpha, 0.0, 3.0), "f32", "G (STE)")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_cached_weight_quantizations_equal_the_plain_entry_points(dtype):
+    """W's two quantizations prepared once: codes and scales bit-exact against the oracle, and forward /
+    activation gradient through the cache bit-identical to the entry points that quantize W themselves."""
+    A, W, dY = synth.small_case(288, 544, 1056, dtype, seed=12)
+    Ad, Wd, dYd = dev(A, dtype), dev(W, dtype), dev(dY, dtype)
+    wq = b.fp4_prepare_weights(Wd)
+    torch.cuda.synchronize()
+    ct, gw = o.quantize_cols(W.numpy())
+    ck, gk = o.quantize_rows(W.numpy())
+    assert np.array_equal(wq.gamma_W.cpu().numpy().view(np.uint32), gw.view(np.uint32))
+    assert np.array_equal(wq.gamma_Wk.cpu().numpy().view(np.uint32), gk.view(np.uint32))
+    assert np.array_equal(host_codes(wq.qWt), ct)
+    assert np.array_equal(host_codes(wq.qWk), ck)
+    Y0, ctx0 = b.fp4_linear_fwd(Ad, Wd, 0.98)
+    Y1, ctx1 = b.fp4_linear_fwd_cached(Ad, Wd, wq, 0.98)
+    n = int(ctx0.nnz.item())
+    assert n == int(ctx1.nnz.item()) > 0
+    assert torch.equal(Y0, Y1) and torch.equal(ctx0.gamma_W, ctx1.gamma_W) and torch.equal(ctx0.val[:n], ctx1.val[:n])
+    assert torch.equal(b.fp4_linear_bwd_dgrad(dYd, Wd), b.fp4_linear_bwd_dgrad_cached(dYd, wq))
+    dW0 = b.fp4_linear_bwd_wgrad(Ad, dYd, Wd, ctx0)
+    dW1 = b.fp4_linear_bwd_wgrad(Ad, dYd, Wd, ctx1)
+    assert torch.equal(dW0, dW1)
 
 
 def test_forward_is_deterministic_and_keeps_guard_bands():
