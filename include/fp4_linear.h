@@ -63,7 +63,9 @@ typedef enum {
                              pointer                                                      */
   FP4_ERR_WORKSPACE = -5, /* workspace NULL or smaller than fp4_workspace_bytes()         */
   FP4_ERR_CAPACITY = -6,  /* residual buffers smaller than 2*floor((1-alpha)*rows*cols)   */
-  FP4_ERR_HIP = -7        /* a kernel launch failed (hipGetLastError)                     */
+  FP4_ERR_HIP = -7,       /* a kernel launch failed (hipGetLastError)                     */
+  FP4_ERR_LIMIT = -8      /* problem larger than the built-in scratch of an entry point
+                             that allocates nothing                                       */
 } fp4_status;
 
 typedef enum { FP4_F32 = 0, FP4_BF16 = 1 } fp4_dtype;
@@ -114,6 +116,20 @@ int64_t fp4_occ_capacity(int64_t rows, int64_t cols, double alpha);
 int fp4_quantize(const void* x, fp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
                  fp4_axis axis, uint8_t* codes, float* gamma,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* fp4_quantize for callers that cannot allocate or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results
+ * bit for bit, no workspace: the column-wise path keeps its partial column maxima in a
+ * file-scope device array of FP4_NOALLOC_SCRATCH_BYTES (one copy per GPU the library runs on,
+ * held until the process ends), which bounds the problem: ceil(rows/128) * cols * 4 bytes must
+ * fit, else FP4_ERR_LIMIT and nothing is enqueued (16384 x 12288 needs 6 MiB).  The row-wise
+ * path needs no scratch and has no limit.  The call allocates nothing and frees nothing; its
+ * first call on a device looks up the array's address (not a stream operation: make that call
+ * outside a capture).  All calls on one GPU share the array: calls that may overlap there --
+ * different streams without an ordering between them -- race; stream order is enough. */
+#define FP4_NOALLOC_SCRATCH_BYTES (8u << 20)
+int fp4_quantize_noalloc(const void* x, fp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                         fp4_axis axis, uint8_t* codes, float* gamma, void* stream);
 
 /* Outlier clamping and compensation on one tensor (Sec. 3.2).
  *   thresholds (out, [2]): lo = v[k], hi = v[n-1-k] of the ascending-sorted values,

@@ -55,6 +55,8 @@ def lib() -> C.CDLL:
         L.fp4_occ_capacity.restype = i64
         L.fp4_occ_capacity.argtypes = [i64, i64, f64]
         L.fp4_quantize.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, vp, sz, vp]
+        L.fp4_quantize_noalloc.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, vp]
+        L.fp4_quantize_noalloc.restype = i32
         L.occ_clamp_residual.argtypes = [vp, i32, i64, i64, i64, f64, vp, vp, vp, vp, vp, vp, vp, i64, vp,
                                          vp, sz, vp]
         L.fp4_linear_fwd.argtypes = [vp, vp, i32, i64, i64, i64, f64, vp, C.POINTER(fp4_fwd_ctx), vp, sz, vp]
@@ -200,6 +202,14 @@ def fp4_quantize(x: torch.Tensor, axis: int, ws: Optional[Workspace] = None) -> 
     _check(lib().fp4_quantize(_ptr(x), _dt(x), rows, cols, cols, axis, _ptr(codes), _ptr(gamma), _ptr(w),
                               w.numel(), _stream()), "fp4_quantize")
     return codes, gamma
+
+
+def fp4_quantize_noalloc(x: torch.Tensor, axis: int, codes: torch.Tensor, gamma: torch.Tensor) -> None:
+    """fp4_quantize without a workspace, into outputs the caller brings (nothing is allocated)."""
+    _dev_check(x, codes, gamma)
+    rows, cols = x.shape
+    _check(lib().fp4_quantize_noalloc(_ptr(x), _dt(x), rows, cols, cols, axis, _ptr(codes), _ptr(gamma),
+                                      _stream()), "fp4_quantize_noalloc")
 
 
 def occ_clamp_residual(x: torch.Tensor, alpha: float, want_codes: bool = True, want_clamped: bool = False,

@@ -156,6 +156,7 @@ extern "C" const char* fp4_status_string(int status) {
     case FP4_ERR_WORKSPACE: return "workspace too small";
     case FP4_ERR_CAPACITY: return "residual capacity too small";
     case FP4_ERR_HIP: return "kernel launch failed";
+    case FP4_ERR_LIMIT: return "problem exceeds the built-in scratch of the no-allocation entry point";
     default: return "unknown status";
   }
 }

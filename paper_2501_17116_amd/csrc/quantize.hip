@@ -7,6 +7,7 @@
 #include "fp4_common.h"
 #include "fp4_measure.h"
 
+#include <mutex>
 #include <type_traits>
 
 namespace {
@@ -954,6 +955,51 @@ extern "C" int fp4_quantize(const void* x, fp4_dtype dt, int64_t rows, int64_t c
   if (!workspace || workspace_bytes < need) return FP4_ERR_WORKSPACE;
   return fp4_launch_quantize_cols(x, dt == FP4_BF16, rows, cols, ld, nullptr, codes, gamma,
                                   reinterpret_cast<uint32_t*>(workspace), (hipStream_t)stream);
+}
+
+// ---- the entry point that allocates nothing -----------------------------------------------------
+namespace {
+// Partial column maxima of the column-wise path live here instead of in a caller workspace.  One
+// copy per GPU the library runs on, held until the process ends.
+constexpr size_t NOALLOC_WORDS = FP4_NOALLOC_SCRATCH_BYTES / sizeof(uint32_t);
+static __device__ __align__(256) uint32_t scratch[NOALLOC_WORDS];
+
+// Device address of `scratch` on the current device.  In host code the array's name is only a
+// handle: the address comes from the runtime, once per device (every GPU has its own copy).
+int noalloc_scratch(uint32_t** out) {
+  static std::mutex mu;
+  static uint32_t* ptr[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return FP4_ERR_HIP;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return FP4_ERR_HIP;
+    ptr[dev] = reinterpret_cast<uint32_t*>(p);
+  }
+  *out = ptr[dev];
+  return FP4_OK;
+}
+}  // namespace
+
+extern "C" int fp4_quantize_noalloc(const void* x, fp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                                    fp4_axis axis, uint8_t* codes, float* gamma, void* stream) {
+  if (dt != FP4_F32 && dt != FP4_BF16) return FP4_ERR_DTYPE;
+  if (axis != FP4_AXIS_ROW && axis != FP4_AXIS_COL) return FP4_ERR_DTYPE;
+  if (rows < 0 || cols < 0 || ld < cols) return FP4_ERR_SHAPE;
+  if (axis == FP4_AXIS_ROW ? (cols & 1) : (rows & 1)) return FP4_ERR_SHAPE;
+  if (rows == 0 || cols == 0) return FP4_OK;
+  if (!x || !codes || !gamma) return FP4_ERR_NULL;
+  if (!aligned16(x) || !aligned16(codes) || (ld % 8) != 0) return FP4_ERR_ARG;
+  if (axis == FP4_AXIS_ROW)   // the row-wise path has no scratch at all
+    return fp4_launch_quantize_rows(x, dt == FP4_BF16, rows, cols, ld, codes, gamma, (hipStream_t)stream);
+  if ((size_t)fp4_quantize_cols_scratch_words(rows, cols) > NOALLOC_WORDS) return FP4_ERR_LIMIT;
+  uint32_t* sp = nullptr;
+  const int rc = noalloc_scratch(&sp);
+  if (rc) return rc;
+  // every word the scale kernel reads is written by the maxima kernel of the same call first, so
+  // what an earlier call left behind is never seen and nothing has to be cleared
+  return fp4_launch_quantize_cols(x, dt == FP4_BF16, rows, cols, ld, nullptr, codes, gamma, sp, (hipStream_t)stream);
 }
 
 extern "C" int fp4_dge_apply(const float* G, const void* W, fp4_dtype dt, const float* gamma_W,
