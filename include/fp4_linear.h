@@ -75,6 +75,12 @@ typedef enum {
   FP4_AXIS_COL = 1  /* one scale per column; codes TRANSPOSED [cols x rows/2]             */
 } fp4_axis;
 
+/* Scope of the clamp thresholds of Sec. 3.2 (the paper does not name the axis of the quantile):
+ * TENSOR: one {lo, hi} pair for the whole activation operand (the default reading);
+ * TOKEN:  one pair per token (row), each the order statistics of that row alone with
+ *         k = floor((1-alpha)*cols) elements allowed per tail; rows of at most 16384 elements. */
+typedef enum { FP4_OCC_TENSOR = 0, FP4_OCC_TOKEN = 1 } fp4_occ_scope;
+
 typedef enum {
   FP4_OP_QUANTIZE = 0, /* (M=rows, K=cols, N ignored)                                     */
   FP4_OP_OCC = 1,      /* (M=rows, K=cols, N ignored)                                     */
@@ -90,12 +96,15 @@ typedef enum {
  * and the residual).  All members are caller-allocated device buffers. */
 typedef struct {
   float*   gamma_W;    /* [N]   forward scales of W, one per output channel               */
-  float*   thresholds; /* [2]   {lo, hi}; {-inf, +inf} when alpha == 1                    */
+  float*   thresholds; /* [2]   {lo, hi}; {-inf, +inf} when alpha == 1.  scope TOKEN:
+                          [2 M] {lo_i, hi_i} of every token                               */
   int64_t* row_ptr;    /* [M+1] CSR of Delta_A = A - clamp(A): row starts                 */
   int32_t* col_idx;    /* [capacity] column of each entry, ascending inside a row         */
   float*   val;        /* [capacity] fl32(A[i,c] - threshold)                             */
   int64_t  capacity;   /* entries available; >= 2*floor((1-alpha)*M*K)                    */
   int64_t* nnz;        /* [1]   number of entries                                         */
+  int32_t  scope;      /* fp4_occ_scope, set by the caller before the forward pass; with
+                          TOKEN capacity >= fp4_occ_capacity_token(M, K, alpha) suffices   */
 } fp4_fwd_ctx;
 
 const char* fp4_status_string(int status);
@@ -145,12 +154,25 @@ int occ_clamp_residual(const void* x, fp4_dtype dt, int64_t rows, int64_t cols, 
                        int64_t capacity, int64_t* nnz,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same with per-token thresholds (FP4_OCC_TOKEN): thresholds (out, [2 rows]) = {lo_i, hi_i},
+ * the (k+1)-th smallest and (k+1)-th largest element of row i, k = floor((1-alpha)*cols); every
+ * row holds at most 2k entries, exactly 2k when no element ties with a threshold.  The tensor is
+ * read once.  cols <= 16384.  capacity >= fp4_occ_capacity_token(rows, cols, alpha) = rows * 2k.
+ * Workspace as occ_clamp_residual. */
+int64_t fp4_occ_capacity_token(int64_t rows, int64_t cols, double alpha);
+int occ_clamp_residual_token(const void* x, fp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                             double alpha, float* thresholds, uint8_t* codes, float* gamma,
+                             void* x_clamped, int64_t* row_ptr, int32_t* col_idx, float* val,
+                             int64_t capacity, int64_t* nnz,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
 /* Forward: Y = dequant(Q(A_c) Q(W)) + Delta_A W   (Fig. 2; Sec. 3.2; App. C.2).
  *   A [M x K], W [K x N], Y [M x N], all dtype dt, dense (ld = row length).
  *   A_c = A clamped at the alpha / 1-alpha order statistics of the whole tensor and
  *   quantized per token; W quantized per output channel; the residual product uses the
  *   unquantized W with fp32 accumulation and is added before the single rounding of Y.
- *   alpha == 1 switches OCC off.  `saved` is filled for fp4_linear_bwd_wgrad. */
+ *   alpha == 1 switches OCC off.  `saved` is filled for fp4_linear_bwd_wgrad; saved->scope
+ *   selects per-tensor (default) or per-token thresholds. */
 int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
                    double alpha, void* Y, const fp4_fwd_ctx* saved,
                    void* workspace, size_t workspace_bytes, void* stream);

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libfp4mi.so")
 
 FP4_F32, FP4_BF16 = 0, 1
 FP4_AXIS_ROW, FP4_AXIS_COL = 0, 1
+FP4_OCC_TENSOR, FP4_OCC_TOKEN = 0, 1
 FP4_OP_QUANTIZE, FP4_OP_OCC, FP4_OP_FWD, FP4_OP_DGRAD, FP4_OP_WGRAD, FP4_OP_SPMM, FP4_OP_PREPARE = range(7)
 
 _lib = None
@@ -32,7 +33,7 @@ class Fp4Error(RuntimeError):
 class fp4_fwd_ctx(C.Structure):
     _fields_ = [("gamma_W", C.c_void_p), ("thresholds", C.c_void_p), ("row_ptr", C.c_void_p),
                 ("col_idx", C.c_void_p), ("val", C.c_void_p), ("capacity", C.c_int64),
-                ("nnz", C.c_void_p)]
+                ("nnz", C.c_void_p), ("scope", C.c_int32)]
 
 
 class fp4_weight_cache(C.Structure):
@@ -59,6 +60,10 @@ def lib() -> C.CDLL:
         L.fp4_quantize_noalloc.restype = i32
         L.occ_clamp_residual.argtypes = [vp, i32, i64, i64, i64, f64, vp, vp, vp, vp, vp, vp, vp, i64, vp,
                                          vp, sz, vp]
+        L.occ_clamp_residual_token.argtypes = L.occ_clamp_residual.argtypes
+        L.occ_clamp_residual_token.restype = i32
+        L.fp4_occ_capacity_token.restype = i64
+        L.fp4_occ_capacity_token.argtypes = [i64, i64, f64]
         L.fp4_linear_fwd.argtypes = [vp, vp, i32, i64, i64, i64, f64, vp, C.POINTER(fp4_fwd_ctx), vp, sz, vp]
         L.fp4_linear_bwd_dgrad.argtypes = [vp, vp, i32, i64, i64, i64, vp, vp, sz, vp]
         L.fp4_linear_bwd_wgrad.argtypes = [vp, vp, vp, i32, i64, i64, i64, C.POINTER(fp4_fwd_ctx), f32, f32,
@@ -174,18 +179,19 @@ def _ws(nbytes: int, ws: Optional[Workspace]) -> torch.Tensor:
 class FwdCtx:
     """Device buffers the forward pass fills for the weight-gradient pass."""
 
-    def __init__(self, M: int, K: int, N: int, alpha: float, device="cuda"):
+    def __init__(self, M: int, K: int, N: int, alpha: float, device="cuda", scope: int = FP4_OCC_TENSOR):
         cap = occ_capacity(M, K, alpha) if alpha < 1.0 else 0
         self.alpha = float(alpha)
+        self.scope = scope
         self.gamma_W = torch.empty(N, dtype=torch.float32, device=device)
-        self.thresholds = torch.empty(2, dtype=torch.float32, device=device)
+        self.thresholds = torch.empty(2 * M if scope == FP4_OCC_TOKEN else 2, dtype=torch.float32, device=device)
         self.row_ptr = torch.empty(M + 1, dtype=torch.int64, device=device)
         self.col_idx = torch.empty(max(cap, 1), dtype=torch.int32, device=device)
         self.val = torch.empty(max(cap, 1), dtype=torch.float32, device=device)
         self.nnz = torch.zeros(1, dtype=torch.int64, device=device)
         self.capacity = cap
         self.c = fp4_fwd_ctx(self.gamma_W.data_ptr(), self.thresholds.data_ptr(), self.row_ptr.data_ptr(),
-                             self.col_idx.data_ptr(), self.val.data_ptr(), cap, self.nnz.data_ptr())
+                             self.col_idx.data_ptr(), self.val.data_ptr(), cap, self.nnz.data_ptr(), scope)
 
 
 def fp4_quantize(x: torch.Tensor, axis: int, ws: Optional[Workspace] = None) -> Tuple[torch.Tensor, torch.Tensor]:
@@ -213,13 +219,20 @@ def fp4_quantize_noalloc(x: torch.Tensor, axis: int, codes: torch.Tensor, gamma:
 
 
 def occ_clamp_residual(x: torch.Tensor, alpha: float, want_codes: bool = True, want_clamped: bool = False,
-                       capacity: Optional[int] = None, ws: Optional[Workspace] = None) -> dict:
+                       capacity: Optional[int] = None, ws: Optional[Workspace] = None,
+                       scope: int = FP4_OCC_TENSOR) -> dict:
     _dev_check(x)
     rows, cols = x.shape
-    cap = occ_capacity(rows, cols, alpha) if capacity is None else capacity
+    token = scope == FP4_OCC_TOKEN
+    if capacity is not None:
+        cap = capacity
+    elif token:
+        cap = int(lib().fp4_occ_capacity_token(rows, cols, float(alpha)))
+    else:
+        cap = occ_capacity(rows, cols, alpha)
     dev = x.device
     out = {
-        "thresholds": torch.empty(2, dtype=torch.float32, device=dev),
+        "thresholds": torch.empty(2 * rows if token else 2, dtype=torch.float32, device=dev),
         "codes": torch.empty((rows, cols // 2), dtype=torch.uint8, device=dev) if want_codes else None,
         "gamma": torch.empty(rows, dtype=torch.float32, device=dev) if want_codes else None,
         "x_clamped": torch.empty_like(x) if want_clamped else None,
@@ -230,7 +243,8 @@ def occ_clamp_residual(x: torch.Tensor, alpha: float, want_codes: bool = True, w
     }
     nb = workspace_bytes(FP4_OP_OCC, rows, cols, 0, _dt(x))
     w = _ws(nb, ws)
-    _check(lib().occ_clamp_residual(_ptr(x), _dt(x), rows, cols, cols, float(alpha), _ptr(out["thresholds"]),
+    fn = lib().occ_clamp_residual_token if token else lib().occ_clamp_residual
+    _check(fn(_ptr(x), _dt(x), rows, cols, cols, float(alpha), _ptr(out["thresholds"]),
                                     _ptr(out["codes"]), _ptr(out["gamma"]), _ptr(out["x_clamped"]),
                                     _ptr(out["row_ptr"]), _ptr(out["col_idx"]), _ptr(out["val"]), cap,
                                     _ptr(out["nnz"]), _ptr(w), w.numel(), _stream()), "occ_clamp_residual")
@@ -238,14 +252,15 @@ def occ_clamp_residual(x: torch.Tensor, alpha: float, want_codes: bool = True, w
 
 
 def fp4_linear_fwd(A: torch.Tensor, W: torch.Tensor, alpha: float, ctx: Optional[FwdCtx] = None,
-                   Y: Optional[torch.Tensor] = None, ws: Optional[Workspace] = None):
+                   Y: Optional[torch.Tensor] = None, ws: Optional[Workspace] = None, scope: int = FP4_OCC_TENSOR):
+    """scope only matters when no ctx is passed (a ctx carries its own)."""
     _dev_check(A, W, Y)
     M, K = A.shape
     K2, N = W.shape
     if K2 != K or A.dtype != W.dtype:
         raise ValueError("A [M,K] and W [K,N] must agree in K and dtype")
     if ctx is None:
-        ctx = FwdCtx(M, K, N, alpha, A.device)
+        ctx = FwdCtx(M, K, N, alpha, A.device, scope)
     if Y is None:
         Y = torch.empty((M, N), dtype=A.dtype, device=A.device)
     nb = workspace_bytes(FP4_OP_FWD, M, K, N, _dt(A))

@@ -21,8 +21,14 @@ int fp4_launch_occ_rows(const void* x, int bf16, int64_t rows, int64_t cols, int
                         uint8_t* codes, float* gamma, void* x_clamped, int32_t* col_idx, float* val,
                         int32_t* tmp_col, float* tmp_val, const int64_t* row_ptr, int64_t capacity, hipStream_t s);
 int fp4_launch_quantize_cols(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
-                             const float* clamp_thr, uint8_t* codes_t, float* gamma, uint32_t* amax_scratch,
-                             hipStream_t s);
+                             const float* clamp_thr, int per_row_thr, uint8_t* codes_t, float* gamma,
+                             uint32_t* amax_scratch, hipStream_t s);
+int fp4_launch_occ_rows_token(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, int64_t tail_k,
+                              float* thr_out, uint8_t* codes, float* gamma, void* x_clamped, int32_t* tmp_col,
+                              float* tmp_val, int32_t* row_cnt, hipStream_t s);
+int fp4_launch_compact_rows(const int32_t* tmp_col, const float* tmp_val, const int32_t* row_cnt, int64_t stride,
+                            const int64_t* row_ptr, int64_t rows, int64_t capacity, int32_t* col_idx, float* val,
+                            hipStream_t s);
 int64_t fp4_quantize_cols_scratch_words(int64_t rows, int64_t cols);
 size_t fp4_select_scratch_bytes();
 int fp4_launch_thresholds(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, int64_t k,
@@ -182,6 +188,52 @@ extern "C" size_t fp4_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, f
   return c.off + 256;
 }
 
+namespace {
+constexpr int64_t TOKEN_MAX_COLS = 16384;   // a row must fit the registers of one workgroup
+
+// The per-token chain: one fused pass (thresholds, clamp, codes, entries at a fixed stride per row),
+// the scan of the rows' entry counts, and the compaction into CSR.
+int occ_token_chain(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, int64_t k_row, float* thresholds,
+                    uint8_t* codes, float* gamma, void* x_clamped, int64_t* row_ptr, int32_t* col_idx, float* val,
+                    int64_t capacity, int64_t* nnz, const OccTemps& t, hipStream_t s) {
+  int rc = fp4_launch_occ_rows_token(x, bf16, rows, cols, ld, k_row, thresholds, codes, gamma, x_clamped, t.tmp_col,
+                                     t.tmp_val, t.row_cnt, s);
+  if (rc) return rc;
+  rc = fp4_launch_scan_rows(t.row_cnt, rows, row_ptr, nnz, s);
+  if (rc) return rc;
+  return fp4_launch_compact_rows(t.tmp_col, t.tmp_val, t.row_cnt, 2 * k_row, row_ptr, rows, capacity, col_idx, val, s);
+}
+}  // namespace
+
+extern "C" int64_t fp4_occ_capacity_token(int64_t rows, int64_t cols, double alpha) {
+  if (rows < 0 || cols < 0 || !(alpha > 0.5) || !(alpha <= 1.0)) return -1;
+  return rows * 2 * tail_count(cols, alpha);
+}
+
+extern "C" int occ_clamp_residual_token(const void* x, fp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
+                                        double alpha, float* thresholds, uint8_t* codes, float* gamma,
+                                        void* x_clamped, int64_t* row_ptr, int32_t* col_idx, float* val,
+                                        int64_t capacity, int64_t* nnz, void* workspace, size_t workspace_bytes,
+                                        void* stream) {
+  if (!dtype_ok(dt)) return FP4_ERR_DTYPE;
+  if (rows <= 0 || cols <= 0 || ld < cols || (cols & 1) || cols > TOKEN_MAX_COLS) return FP4_ERR_SHAPE;
+  if (!(alpha > 0.5) || !(alpha <= 1.0)) return FP4_ERR_ARG;
+  if (!x || !thresholds || !row_ptr || !nnz) return FP4_ERR_NULL;
+  if ((codes == nullptr) != (gamma == nullptr)) return FP4_ERR_NULL;
+  const int64_t k_row = tail_count(cols, alpha);
+  if (2 * k_row >= cols) return FP4_ERR_ARG;
+  if (capacity < rows * 2 * k_row) return FP4_ERR_CAPACITY;
+  if (capacity > 0 && (!col_idx || !val)) return FP4_ERR_NULL;
+  if (!aligned16(x) || (ld % 8) != 0 || (codes && !aligned16(codes)) || (x_clamped && !aligned16(x_clamped)))
+    return FP4_ERR_ARG;
+  if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_OCC, rows, cols, 0, dt)) return FP4_ERR_WORKSPACE;
+  if (rows * 2 * k_row > provisioned_entries(rows, cols)) return FP4_ERR_ARG;  // alpha below 0.9 is not provisioned
+  Carver c(reinterpret_cast<void*>(align_up((size_t)(uintptr_t)workspace, 256)));
+  OccTemps t = carve_occ(c, rows, provisioned_entries(rows, cols));
+  return occ_token_chain(x, dt == FP4_BF16, rows, cols, ld, k_row, thresholds, codes, gamma, x_clamped, row_ptr, col_idx,
+                         val, capacity, nnz, t, (hipStream_t)stream);
+}
+
 extern "C" int occ_clamp_residual(const void* x, fp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,
                                   double alpha, float* thresholds, uint8_t* codes, float* gamma,
                                   void* x_clamped, int64_t* row_ptr, int32_t* col_idx, float* val,
@@ -237,12 +289,17 @@ int fwd_impl(const void* A, const void* W, const fp4_weight_cache* wq, fp4_dtype
   if (!A || !W || !Y || !saved || !saved->gamma_W) return FP4_ERR_NULL;
   if (!aligned16(A) || !aligned16(W) || !aligned16(Y)) return FP4_ERR_ARG;
   const bool occ = alpha < 1.0;
-  const int64_t k = tail_count(M * K, alpha);
+  if (saved->scope != FP4_OCC_TENSOR && saved->scope != FP4_OCC_TOKEN) return FP4_ERR_DTYPE;
+  const bool token = occ && saved->scope == FP4_OCC_TOKEN;
+  const int64_t k = tail_count(M * K, alpha);       // per tail of the tensor
+  const int64_t k_row = tail_count(K, alpha);       // per tail of a token
+  const int64_t need = token ? M * 2 * k_row : 2 * k;
   if (occ) {
     if (!saved->thresholds || !saved->row_ptr || !saved->nnz) return FP4_ERR_NULL;
-    if (saved->capacity < 2 * k) return FP4_ERR_CAPACITY;
+    if (token && (K > TOKEN_MAX_COLS || 2 * k_row >= K)) return FP4_ERR_SHAPE;
+    if (saved->capacity < need) return FP4_ERR_CAPACITY;
     if (saved->capacity > 0 && (!saved->col_idx || !saved->val)) return FP4_ERR_NULL;
-    if (2 * k > provisioned_entries(M, K)) return FP4_ERR_ARG;   // alpha below 0.9 is not provisioned
+    if (need > provisioned_entries(M, K)) return FP4_ERR_ARG;   // alpha below 0.9 is not provisioned
   }
   if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_FWD, M, K, N, dt)) return FP4_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
@@ -261,24 +318,29 @@ int fwd_impl(const void* A, const void* W, const fp4_weight_cache* wq, fp4_dtype
       if (hipGetLastError() != hipSuccess) return FP4_ERR_HIP;
     }
   } else {
-    rc = fp4_launch_quantize_cols(W, bf16, K, N, N, nullptr, w.qWt, saved->gamma_W, w.amax, s);
+    rc = fp4_launch_quantize_cols(W, bf16, K, N, N, nullptr, 0, w.qWt, saved->gamma_W, w.amax, s);
     if (rc) return rc;
   }
   const float* addend = nullptr;
   if (occ) {
     const int64_t cap = std::min(saved->capacity, provisioned_entries(M, K));  // never beyond the temporaries
-    rc = fp4_launch_thresholds(A, bf16, M, K, K, k, saved->thresholds, w.occ.select, w.occ.total, s);
-    if (rc) return rc;
-    rc = fp4_launch_occ_count(A, bf16, M, K, K, saved->thresholds, w.occ.row_cnt, s);
-    if (rc) return rc;
-    rc = fp4_launch_scan_rows(w.occ.row_cnt, M, saved->row_ptr, saved->nnz, s);
-    if (rc) return rc;
-    rc = fp4_launch_occ_rows(A, bf16, M, K, K, saved->thresholds, w.qA, w.gA, nullptr, saved->col_idx, saved->val,
-                             w.occ.tmp_col, w.occ.tmp_val, saved->row_ptr, cap, s);
-    if (rc == 1) {   // streamed rows: entries unordered in the temporaries
-      rc = fp4_launch_order_rows(saved->row_ptr, M, K, cap, w.occ.tmp_col, w.occ.tmp_val, saved->col_idx, saved->val, s);
-      if (rc == 1)
-        rc = fp4_launch_csr_gather(w.occ.tmp_col, w.occ.tmp_val, M, cap, saved->row_ptr, saved->col_idx, saved->val, s);
+    if (token) {
+      rc = occ_token_chain(A, bf16, M, K, K, k_row, saved->thresholds, w.qA, w.gA, nullptr, saved->row_ptr,
+                           saved->col_idx, saved->val, cap, saved->nnz, w.occ, s);
+    } else {
+      rc = fp4_launch_thresholds(A, bf16, M, K, K, k, saved->thresholds, w.occ.select, w.occ.total, s);
+      if (rc) return rc;
+      rc = fp4_launch_occ_count(A, bf16, M, K, K, saved->thresholds, w.occ.row_cnt, s);
+      if (rc) return rc;
+      rc = fp4_launch_scan_rows(w.occ.row_cnt, M, saved->row_ptr, saved->nnz, s);
+      if (rc) return rc;
+      rc = fp4_launch_occ_rows(A, bf16, M, K, K, saved->thresholds, w.qA, w.gA, nullptr, saved->col_idx, saved->val,
+                               w.occ.tmp_col, w.occ.tmp_val, saved->row_ptr, cap, s);
+      if (rc == 1) {   // streamed rows: entries unordered in the temporaries
+        rc = fp4_launch_order_rows(saved->row_ptr, M, K, cap, w.occ.tmp_col, w.occ.tmp_val, saved->col_idx, saved->val, s);
+        if (rc == 1)
+          rc = fp4_launch_csr_gather(w.occ.tmp_col, w.occ.tmp_val, M, cap, saved->row_ptr, saved->col_idx, saved->val, s);
+      }
     }
     if (rc) return rc;
     // Delta_A W with the unquantized W, fp32; lands where the GEMM epilogue picks it up
@@ -353,7 +415,7 @@ extern "C" int fp4_prepare_weights(const void* W, fp4_dtype dt, int64_t K, int64
   hipStream_t s = (hipStream_t)stream;
   const int bf16 = dt == FP4_BF16;
   uint32_t* amax = reinterpret_cast<uint32_t*>(align_up((size_t)(uintptr_t)workspace, 256));
-  int rc = fp4_launch_quantize_cols(W, bf16, K, N, N, nullptr, wq->qWt, wq->gamma_W, amax, s);   // forward's operand
+  int rc = fp4_launch_quantize_cols(W, bf16, K, N, N, nullptr, 0, wq->qWt, wq->gamma_W, amax, s);   // forward's operand
   if (rc) return rc;
   return fp4_launch_quantize_rows(W, bf16, K, N, N, wq->qWk, wq->gamma_Wk, s);                   // dgrad's operand
 }
@@ -390,6 +452,8 @@ extern "C" int fp4_linear_bwd_wgrad(const void* A, const void* dY, const void* W
   const int bf16 = dt == FP4_BF16;
   Carver c(reinterpret_cast<void*>(align_up((size_t)(uintptr_t)workspace, 256)));
   WgradWs w = carve_wgrad(c, M, K, N);
+  if (saved->scope != FP4_OCC_TENSOR && saved->scope != FP4_OCC_TOKEN) return FP4_ERR_DTYPE;
+  const int token = occ && saved->scope == FP4_OCC_TOKEN;   // thresholds: one pair per token
   // as the forward pass: entries beyond what the workspaces provide for cannot exist
   const int64_t cap = occ ? std::min(saved->capacity, provisioned_entries(M, K)) : 0;
   int rc = FP4_OK;
@@ -397,8 +461,8 @@ extern "C" int fp4_linear_bwd_wgrad(const void* A, const void* dY, const void* W
     rc = fp4_launch_csr_transpose(saved->row_ptr, saved->col_idx, saved->val, saved->nnz, M, K, cap,
                                   w.t_ptr, w.t_idx, w.t_val, w.u_idx, w.u_val, w.t_scratch, s);
   // A_c per input channel (codes [K x M/2]); dY per output channel (codes [N x M/2])
-  if (!rc) rc = fp4_launch_quantize_cols(A, bf16, M, K, K, occ ? saved->thresholds : nullptr, w.qAt, w.gAk, w.amax, s);
-  if (!rc) rc = fp4_launch_quantize_cols(dY, bf16, M, N, N, nullptr, w.qdYt, w.gdYn, w.amax, s);
+  if (!rc) rc = fp4_launch_quantize_cols(A, bf16, M, K, K, occ ? saved->thresholds : nullptr, token, w.qAt, w.gAk, w.amax, s);
+  if (!rc) rc = fp4_launch_quantize_cols(dY, bf16, M, N, N, nullptr, 0, w.qdYt, w.gdYn, w.amax, s);
   if (rc) return rc;
   const float* addend = nullptr;
   if (occ) {

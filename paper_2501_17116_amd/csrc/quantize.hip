@@ -665,6 +665,7 @@ struct ColArgs {
   float* gamma;          // out [cols]
   uint32_t* amax_bits;   // scratch [ceil(rows / CA_ROWS)][cols]: partial column maxima per row block
   const float* thr;      // clamp thresholds or null
+  int64_t thr_stride;    // 0: one {lo, hi} pair for the tensor; 2: one pair per row, thr[2 r], thr[2 r + 1]
   int64_t rows, cols, ld;
 };
 
@@ -688,6 +689,7 @@ __global__ __launch_bounds__(256) void col_absmax_kernel(ColArgs a) {
     for (int64_t r = r0 + wave; r < r1; r += 4) {
       float v[8];
       load8<DT>(a.x, r * a.ld + unit * 8, valid, v);
+      if (CLAMP && a.thr_stride) { lo = a.thr[r * a.thr_stride]; hi = a.thr[r * a.thr_stride + 1]; }
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         float x = v[e];
@@ -763,12 +765,18 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColArgs a) {
       if (r < a.rows) load8<DT>(a.x, r * a.ld + col, valid, v0);
       if (r + 1 < a.rows) load8<DT>(a.x, (r + 1) * a.ld + col, valid, v1);
     }
+    float lo1 = lo, hi1 = hi;
+    if (CLAMP && a.thr_stride) {   // per-row thresholds
+      const int64_t ra = min(r, a.rows - 1), rb = min(r + 1, a.rows - 1);
+      lo = a.thr[ra * a.thr_stride]; hi = a.thr[ra * a.thr_stride + 1];
+      lo1 = a.thr[rb * a.thr_stride]; hi1 = a.thr[rb * a.thr_stride + 1];
+    }
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       float x0 = v0[e], x1 = v1[e];
       if (CLAMP) {
         x0 = x0 < lo ? lo : (x0 > hi ? hi : x0);
-        x1 = x1 < lo ? lo : (x1 > hi ? hi : x1);
+        x1 = x1 < lo1 ? lo1 : (x1 > hi1 ? hi1 : x1);
         if (r >= a.rows || e >= valid) x0 = 0.0f;       // nothing there: code 0, whatever the thresholds
         if (r + 1 >= a.rows || e >= valid) x1 = 0.0f;
       }
@@ -929,11 +937,12 @@ int fp4_launch_compact_rows(const int32_t* tmp_col, const float* tmp_val, const 
 }
 
 int fp4_launch_quantize_cols(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
-                             const float* clamp_thr, uint8_t* codes_t, float* gamma,
+                             const float* clamp_thr, int per_row_thr, uint8_t* codes_t, float* gamma,
                              uint32_t* amax_scratch, hipStream_t s) {
   if (rows == 0 || cols == 0) return FP4_OK;
   ColArgs a = {};
   a.x = x; a.codes_t = codes_t; a.gamma = gamma; a.amax_bits = amax_scratch; a.thr = clamp_thr;
+  a.thr_stride = per_row_thr ? 2 : 0;
   a.rows = rows; a.cols = cols; a.ld = ld;
   if (clamp_thr) return bf16 ? launch_cols<BF16, true>(a, s) : launch_cols<F32, true>(a, s);
   return bf16 ? launch_cols<BF16, false>(a, s) : launch_cols<F32, false>(a, s);
@@ -953,7 +962,7 @@ extern "C" int fp4_quantize(const void* x, fp4_dtype dt, int64_t rows, int64_t c
     return fp4_launch_quantize_rows(x, dt == FP4_BF16, rows, cols, ld, codes, gamma, (hipStream_t)stream);
   const size_t need = fp4_workspace_bytes(FP4_OP_QUANTIZE, rows, cols, 0, dt);
   if (!workspace || workspace_bytes < need) return FP4_ERR_WORKSPACE;
-  return fp4_launch_quantize_cols(x, dt == FP4_BF16, rows, cols, ld, nullptr, codes, gamma,
+  return fp4_launch_quantize_cols(x, dt == FP4_BF16, rows, cols, ld, nullptr, 0, codes, gamma,
                                   reinterpret_cast<uint32_t*>(workspace), (hipStream_t)stream);
 }
 
@@ -999,7 +1008,7 @@ extern "C" int fp4_quantize_noalloc(const void* x, fp4_dtype dt, int64_t rows, i
   if (rc) return rc;
   // every word the scale kernel reads is written by the maxima kernel of the same call first, so
   // what an earlier call left behind is never seen and nothing has to be cleared
-  return fp4_launch_quantize_cols(x, dt == FP4_BF16, rows, cols, ld, nullptr, codes, gamma, sp, (hipStream_t)stream);
+  return fp4_launch_quantize_cols(x, dt == FP4_BF16, rows, cols, ld, nullptr, 0, codes, gamma, sp, (hipStream_t)stream);
 }
 
 extern "C" int fp4_dge_apply(const float* G, const void* W, fp4_dtype dt, const float* gamma_W,

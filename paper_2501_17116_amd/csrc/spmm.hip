@@ -344,7 +344,7 @@ FP4_D void long_dense_body(float* V, const void* D, int64_t m0, int rows_here, i
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[l][e] = 0.0f;
   if (valid > 0) {
-    constexpr int UN = NL <= 8 ? 4 : 2;   // rows in flight per wave
+    constexpr int UN = NL <= 4 ? 8 : (NL <= 8 ? 4 : 2);   // rows in flight per wave
     int r = wave;
     for (; r + LD_WAVES * (UN - 1) < rows_here; r += LD_WAVES * UN) {
       float d[UN][8];
@@ -578,6 +578,7 @@ __global__ __launch_bounds__(256) void csr_transpose_fill_kernel(const int64_t* 
 // i.e. behind every entry of the column from an earlier row: the transposed matrix comes out with
 // ascending indices inside every segment, without global atomics and without an ordering pass.
 constexpr int MB_ROWS = 64;          // rows per block = bits per mask
+constexpr int MB_THREADS = 1024;   // per workgroup in the two passes that walk entries: they are latency-bound
 constexpr int MB_MAXQ = 16384;       // columns whose masks (8 bytes each) fit 128 KiB of LDS
 
 // first (entry offset, row) bookkeeping shared by pass 1 and pass 3: s_rp[0..64] = clipped row starts
@@ -599,23 +600,23 @@ FP4_D int mb_row_of(const long long* s_rp, long long e) {
 }
 
 template <int QMAX>   // columns the LDS masks are laid out for (the launcher picks the smallest that fits)
-__global__ __launch_bounds__(256) void csr_mask_count_kernel(const int64_t* row_ptr, const int32_t* col_idx,
+__global__ __launch_bounds__(MB_THREADS) void csr_mask_count_kernel(const int64_t* row_ptr, const int32_t* col_idx,
                                                              int64_t rows, int64_t Q, int64_t capacity,
                                                              uint8_t* cnt8) {
   __shared__ uint32_t mb_mask[2 * QMAX];   // rows 0..31 of the block in word 2c, rows 32..63 in word 2c + 1
   __shared__ long long s_rp[MB_ROWS + 1];
   const int64_t r0 = (int64_t)blockIdx.x * MB_ROWS;
-  for (int i = threadIdx.x; i < 2 * Q; i += 256) mb_mask[i] = 0;
+  for (int i = threadIdx.x; i < 2 * Q; i += MB_THREADS) mb_mask[i] = 0;
   mb_load_rows(row_ptr, rows, capacity, r0, s_rp);
   __syncthreads();
   const long long b = s_rp[0], e = s_rp[MB_ROWS];
-  for (long long i = b + threadIdx.x; i < e; i += 256) {
+  for (long long i = b + threadIdx.x; i < e; i += MB_THREADS) {
     const int r = mb_row_of(s_rp, i);
     atomicOr(&mb_mask[2 * col_idx[i] + (r >> 5)], 1u << (r & 31));
   }
   __syncthreads();
   uint8_t* out = cnt8 + (int64_t)blockIdx.x * Q;
-  for (int c = threadIdx.x; c < Q; c += 256) out[c] = (uint8_t)(__popc(mb_mask[2 * c]) + __popc(mb_mask[2 * c + 1]));
+  for (int c = threadIdx.x; c < Q; c += MB_THREADS) out[c] = (uint8_t)(__popc(mb_mask[2 * c]) + __popc(mb_mask[2 * c + 1]));
 }
 
 // 64 columns per workgroup; the four waves split the blocks into quarters: sum, exchange, rescan.
@@ -656,24 +657,24 @@ __global__ __launch_bounds__(256) void csr_mask_scan_kernel(const uint8_t* cnt8,
 }
 
 template <int QMAX>
-__global__ __launch_bounds__(256) void csr_mask_fill_kernel(const int64_t* row_ptr, const int32_t* col_idx,
+__global__ __launch_bounds__(MB_THREADS) void csr_mask_fill_kernel(const int64_t* row_ptr, const int32_t* col_idx,
                                                             const float* val, int64_t rows, int64_t Q,
                                                             int64_t capacity, const int64_t* t_ptr,
                                                             const uint32_t* ex, int32_t* t_idx, float* t_val) {
   __shared__ uint32_t mb_mask[2 * QMAX];
   __shared__ long long s_rp[MB_ROWS + 1];
   const int64_t r0 = (int64_t)blockIdx.x * MB_ROWS;
-  for (int i = threadIdx.x; i < 2 * Q; i += 256) mb_mask[i] = 0;
+  for (int i = threadIdx.x; i < 2 * Q; i += MB_THREADS) mb_mask[i] = 0;
   mb_load_rows(row_ptr, rows, capacity, r0, s_rp);
   __syncthreads();
   const long long b = s_rp[0], e = s_rp[MB_ROWS];
-  for (long long i = b + threadIdx.x; i < e; i += 256) {
+  for (long long i = b + threadIdx.x; i < e; i += MB_THREADS) {
     const int r = mb_row_of(s_rp, i);
     atomicOr(&mb_mask[2 * col_idx[i] + (r >> 5)], 1u << (r & 31));
   }
   __syncthreads();
   const uint32_t* exb = ex + (int64_t)blockIdx.x * Q;
-  for (long long i = b + threadIdx.x; i < e; i += 256) {
+  for (long long i = b + threadIdx.x; i < e; i += MB_THREADS) {
     const int r = mb_row_of(s_rp, i);
     const int32_t c = col_idx[i];
     const uint32_t lo = mb_mask[2 * c], hi = mb_mask[2 * c + 1];
@@ -833,11 +834,11 @@ int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, con
     uint32_t* ex = reinterpret_cast<uint32_t*>(scratch + Q + 64);
     uint8_t* cnt8 = reinterpret_cast<uint8_t*>(ex + (int64_t)nblocks * Q);
     auto count = [&](auto qmax) {
-      hipLaunchKernelGGL((csr_mask_count_kernel<decltype(qmax)::value>), dim3(nblocks), dim3(256), 0, s, row_ptr, col_idx,
+      hipLaunchKernelGGL((csr_mask_count_kernel<decltype(qmax)::value>), dim3(nblocks), dim3(MB_THREADS), 0, s, row_ptr, col_idx,
                          P, Q, capacity, cnt8);
     };
     auto fill = [&](auto qmax) {
-      hipLaunchKernelGGL((csr_mask_fill_kernel<decltype(qmax)::value>), dim3(nblocks), dim3(256), 0, s, row_ptr, col_idx,
+      hipLaunchKernelGGL((csr_mask_fill_kernel<decltype(qmax)::value>), dim3(nblocks), dim3(MB_THREADS), 0, s, row_ptr, col_idx,
                          val, P, Q, capacity, t_ptr, ex, t_idx, t_val);
     };
     using Q4 = std::integral_constant<int, 4096>;

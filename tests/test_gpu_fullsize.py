@@ -96,3 +96,34 @@ def test_full_size_layer_sampled(cfg_name, layer_name, tokens, alpha):
     un = b.fp4_unpack(codes)
     assert int((un == 8).sum().item()) == 0                         # -0 is never emitted
     assert bool(((un & 7) == 7).any(dim=1).all().item())            # every channel reaches magnitude 6
+
+
+def test_full_size_layer_per_token_thresholds():
+    """The 4096 -> 4096 layer of the 7B block at 16384 tokens under the per-token reading of the clamp."""
+    cfg = synth.CONFIGS["c3"]
+    shape = [l for l in cfg.layers if l.name == "o"][0]
+    A, W, dY = synth.make_layer(cfg, shape)
+    M, K, N = A.shape[0], shape.K, shape.N
+    Ad, Wd, dYd = (t.to(torch.bfloat16).cuda() for t in (A, W, dY))
+    An, Wn, dYn = A.numpy(), W.numpy(), dY.numpy()
+    rows = np.unique(np.array([0, 1, 255, 256, 4097, 8191, 12345, M - 1]) % M)
+    chans = np.array([0, 31, 1000, K - 1] + synth.outlier_channels(cfg.idx, K, cfg.outlier_frac).tolist()[:2])
+    Y, ctx = b.fp4_linear_fwd(Ad, Wd, cfg.alpha, scope=b.FP4_OCC_TOKEN)
+    lo, hi = o.occ_thresholds_per_token(An, cfg.alpha)
+    thr = ctx.thresholds.cpu().numpy().reshape(M, 2)
+    assert np.array_equal(thr[:, 0], lo) and np.array_equal(thr[:, 1], hi)
+    k = o.occ_tail_count(K, cfg.alpha)
+    rp = ctx.row_ptr.cpu().numpy()
+    below, above = An < lo[:, None], An > hi[:, None]
+    assert np.array_equal(np.diff(rp), (below | above).sum(axis=1)) and np.all(np.diff(rp) <= 2 * k)
+    Yref, st = o.fp4_linear_fwd(An, Wn, cfg.alpha, "f32", rows=rows, scope="token")
+    ci, cv = ctx.col_idx.cpu().numpy(), ctx.val.cpu().numpy()
+    for si, r in enumerate(rows):
+        a, e = rp[r], rp[r + 1]
+        sa, se = st.csr.row_ptr[si], st.csr.row_ptr[si + 1]
+        assert np.array_equal(ci[a:e], st.csr.col_idx[sa:se])
+        assert np.array_equal(cv[a:e].view(np.uint32), st.csr.val[sa:se].view(np.uint32))
+    _close(Y.float().cpu().numpy()[rows], Yref, True, float(np.abs(Yref).max()))
+    dW = b.fp4_linear_bwd_wgrad(Ad, dYd, Wd, ctx, cfg.dge_k, cfg.dge_cap)
+    dWref = o.fp4_linear_bwd_wgrad(An, dYn, Wn, cfg.alpha, cfg.dge_k, cfg.dge_cap, rows=chans, scope="token")
+    _close(dW.cpu().numpy()[chans], dWref, False, float(np.abs(dWref).max()))

@@ -277,6 +277,54 @@ def test_occ_raw_abi_ragged_cols_and_padded_rows(rows, cols, ld, alpha, dtype):
     assert np.array_equal(host_codes(codes), rc)
 
 
+def _check_occ_token(x: torch.Tensor, dtype: str, alpha: float):
+    out = b.occ_clamp_residual(dev(x, dtype), alpha, want_codes=True, want_clamped=True, scope=b.FP4_OCC_TOKEN)
+    torch.cuda.synchronize()
+    xn = x.numpy()
+    R, Ccols = xn.shape
+    lo, hi = o.occ_thresholds_per_token(xn, alpha)
+    thr = out["thresholds"].cpu().numpy().reshape(R, 2)
+    assert np.array_equal(thr[:, 0], lo) and np.array_equal(thr[:, 1], hi)
+    xc, csr = o.occ_clamp_residual(xn, lo, hi)
+    nnz = int(out["nnz"].item())
+    assert nnz == csr.val.size <= R * 2 * o.occ_tail_count(Ccols, alpha)
+    assert np.array_equal(out["row_ptr"].cpu().numpy(), csr.row_ptr)
+    assert np.array_equal(out["col_idx"].cpu().numpy()[:nnz], csr.col_idx)
+    assert np.array_equal(out["val"].cpu().numpy()[:nnz].view(np.uint32), csr.val.view(np.uint32))
+    assert np.array_equal(out["x_clamped"].float().cpu().numpy(), xc)
+    rc, rg = o.quantize_rows(xc)
+    assert np.array_equal(out["gamma"].cpu().numpy().view(np.uint32), rg.view(np.uint32))
+    assert np.array_equal(host_codes(out["codes"]), rc)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape,alpha", [((256, 512), 0.99), ((100, 72), 0.97), ((64, 4096), 0.999), ((9, 2056), 0.99),
+                                          ((300, 640), 1.0), ((5, 6000), 0.98), ((3, 12000), 0.99), ((130, 11008), 0.99),
+                                          ((37, 1544), 0.98), ((29, 2048), 0.9), ((4, 14000), 0.97), ((7, 16384), 0.99),
+                                          ((6, 16), 0.9), ((33, 4088), 0.99)])
+def test_occ_per_token_thresholds_bit_exact(shape, alpha, dtype):
+    """The per-token reading: every row's own order statistics (found in registers by radix selection),
+    clamp, residual and codes, one row-kernel variant per shape class, ragged row lengths included."""
+    cfg = synth.CONFIGS["c1"]
+    x = synth.make_activation(cfg, shape[0], shape[1], salt=shape[0] + 1)
+    _check_occ_token(synth._finish(x, dtype), dtype, alpha)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_occ_per_token_ties_constant_rows_and_signed_zeros(dtype):
+    g = torch.Generator().manual_seed(31)
+    x = torch.randint(-3, 4, (40, 256), generator=g).float()          # heavy ties around the thresholds
+    x[3] = 1.5                                                        # a constant row: nothing clamped
+    x[4] = 0.0
+    x[5, ::2] = -0.0
+    x[6] = torch.randn(256, generator=g).abs() + 1                    # one-sided rows
+    x[7] = -torch.randn(256, generator=g).abs()
+    _check_occ_token(synth._finish(x, dtype), dtype, 0.95)
+    x = torch.randn(16, 4096, generator=g) * torch.exp(4 * torch.randn(16, 1, generator=g))   # rows of very different scale
+    x[:, 7] *= 1e4
+    _check_occ_token(synth._finish(x, dtype), dtype, 0.99)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_occ_with_ties_one_sided_and_constant(dtype):
     g = torch.Generator().manual_seed(3)
@@ -516,6 +564,34 @@ def test_cached_weight_quantizations_equal_the_plain_entry_points(dtype):
     dW0 = b.fp4_linear_bwd_wgrad(Ad, dYd, Wd, ctx0)
     dW1 = b.fp4_linear_bwd_wgrad(Ad, dYd, Wd, ctx1)
     assert torch.equal(dW0, dW1)
+
+
+@pytest.mark.parametrize("name,M,K,N,dtype,alpha", [("c1", 256, 512, 512, "f32", 0.99),
+                                                     ("rag", 288, 544, 1056, "bf16", 0.99),
+                                                     ("long", 2304, 64, 96, "bf16", 0.9),
+                                                     ("blocks", 1120, 1056, 160, "bf16", 0.98),
+                                                     ("wide", 64, 11008, 32, "bf16", 0.99),
+                                                     ("off", 96, 128, 96, "f32", 1.0)])
+def test_layer_with_per_token_thresholds(name, M, K, N, dtype, alpha):
+    """Forward and weight gradient under the per-token reading of the clamp (the activation gradient does
+    not involve the clamp): saved state bit-exact, outputs within tolerance."""
+    A, W, dY = _layer_inputs(name, M, K, N, dtype)
+    Ad, Wd, dYd = dev(A, dtype), dev(W, dtype), dev(dY, dtype)
+    Y, ctx = b.fp4_linear_fwd(Ad, Wd, alpha, scope=b.FP4_OCC_TOKEN)
+    torch.cuda.synchronize()
+    Yref, st = o.fp4_linear_fwd(A.numpy(), W.numpy(), alpha, "f32", scope="token")
+    if alpha < 1.0:
+        thr = ctx.thresholds.cpu().numpy().reshape(M, 2)
+        assert np.array_equal(thr[:, 0], st.lo) and np.array_equal(thr[:, 1], st.hi)
+        nnz = int(ctx.nnz.item())
+        assert nnz == st.csr.val.size
+        assert np.array_equal(ctx.row_ptr.cpu().numpy(), st.csr.row_ptr)
+        assert np.array_equal(ctx.col_idx.cpu().numpy()[:nnz], st.csr.col_idx)
+        assert np.array_equal(ctx.val.cpu().numpy()[:nnz].view(np.uint32), st.csr.val.view(np.uint32))
+    assert_close(Y, Yref, dtype, "Y (per-token)")
+    dW = b.fp4_linear_bwd_wgrad(Ad, dYd, Wd, ctx, 5.0, 3.0)
+    assert_close(dW, o.fp4_linear_bwd_wgrad(A.numpy(), dY.numpy(), W.numpy(), alpha, 5.0, 3.0, scope="token"), "f32",
+                 "dW (per-token)")
 
 
 def test_forward_is_deterministic_and_keeps_guard_bands():
