@@ -18,6 +18,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 FP4_MFMA_PEAK_TFLOPS = 10100.0   # MI355X dense FP4 (published)
+FP32_VECTOR_PEAK_TFLOPS = 157.3  # MI355X fp32 vector (published; counts packed FMAs)
 
 
 def build_layers(cfg, torch, b):
@@ -49,11 +50,33 @@ def build_layers(cfg, torch, b):
     return layers
 
 
-def run_step(cfg, layers, b, ws):
+def run_step(cfg, layers, b, ws, ctx_key="ctx", alpha=None, cached=False):
+    """One pass of the whole path over every layer.  ctx_key picks the saved-state buffers (their
+    capacity and threshold scope go with an operating point); cached = W's quantizations come from
+    the per-layer weight cache (valid between optimizer steps) instead of being redone."""
+    alpha = cfg.alpha if alpha is None else alpha
     for L in layers:
-        b.fp4_linear_fwd(L["A"], L["W"], cfg.alpha, ctx=L["ctx"], Y=L["Y"], ws=ws)
-        b.fp4_linear_bwd_dgrad(L["dY"], L["W"], dA=L["dA"], ws=ws)
-        b.fp4_linear_bwd_wgrad(L["A"], L["dY"], L["W"], L["ctx"], cfg.dge_k, cfg.dge_cap, dW=L["dW"], ws=ws)
+        if cached:
+            b.fp4_linear_fwd_cached(L["A"], L["W"], L["wq"], alpha, ctx=L[ctx_key], Y=L["Y"], ws=ws)
+            b.fp4_linear_bwd_dgrad_cached(L["dY"], L["wq"], dA=L["dA"], ws=ws)
+        else:
+            b.fp4_linear_fwd(L["A"], L["W"], alpha, ctx=L[ctx_key], Y=L["Y"], ws=ws)
+            b.fp4_linear_bwd_dgrad(L["dY"], L["W"], dA=L["dA"], ws=ws)
+        b.fp4_linear_bwd_wgrad(L["A"], L["dY"], L["W"], L[ctx_key], cfg.dge_k, cfg.dge_cap, dW=L["dW"], ws=ws)
+
+
+def time_steps(fn, torch, steps, warmup=1):
+    for _ in range(warmup):
+        fn()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
 
 
 def cpu_baseline(cfg):
@@ -64,8 +87,8 @@ def cpu_baseline(cfg):
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        cores = 1
+    except Exception:   # the BLAS pool's size cannot be read: what the process may run on
+        cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
     l = min(cfg.layers, key=lambda s: s.K * s.N)
     Ms = min(l.M, 8192)   # 10-20 s of oracle work on the GPU machine's 16 host threads
     A, W, dY = synth.make_layer(cfg, l, M=Ms)
@@ -177,6 +200,62 @@ def kernel_report(cfg, layers, b, torch, ws):
     return rep
 
 
+def operating_points(cfg, layers, b, torch, ws, step_flops, steps=3):
+    """The same step at the other residual densities of Sec. 4.3 (alpha = 0.999 / 0.97: 0.2 % / 6 %), with the
+    compensation off, under the per-token reading of the clamp, and with W's quantizations cached across
+    micro-batches.  Whole-path ms per step and TFLOP/s on the dense GEMM FLOPs, like the headline."""
+    out = {}
+
+    def leg(name, **kw):
+        ms = time_steps(lambda: run_step(cfg, layers, b, ws, **kw), torch, steps)
+        out[name] = {"ms_per_step": ms, "TFLOP/s": step_flops / (ms * 1e-3) / 1e12}
+
+    for a in (0.999, 0.97, 1.0):
+        if a == cfg.alpha:
+            continue
+        key = "ctx_a%g" % a
+        for L in layers:
+            l = L["shape"]
+            L[key] = b.FwdCtx(l.M, l.K, l.N, a)
+        leg("alpha=%g" % a if a < 1.0 else "occ_off", ctx_key=key, alpha=a)
+        for L in layers:
+            del L[key]
+    if all(L["shape"].K <= 16384 for L in layers):
+        for L in layers:
+            l = L["shape"]
+            L["ctx_tok"] = b.FwdCtx(l.M, l.K, l.N, cfg.alpha, scope=b.FP4_OCC_TOKEN)
+        leg("per_token_thresholds(alpha=%g)" % cfg.alpha, ctx_key="ctx_tok")
+        L0 = layers[0]
+        l = L0["shape"]
+        eb = 2 if cfg.dtype == "bf16" else 4
+        As = _rotating(L0["A"], torch)
+        st = {"i": 0}
+
+        def occ_tok():
+            st["i"] += 1
+            b.occ_clamp_residual(As[st["i"] % len(As)], cfg.alpha, ws=ws, scope=b.FP4_OCC_TOKEN)
+        t = _time(occ_tok, torch)
+        nbytes = l.M * l.K * (eb + 0.5 + 8 * 2 * (1 - cfg.alpha)) + 20 * l.M   # one read: the row holds its own thresholds
+        out["occ_clamp_residual_token(A)"] = {"us": t * 1e6, "GB/s": nbytes / t / 1e9,
+                                              "frac_of_hbm_peak": nbytes / t / 1e9 / HBM_PEAK_GBS}
+        del As
+        c = L0["ctx_tok"]
+        R = torch.empty(l.M, l.N, device="cuda", dtype=torch.float32)
+        t = _time(lambda: b.fp4_residual_spmm(c.row_ptr, c.col_idx, c.val, l.K, L0["W"], R=R, ws=ws), torch)
+        nnz = int(c.nnz.item())
+        out["residual_spmm(fwd, per-token rows)"] = {"nnz": nnz, "us": t * 1e6, "GFLOP/s": 2.0 * nnz * l.N / t / 1e9}
+        del R
+        for L in layers:
+            del L["ctx_tok"]
+    for L in layers:
+        L["wq"] = b.fp4_prepare_weights(L["W"], ws=ws)
+    leg("cached_W_quantizations", cached=True)
+    for L in layers:
+        del L["wq"]
+    run_step(cfg, layers, b, ws)   # leave the default saved state behind
+    return out
+
+
 def ceilings(b, torch):
     """What this part sustains: FP4 MFMA issue loop (constant and random operand data) and a
     streaming copy.  Context for the roofline fractions, which stay quoted against the
@@ -237,7 +316,9 @@ def main():
         run_step(cfg, layers, b, ws)
     torch.cuda.synchronize()
 
-    b.fp4_trace_gemm_begin(n_gemm * args.steps)
+    n_spmm = 2 * len(layers) if cfg.alpha < 1.0 else 0
+    n_trace = (n_gemm + n_spmm) * args.steps
+    b.fp4_trace_begin(n_trace)
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -249,7 +330,9 @@ def main():
     torch.cuda.synchronize()
     t_wall = time.perf_counter() - t_wall0
     ms_total = e0.elapsed_time(e1)
-    gemm_ms = b.fp4_trace_gemm_end(n_gemm * args.steps)
+    trace = b.fp4_trace_end(n_trace)
+    gemm_ms = [ms for kind, ms in trace if kind == b.FP4_TRACE_GEMM]
+    spmm_ms = [ms for kind, ms in trace if kind == b.FP4_TRACE_SPMM]
     ms_per_step = ms_total / args.steps
     value = step_flops / (ms_per_step * 1e-3) / 1e12
 
@@ -267,18 +350,35 @@ def main():
                                 ", ".join("%s %dx%d" % (l.name, l.K, l.N) for l in cfg.layers),
                                 cfg.layers[0].M, cfg.dtype, cfg.alpha, cfg.dge_k),
                    "gemm_flop_per_step": step_flops, "wall_ms_per_step": t_wall / args.steps * 1e3},
+        # the contraction the metric names: the FP4 GEMM against the FP4 matrix-core peak
         "roofline": {"bound": "mfma", "kernel": "fp4_gemm_nt_kernel", "achieved": achieved,
                      "peak": FP4_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / FP4_MFMA_PEAK_TFLOPS,
                      "traffic": None, "avg_launch_ms": avg_gemm_ms, "launches": len(gemm_ms),
-                     "gemm_share_of_step": sum(gemm_ms) / ms_total if ms_total else None},
+                     "share_of_step": sum(gemm_ms) / ms_total if ms_total else None},
     }
+    if spmm_ms:
+        # the kernel the step spends most of its time in: the residual product, plain fp32 FMAs on the
+        # vector ALUs (2 nnz N FLOP per launch), against the published fp32 vector peak
+        nnz = [int(L["ctx"].nnz.item()) for L in layers]
+        spmm_flops = sum(2 * 2.0 * n * L["shape"].N for n, L in zip(nnz, layers))   # forward + weight gradient
+        avg_spmm_ms = sum(spmm_ms) / len(spmm_ms)
+        ach = spmm_flops / n_spmm / (avg_spmm_ms * 1e-3) / 1e12
+        out["roofline_residual"] = {"bound": "alu", "kernel": "spmm_tile_kernel", "achieved": ach,
+                                    "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                    "frac": ach / FP32_VECTOR_PEAK_TFLOPS, "traffic": None,
+                                    "avg_launch_ms": avg_spmm_ms, "launches": len(spmm_ms),
+                                    "share_of_step": sum(spmm_ms) / ms_total if ms_total else None,
+                                    "nnz_per_layer": nnz}
     tfile = os.path.join(ROOT, "profiles", "fp4_gemm_nt_kernel_%s_hbm_traffic.txt" % args.workload)
-    if os.path.exists(tfile):
+    if os.path.exists(tfile):   # hardware counters cannot be read from inside the run: the committed PMC summary
         for line in open(tfile):
             if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
                 out["roofline"]["traffic"] = float(line.split("=", 1)[1])
+                out["roofline"]["traffic_source"] = os.path.relpath(tfile, ROOT)
     if not args.no_kernel_report:
         out["kernels"] = kernel_report(cfg, layers, b, torch, ws)
+        if cfg.alpha < 1.0 and args.alpha is None:
+            out["operating_points"] = operating_points(cfg, layers, b, torch, ws, step_flops)
         out["ceilings"] = ceilings(b, torch)
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()

@@ -40,14 +40,15 @@ int fp4_probe_mfma(const void* operand_bytes, int64_t nbytes, int workgroups, in
 int fp4_probe_copy(const void* src, void* dst, int64_t nbytes, void* stream);
 
 /* ---- measurement helper (host-side state, off by default; not thread-safe) ----
- * Between fp4_trace_gemm_begin(n) and fp4_trace_gemm_end() every launch of the FP4 GEMM
- * kernel, from any entry point, is bracketed by a pair of HIP events recorded on the
- * launch's own stream (at most n launches; later ones are not recorded).
- * fp4_trace_gemm_end waits for the recorded launches, writes their durations in
- * milliseconds, in launch order, to ms_host[0..capacity) (HOST memory) and returns the
- * number of launches recorded (>= 0) or a negative fp4_status. */
-int fp4_trace_gemm_begin(int max_launches);
-int fp4_trace_gemm_end(float* ms_host, int capacity);
+ * Between fp4_trace_begin(n) and fp4_trace_end() every launch of the FP4 GEMM kernel and of the
+ * tiled sparse-product kernel, from any entry point, is bracketed by a pair of HIP events recorded
+ * on the launch's own stream (at most n launches; later ones are not recorded).
+ * fp4_trace_end waits for the recorded launches, writes their durations in milliseconds and their
+ * kinds, in launch order, to ms_host / kind_host [0..capacity) (HOST memory) and returns the number
+ * of launches recorded (>= 0) or a negative fp4_status. */
+enum { FP4_TRACE_GEMM = 0, FP4_TRACE_SPMM = 1 };
+int fp4_trace_begin(int max_launches);
+int fp4_trace_end(float* ms_host, int* kind_host, int capacity);
 
 #ifdef __cplusplus
 }

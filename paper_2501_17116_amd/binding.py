@@ -85,10 +85,10 @@ def lib() -> C.CDLL:
         L.fp4_probe_mfma.restype = i32
         L.fp4_probe_copy.argtypes = [vp, vp, i64, vp]
         L.fp4_probe_copy.restype = i32
-        L.fp4_trace_gemm_begin.argtypes = [i32]
-        L.fp4_trace_gemm_begin.restype = i32
-        L.fp4_trace_gemm_end.argtypes = [vp, i32]
-        L.fp4_trace_gemm_end.restype = i32
+        L.fp4_trace_begin.argtypes = [i32]
+        L.fp4_trace_begin.restype = i32
+        L.fp4_trace_end.argtypes = [vp, vp, i32]
+        L.fp4_trace_end.restype = i32
         for name in ("fp4_quantize", "occ_clamp_residual", "fp4_linear_fwd", "fp4_linear_bwd_dgrad",
                      "fp4_linear_bwd_wgrad", "fp4_gemm", "fp4_unpack", "fp4_dge_apply", "fp4_residual_spmm",
                      "fp4_host_round_codes", "fp4_device_round_codes", "fp4_device_round_sweep"):
@@ -443,17 +443,21 @@ def fp4_device_round_sweep(device="cuda:0") -> int:
     return int(cnt.item())
 
 
-def fp4_trace_gemm_begin(max_launches: int) -> None:
-    _check(lib().fp4_trace_gemm_begin(int(max_launches)), "fp4_trace_gemm_begin")
+FP4_TRACE_GEMM, FP4_TRACE_SPMM = 0, 1
 
 
-def fp4_trace_gemm_end(max_launches: int):
-    """Durations (ms) of the GEMM launches recorded since fp4_trace_gemm_begin, in order."""
+def fp4_trace_begin(max_launches: int) -> None:
+    _check(lib().fp4_trace_begin(int(max_launches)), "fp4_trace_begin")
+
+
+def fp4_trace_end(max_launches: int):
+    """[(kind, ms)] of the GEMM / tiled sparse-product launches recorded since fp4_trace_begin, in order."""
     buf = (C.c_float * max_launches)()
-    n = lib().fp4_trace_gemm_end(C.cast(buf, C.c_void_p), max_launches)
+    kinds = (C.c_int * max_launches)()
+    n = lib().fp4_trace_end(C.cast(buf, C.c_void_p), C.cast(kinds, C.c_void_p), max_launches)
     if n < 0:
-        raise Fp4Error(n, "fp4_trace_gemm_end")
-    return [float(buf[i]) for i in range(min(n, max_launches))]
+        raise Fp4Error(n, "fp4_trace_end")
+    return [(int(kinds[i]), float(buf[i])) for i in range(min(n, max_launches))]
 
 
 def fp4_probe_mfma(operand_bytes: torch.Tensor, workgroups: int, iters: int, sink: torch.Tensor) -> None:

@@ -17,7 +17,6 @@
 
 #include <algorithm>
 #include <utility>
-#include <vector>
 
 typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -430,17 +429,12 @@ int compute_units_of_current_device() {
   return n;
 }
 
-// Optional per-launch timing of the GEMM kernel (off unless fp4_trace_gemm_begin was called).
-struct GemmTrace {
-  std::vector<hipEvent_t> ev;  // start/stop pairs
-  int used = 0;
-  bool on = false;
-};
-GemmTrace g_trace;
-
 }  // namespace
 
 // Internal launcher shared by fp4_gemm and the layer entry points.
+int fp4_trace_open(int kind, hipStream_t stream);
+void fp4_trace_close(int slot, hipStream_t stream);
+
 int fp4_launch_gemm(const uint8_t* L, const float* gl, const uint8_t* Rt, const float* gr,
                     int64_t P, int64_t Q, int64_t Kc, const float* addend, void* out, int out_bf16,
                     int64_t ldo, const void* W, int w_bf16, int64_t ldw, const float* gamma_w,
@@ -455,8 +449,7 @@ int fp4_launch_gemm(const uint8_t* L, const float* gl, const uint8_t* Rt, const 
   const int total = g.tiles_p * g.tiles_q;
   const int n_cu = compute_units_of_current_device();
   const dim3 grid(std::min(((total + 7) / 8) * 8, (n_cu / 8) * 8)), block(NTHREADS);
-  const bool traced = g_trace.on && 2 * g_trace.used + 1 < (int)g_trace.ev.size();
-  if (traced) (void)hipEventRecord(g_trace.ev[2 * g_trace.used], stream);
+  const int trace_slot = fp4_trace_open(FP4_TRACE_GEMM, stream);
   const bool ragged = (g.Kb % BKB) != 0;
 #define FP4_GEMM_LAUNCH(OB, DG, WB)                                                                       \
   do {                                                                                                    \
@@ -476,35 +469,9 @@ int fp4_launch_gemm(const uint8_t* L, const float* gl, const uint8_t* Rt, const 
     FP4_GEMM_LAUNCH(false, false, false);
   }
 #undef FP4_GEMM_LAUNCH
-  if (traced) (void)hipEventRecord(g_trace.ev[2 * g_trace.used++ + 1], stream);
+  fp4_trace_close(trace_slot, stream);
   FP4_CHECK_LAUNCH();
   return FP4_OK;
-}
-
-extern "C" int fp4_trace_gemm_begin(int max_launches) {
-  if (max_launches <= 0) return FP4_ERR_SHAPE;
-  for (hipEvent_t e : g_trace.ev) (void)hipEventDestroy(e);
-  g_trace.ev.assign(2 * (size_t)max_launches, nullptr);
-  for (hipEvent_t& e : g_trace.ev)
-    if (hipEventCreate(&e) != hipSuccess) return FP4_ERR_HIP;
-  g_trace.used = 0;
-  g_trace.on = true;
-  return FP4_OK;
-}
-
-extern "C" int fp4_trace_gemm_end(float* ms_host, int capacity) {
-  g_trace.on = false;
-  int n = g_trace.used < capacity ? g_trace.used : capacity;
-  for (int i = 0; i < n; ++i) {
-    if (hipEventSynchronize(g_trace.ev[2 * i + 1]) != hipSuccess) return FP4_ERR_HIP;
-    if (hipEventElapsedTime(&ms_host[i], g_trace.ev[2 * i], g_trace.ev[2 * i + 1]) != hipSuccess)
-      return FP4_ERR_HIP;
-  }
-  for (hipEvent_t e : g_trace.ev) (void)hipEventDestroy(e);
-  g_trace.ev.clear();
-  const int used = g_trace.used;
-  g_trace.used = 0;
-  return used;
 }
 
 extern "C" int fp4_gemm(const uint8_t* codes_l, const float* gamma_l, const uint8_t* codes_rt,

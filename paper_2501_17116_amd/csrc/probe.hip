@@ -67,3 +67,54 @@ extern "C" int fp4_probe_copy(const void* src, void* dst, int64_t nbytes, void* 
   FP4_CHECK_LAUNCH();
   return FP4_OK;
 }
+
+// ---- per-launch timing of the two heavy kernels (off unless fp4_trace_begin was called) ---------
+#include <vector>
+namespace {
+struct LaunchTrace {
+  std::vector<hipEvent_t> ev;   // start/stop pairs
+  std::vector<int> kind;
+  int used = 0;
+  bool on = false;
+};
+LaunchTrace g_trace;
+}  // namespace
+
+// Called by the launchers around a kernel launch: a slot (>= 0) while tracing is on and room is left.
+int fp4_trace_open(int kind, hipStream_t stream) {
+  if (!g_trace.on || 2 * g_trace.used + 1 >= (int)g_trace.ev.size()) return -1;
+  const int slot = g_trace.used++;
+  g_trace.kind[slot] = kind;
+  (void)hipEventRecord(g_trace.ev[2 * slot], stream);
+  return slot;
+}
+void fp4_trace_close(int slot, hipStream_t stream) {
+  if (slot >= 0) (void)hipEventRecord(g_trace.ev[2 * slot + 1], stream);
+}
+
+extern "C" int fp4_trace_begin(int max_launches) {
+  if (max_launches <= 0) return FP4_ERR_SHAPE;
+  for (hipEvent_t e : g_trace.ev) (void)hipEventDestroy(e);
+  g_trace.ev.assign(2 * (size_t)max_launches, nullptr);
+  g_trace.kind.assign((size_t)max_launches, 0);
+  for (hipEvent_t& e : g_trace.ev)
+    if (hipEventCreate(&e) != hipSuccess) return FP4_ERR_HIP;
+  g_trace.used = 0;
+  g_trace.on = true;
+  return FP4_OK;
+}
+
+extern "C" int fp4_trace_end(float* ms_host, int* kind_host, int capacity) {
+  g_trace.on = false;
+  const int n = g_trace.used < capacity ? g_trace.used : capacity;
+  for (int i = 0; i < n; ++i) {
+    if (hipEventSynchronize(g_trace.ev[2 * i + 1]) != hipSuccess) return FP4_ERR_HIP;
+    if (hipEventElapsedTime(&ms_host[i], g_trace.ev[2 * i], g_trace.ev[2 * i + 1]) != hipSuccess) return FP4_ERR_HIP;
+    kind_host[i] = g_trace.kind[i];
+  }
+  for (hipEvent_t e : g_trace.ev) (void)hipEventDestroy(e);
+  g_trace.ev.clear();
+  const int used = g_trace.used;
+  g_trace.used = 0;
+  return used;
+}

@@ -179,6 +179,7 @@ struct RowArgs {
 // part.  All counts are exact, so the result does not depend on the order of the atomics.
 // ------------------------------------------------------------------------------------------
 constexpr int TS_WORDS = 2048;   // LDS words per row: 256 bins x 8 replicas, or 2 targets x 256 bins x 4 replicas
+constexpr int TS_ROW = TS_WORDS + 64;   // plus one word per lane for additions that count nothing
 
 template <int TPR>
 FP4_D void row_sync() {
@@ -195,9 +196,58 @@ FP4_D void row_sync() {
 // zero) and only the key's upper 16 bits matter (the lower ones are the same for equal values).
 FP4_D uint32_t order_key32(uint32_t bits) { return bits ^ ((uint32_t)((int32_t)bits >> 31) | 0x80000000u); }
 
+// One histogram pass over the row's cached units.  FIRST: all elements, digit = top byte, 8 replicas
+// per bin.  Later passes: only elements whose bits above the digit equal one of the two prefixes,
+// into that target's histogram (4 replicas per bin; equal prefixes share histogram 0).  One atomic
+// per element and no branch: an element that takes no part (past the row's end, outside both
+// target bins) adds to a word of its own lane that nobody reads.
+template <class DT, int TPR, int NV, bool FIRST>
+FP4_D void select_hist_pass(Raw8<DT> (&cache)[NV], bool row_ok, int t, int64_t cols, int64_t nunits, int dshift,
+                            int pshift, uint32_t prefix0, uint32_t prefix1, uint32_t* hist) {
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t trash = TS_WORDS + lane;
+  const uint32_t rep8 = lane & 7, rep4 = lane & 3;
+#pragma unroll
+  for (int u = 0; u < NV; ++u) {
+    // every pass derives the keys from the raw units again: hide that they are loop-invariant, or
+    // the optimizer keeps all of a thread's keys alive across the passes
+    if constexpr (__is_same(DT, BF16)) asm volatile("" : "+v"(cache[u].r));
+    else asm volatile("" : "+v"(cache[u].a), "+v"(cache[u].b));
+    const int64_t unit = (int64_t)u * TPR + t;
+    const int valid = (row_ok && unit < nunits) ? (int)min((int64_t)8, cols - unit * 8) : 0;
+    uint32_t bits[8];
+    if constexpr (__is_same(DT, BF16)) {
+      bits[0] = cache[u].r.x << 16; bits[1] = cache[u].r.x & 0xffff0000u;
+      bits[2] = cache[u].r.y << 16; bits[3] = cache[u].r.y & 0xffff0000u;
+      bits[4] = cache[u].r.z << 16; bits[5] = cache[u].r.z & 0xffff0000u;
+      bits[6] = cache[u].r.w << 16; bits[7] = cache[u].r.w & 0xffff0000u;
+    } else {
+      bits[0] = f2u(cache[u].a.x); bits[1] = f2u(cache[u].a.y); bits[2] = f2u(cache[u].a.z); bits[3] = f2u(cache[u].a.w);
+      bits[4] = f2u(cache[u].b.x); bits[5] = f2u(cache[u].b.y); bits[6] = f2u(cache[u].b.z); bits[7] = f2u(cache[u].b.w);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t key = order_key32(bits[e]);
+      const uint32_t d = (key >> dshift) & 255u;
+      uint32_t slot, take;
+      if constexpr (FIRST) {
+        slot = d * 8 + rep8;
+        take = e < valid ? ~0u : 0u;
+      } else {
+        const uint32_t above = key >> pshift;
+        const uint32_t m0 = above == prefix0 ? ~0u : 0u, m1 = above == prefix1 ? ~0u : 0u;
+        slot = d * 4 + rep4 + (1024u & ~m0);            // target 0's histogram wins when both match
+        take = (m0 | m1) & (e < valid ? ~0u : 0u);
+      }
+      atomicAdd(&hist[(slot & take) | (trash & ~take)], 1u);
+    }
+    __builtin_amdgcn_sched_barrier(0);   // one unit at a time: keeps the register count down
+  }
+}
+
 template <class DT, int TPR, int NV>
-FP4_D void select_row_thresholds(const Raw8<DT> (&cache)[NV], bool row_ok, int t, int64_t cols, int64_t nunits,
-                                 int64_t tail_k, uint32_t* hist /* this row's TS_WORDS */, uint32_t* s_sel /* [>= 8] */,
+FP4_D void select_row_thresholds(Raw8<DT> (&cache)[NV], bool row_ok, int t, int64_t cols, int64_t nunits,
+                                 int64_t tail_k, uint32_t* hist /* this row's TS_ROW words */, uint32_t* s_sel /* [>= 8] */,
                                  float& lo, float& hi) {
   constexpr int KEY_BITS = __is_same(DT, BF16) ? 16 : 32;
   constexpr int PASSES = KEY_BITS / 8;
@@ -210,37 +260,11 @@ FP4_D void select_row_thresholds(const Raw8<DT> (&cache)[NV], bool row_ok, int t
     row_sync<TPR>();
     const int dshift = 32 - 8 * (p + 1);    // digit = (key >> dshift) & 255
     const int pshift = 32 - 8 * p;          // bits above the digit
-#pragma unroll
-    for (int u = 0; u < NV; ++u) {
-      const int64_t unit = (int64_t)u * TPR + t;
-      const int valid = (row_ok && unit < nunits) ? (int)min((int64_t)8, cols - unit * 8) : 0;
-      uint32_t bits[8];
-      if constexpr (__is_same(DT, BF16)) {
-        bits[0] = cache[u].r.x << 16; bits[1] = cache[u].r.x & 0xffff0000u;
-        bits[2] = cache[u].r.y << 16; bits[3] = cache[u].r.y & 0xffff0000u;
-        bits[4] = cache[u].r.z << 16; bits[5] = cache[u].r.z & 0xffff0000u;
-        bits[6] = cache[u].r.w << 16; bits[7] = cache[u].r.w & 0xffff0000u;
-      } else {
-        bits[0] = f2u(cache[u].a.x); bits[1] = f2u(cache[u].a.y); bits[2] = f2u(cache[u].a.z); bits[3] = f2u(cache[u].a.w);
-        bits[4] = f2u(cache[u].b.x); bits[5] = f2u(cache[u].b.y); bits[6] = f2u(cache[u].b.z); bits[7] = f2u(cache[u].b.w);
-      }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        if (e < valid) {
-          const uint32_t key = order_key32(bits[e]);
-          const uint32_t d = (key >> dshift) & 255u;
-          if (p == 0) {
-            atomicAdd(&hist[d * 8 + (lane & 7)], 1u);
-          } else {
-            const uint32_t above = key >> pshift;
-            if (above == prefix[0]) atomicAdd(&hist[d * 4 + (lane & 3)], 1u);
-            if (above == prefix[1]) atomicAdd(&hist[1024 + d * 4 + (lane & 3)], 1u);
-          }
-        }
-      }
-    }
+    if (p == 0) select_hist_pass<DT, TPR, NV, true>(cache, row_ok, t, cols, nunits, dshift, 0, 0u, 0u, hist);
+    else select_hist_pass<DT, TPR, NV, false>(cache, row_ok, t, cols, nunits, dshift, pshift, prefix[0], prefix[1], hist);
     row_sync<TPR>();
     // the bin that holds each target's rank: exclusive prefix of the bin counts over the row's threads
+    const bool shared_hist = prefix[0] == prefix[1];   // then every matching element was counted in histogram 0
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       constexpr int BPT = 256 / TPR;   // bins per thread: 4 (one wave) or 1 (the workgroup)
@@ -252,7 +276,8 @@ FP4_D void select_row_thresholds(const Raw8<DT> (&cache)[NV], bool row_ok, int t
           const u32x4 q0 = reinterpret_cast<const u32x4*>(hist)[b * 2], q1 = reinterpret_cast<const u32x4*>(hist)[b * 2 + 1];
           c[j] = q0.x + q0.y + q0.z + q0.w + q1.x + q1.y + q1.z + q1.w;
         } else {
-          const u32x4 q0 = reinterpret_cast<const u32x4*>(hist)[s * 256 + b];
+          const int h = (s == 1 && !shared_hist) ? 256 : 0;
+          const u32x4 q0 = reinterpret_cast<const u32x4*>(hist)[h + b];
           c[j] = q0.x + q0.y + q0.z + q0.w;
         }
         sum += c[j];
@@ -319,7 +344,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
   __shared__ float s_max[4];
   __shared__ int s_cnt[4];
   __shared__ int s_round[CACHED ? NV : 1][4];
-  __shared__ __attribute__((aligned(16))) uint32_t s_hist[TOKEN ? RPB * TS_WORDS : 4];
+  __shared__ __attribute__((aligned(16))) uint32_t s_hist[TOKEN ? RPB * TS_ROW : 4];
   __shared__ uint32_t s_sel[8];
 
   const int tid = threadIdx.x;
@@ -360,7 +385,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
     }
     if constexpr (TOKEN) {
       select_row_thresholds<DT, TPR, NV>(cache, row_ok, t, a.cols, nunits, a.tail_k,
-                                         s_hist + (TPR == 256 ? 0 : wave * TS_WORDS), s_sel, lo, hi);
+                                         s_hist + (TPR == 256 ? 0 : wave * TS_ROW), s_sel, lo, hi);
       if (row_ok && t == 0) { a.thr_out[2 * row] = lo; a.thr_out[2 * row + 1] = hi; }
     }
 #pragma unroll

@@ -17,6 +17,7 @@
 // stall their workgroup; they are left out of the tiled kernel and handled by a kernel that
 // spreads one row's entries over a workgroup and reduces.
 #include "fp4_common.h"
+#include "fp4_measure.h"
 
 #include <algorithm>
 #include <type_traits>
@@ -764,6 +765,8 @@ __global__ __launch_bounds__(256) void csr_bitmap_sort_kernel(const int64_t* seg
 }  // namespace
 
 // ---- launchers ---------------------------------------------------------------------------------
+int fp4_trace_open(int kind, hipStream_t stream);
+void fp4_trace_close(int slot, hipStream_t stream);
 int64_t fp4_spmm_long_list_cap(int64_t capacity) { return capacity / LONG_ROW + 2; }
 
 // int32 words of scratch fp4_launch_spmm needs: count[64 (only [0] used)], list[list_cap], then
@@ -779,10 +782,12 @@ int fp4_launch_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float*
   if (P == 0 || N == 0) return FP4_OK;
   if (Q >= ((int64_t)1 << 21)) return FP4_ERR_SHAPE;   // 32-bit entry offsets inside a workgroup's 1024 rows
   const dim3 grid((unsigned)((P + SP_ROWS - 1) / SP_ROWS), (unsigned)((N + SP_COLS - 1) / SP_COLS));
+  const int trace_slot = fp4_trace_open(FP4_TRACE_SPMM, s);
   if (bf16)
     hipLaunchKernelGGL((spmm_tile_kernel<BF16>), grid, dim3(SP_ROWS), 0, s, row_ptr, col_idx, val, capacity, P, Q, D, N, R);
   else
     hipLaunchKernelGGL((spmm_tile_kernel<F32>), grid, dim3(SP_ROWS), 0, s, row_ptr, col_idx, val, capacity, P, Q, D, N, R);
+  fp4_trace_close(trace_slot, s);
   if (Q > LONG_ROW && capacity > LONG_ROW) {   // otherwise no row can be long
     int32_t* count = scratch;
     int32_t* list = scratch + 64;
