@@ -285,6 +285,91 @@ def scaled_weights(W: np.ndarray, gamma_w: np.ndarray) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------------
+# Mixed formats (Sec. 4.3 ablations: W4A8 = 4-bit weights with 8-bit activations, W8A4 the
+# reverse).  The paper names FP8 without fixing the variant or a rounding rule; reading: the
+# OCP E4M3 format (1 sign, 4 exponent bits with bias 7, 3 mantissa bits, no infinities, largest
+# magnitude 448, subnormal quantum 2^-9), round to nearest with ties to even, sign kept,
+# magnitudes above 448 saturate; absmax scaling as Eq. 1 with MAX = 448, vector-wise like FP4.
+# ----------------------------------------------------------------------------------
+FP8_MAX = F32(448.0)
+
+
+def q_e4m3(v: np.ndarray) -> np.ndarray:
+    """fp32 values -> E4M3 codes (uint8).  Finite inputs."""
+    v = np.asarray(v, dtype=F32)
+    a = np.abs(v.astype(np.float64))
+    _, e = np.frexp(np.maximum(a, 2.0 ** -6))            # a = m * 2^e, m in [0.5, 1)  =>  binade exponent e - 1
+    quantum = np.ldexp(1.0, (e - 1) - 3)                  # three mantissa bits; 2^-9 below the smallest normal
+    q = np.minimum(np.rint(a / quantum) * quantum, 448.0)   # np.rint: ties to even
+    m, e2 = np.frexp(np.where(q >= 2.0 ** -6, q, 1.0))
+    normal = (((e2 - 1) + 7).astype(np.int64) << 3) | np.rint((m * 2.0 - 1.0) * 8.0).astype(np.int64)
+    sub = np.rint(q * 512.0).astype(np.int64)            # 0..7 in units of 2^-9
+    mag = np.where(q >= 2.0 ** -6, normal, sub)
+    return (mag | (np.signbit(v).astype(np.int64) << 7)).astype(np.uint8)
+
+
+def e4m3_decode(codes: np.ndarray) -> np.ndarray:
+    """E4M3 codes -> fp32 values (exact).  The NaN patterns (0x7f, 0xff) are never produced."""
+    codes = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    ef, mf = (codes >> 3) & 15, codes & 7
+    mag = np.where(ef == 0, mf * 2.0 ** -9, (1.0 + mf / 8.0) * np.exp2(ef.astype(np.float64) - 7.0))
+    return np.where(codes & 128, -mag, mag).astype(F32)
+
+
+def quantize_rows_fp8(x: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """One scale per row, gamma = fl32(448 / absmax) (1 for a vanishing row), codes = E4M3 of
+    fl32(x * gamma)."""
+    x = np.asarray(x, dtype=F32)
+    amax = np.max(np.abs(x), axis=1) if x.shape[1] else np.zeros(x.shape[0], F32)
+    with np.errstate(divide="ignore", over="ignore", invalid="ignore"):
+        g = (FP8_MAX / amax).astype(F32)
+    gamma = np.where(np.isfinite(g) & (amax > 0), g, F32(1.0)).astype(F32)
+    return q_e4m3((x * gamma[:, None]).astype(F32)), gamma
+
+
+def quantize_cols_fp8(x: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """One scale per column, codes transposed [C, R] (as quantize_cols)."""
+    return quantize_rows_fp8(np.ascontiguousarray(np.asarray(x, dtype=F32).T))
+
+
+def dequant_gemm_values(vals_l: np.ndarray, gamma_l: np.ndarray, vals_rt: np.ndarray, gamma_r: np.ndarray) -> np.ndarray:
+    """(L Rt^T) / (gamma_l gamma_r) for decoded operand values of any format, fp64 (Fig. 2)."""
+    acc = vals_l.astype(np.float64) @ vals_rt.astype(np.float64).T
+    return acc * (1.0 / gamma_l.astype(np.float64))[:, None] * (1.0 / gamma_r.astype(np.float64))[None, :]
+
+
+def linear_fwd_mixed(A: np.ndarray, W: np.ndarray, act_fp8: bool, wgt_fp8: bool, alpha: float = 1.0,
+                     out_dtype: str = "f32") -> np.ndarray:
+    """Forward pass with one operand in FP8 (Sec. 4.3): W4A8 (act_fp8: activations E4M3 per token, no
+    clamp -- the ablation isolates the weight side) or W8A4 (wgt_fp8: weights E4M3 per output channel,
+    activations FP4 with the clamp and residual of Sec. 3.2)."""
+    A = np.asarray(A, dtype=F32)
+    W = np.asarray(W, dtype=F32)
+    res = None
+    if act_fp8:
+        if alpha != 1.0:
+            raise ValueError("the clamp belongs to 4-bit activations")
+        ca, ga = quantize_rows_fp8(A)
+        va = e4m3_decode(ca)
+    else:
+        lo, hi = occ_thresholds(A, alpha)
+        Ac, csr = occ_clamp_residual(A, lo, hi)
+        ca, ga = quantize_rows(Ac)
+        va = e2m1_decode(ca)
+        res = csr
+    if wgt_fp8:
+        cw, gw = quantize_cols_fp8(W)
+        vw = e4m3_decode(cw)
+    else:
+        cw, gw = quantize_cols(W)
+        vw = e2m1_decode(cw)
+    Y = dequant_gemm_values(va, ga, vw, gw)
+    if res is not None and res.val.size:
+        Y = Y + res.to_dense() @ W.astype(np.float64)
+    return round_to_dtype(Y, out_dtype)
+
+
+# ----------------------------------------------------------------------------------
 # The linear layer: forward, dgrad, wgrad
 # ----------------------------------------------------------------------------------
 class FwdState(NamedTuple):
