@@ -70,6 +70,11 @@ typedef enum {
 
 typedef enum { FP4_F32 = 0, FP4_BF16 = 1 } fp4_dtype;
 
+/* Operand formats of the mixed-format ablations (Sec. 4.3): E2M1 as above; E4M3 = the OCP FP8
+ * format (bias 7, largest magnitude 448, no infinities), one code per byte, rounded to nearest
+ * with ties to even, sign kept, saturating, scaled with gamma = fl32(448 / absmax). */
+typedef enum { FP4_FMT_E2M1 = 0, FP4_FMT_E4M3 = 1 } fp4_format;
+
 typedef enum {
   FP4_AXIS_ROW = 0, /* one scale per row;    codes [rows x cols/2], cols contiguous       */
   FP4_AXIS_COL = 1  /* one scale per column; codes TRANSPOSED [cols x rows/2]             */
@@ -88,7 +93,8 @@ typedef enum {
   FP4_OP_DGRAD = 3,
   FP4_OP_WGRAD = 4,
   FP4_OP_SPMM = 5,     /* (M=P rows of S, K=Q, N)                                        */
-  FP4_OP_PREPARE = 6   /* fp4_prepare_weights (M ignored)                                 */
+  FP4_OP_PREPARE = 6,  /* fp4_prepare_weights (M ignored)                                 */
+  FP4_OP_FWD_MIXED = 7 /* fp4_linear_fwd_mixed                                            */
 } fp4_op;
 
 /* What the forward pass leaves for the weight-gradient pass (Sec. 3.1 needs the
@@ -231,6 +237,29 @@ int fp4_linear_bwd_wgrad(const void* A, const void* dY, const void* W, fp4_dtype
 int fp4_gemm(const uint8_t* codes_l, const float* gamma_l, const uint8_t* codes_rt,
              const float* gamma_r, int64_t P, int64_t Q, int64_t Kc,
              const float* addend, void* out, fp4_dtype out_dt, int64_t ldo, void* stream);
+
+/* ---- mixed formats: W4A8 / W8A4 (Sec. 4.3) ----
+ * fp8_quantize: as fp4_quantize with E4M3 codes, one per byte: ROW: codes [rows x cols];
+ *   COL: codes TRANSPOSED [cols x rows].  Workspace as fp4_quantize (COL only).
+ * fp4_gemm_mixed: as fp4_gemm with exactly one operand in E4M3 ([rows x Kc] bytes) and the other
+ *   in E2M1 ([rows x Kc/2] bytes); Kc a multiple of 128.  The fp32 accumulator of a mixed product is
+ *   not exact (products are multiples of 2^-10 up to 2688), so results are compared under the
+ *   tolerance of the scaled outputs.
+ * fp4_linear_fwd_mixed: the forward pass with one operand in 8 bits.  act_fmt = E4M3, wgt_fmt =
+ *   E2M1 (W4A8): activations E4M3 per token, no clamp (alpha must be 1), weights E2M1 per output
+ *   channel.  act_fmt = E2M1, wgt_fmt = E4M3 (W8A4): activations E2M1 per token with the clamp and
+ *   residual of Sec. 3.2, weights E4M3 per output channel.  saved as in fp4_linear_fwd (gamma_W
+ *   then holds the 8-bit scales in the W8A4 case).  K a multiple of 128.  Workspace:
+ *   fp4_workspace_bytes(FP4_OP_FWD_MIXED, M, K, N, dt).  The backward passes stay FP4. */
+int fp8_quantize(const void* x, fp4_dtype dt, int64_t rows, int64_t cols, int64_t ld, fp4_axis axis,
+                 uint8_t* codes, float* gamma, void* workspace, size_t workspace_bytes, void* stream);
+int fp4_gemm_mixed(const uint8_t* codes_l, fp4_format fmt_l, const float* gamma_l,
+                   const uint8_t* codes_rt, fp4_format fmt_r, const float* gamma_r,
+                   int64_t P, int64_t Q, int64_t Kc, const float* addend, void* out, fp4_dtype out_dt,
+                   int64_t ldo, void* stream);
+int fp4_linear_fwd_mixed(const void* A, const void* W, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
+                         fp4_format act_fmt, fp4_format wgt_fmt, double alpha, void* Y,
+                         const fp4_fwd_ctx* saved, void* workspace, size_t workspace_bytes, void* stream);
 
 /* One 4-bit code per output byte (for inspecting packed tensors). */
 int fp4_unpack(const uint8_t* codes, int64_t rows, int64_t cols, uint8_t* one_per_byte,

@@ -17,6 +17,8 @@ extern "C" {
  * n fp32 values in HOST memory (the same inline function the kernels use, compiled for
  * the CPU; lets the rounding be checked exhaustively without a GPU). */
 int fp4_host_round_codes(const float* x_host, int64_t n, uint8_t* codes_host);
+/* The same for the E4M3 rounding of the mixed-format path. */
+int fp8_host_round_codes(const float* x_host, int64_t n, uint8_t* codes_host);
 
 /* The rounding as the quantization kernels perform it on the device (App. A's rule carried out
  * by the FP4 convert instruction, eight values per packed word): codes[i] = Q(x[i]), one code per

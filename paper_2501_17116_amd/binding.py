@@ -19,7 +19,8 @@ LIB_PATH = os.path.join(_HERE, "libfp4mi.so")
 FP4_F32, FP4_BF16 = 0, 1
 FP4_AXIS_ROW, FP4_AXIS_COL = 0, 1
 FP4_OCC_TENSOR, FP4_OCC_TOKEN = 0, 1
-FP4_OP_QUANTIZE, FP4_OP_OCC, FP4_OP_FWD, FP4_OP_DGRAD, FP4_OP_WGRAD, FP4_OP_SPMM, FP4_OP_PREPARE = range(7)
+FP4_OP_QUANTIZE, FP4_OP_OCC, FP4_OP_FWD, FP4_OP_DGRAD, FP4_OP_WGRAD, FP4_OP_SPMM, FP4_OP_PREPARE, FP4_OP_FWD_MIXED = range(8)
+FP4_FMT_E2M1, FP4_FMT_E4M3 = 0, 1
 
 _lib = None
 
@@ -73,6 +74,12 @@ def lib() -> C.CDLL:
                                             C.POINTER(fp4_fwd_ctx), vp, sz, vp]
         L.fp4_linear_bwd_dgrad_cached.argtypes = [vp, C.POINTER(fp4_weight_cache), i32, i64, i64, i64, vp, vp, sz, vp]
         for name in ("fp4_prepare_weights", "fp4_linear_fwd_cached", "fp4_linear_bwd_dgrad_cached"):
+            getattr(L, name).restype = i32
+        L.fp8_quantize.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, vp, sz, vp]
+        L.fp4_gemm_mixed.argtypes = [vp, i32, vp, vp, i32, vp, i64, i64, i64, vp, vp, i32, i64, vp]
+        L.fp4_linear_fwd_mixed.argtypes = [vp, vp, i32, i64, i64, i64, i32, i32, f64, vp, C.POINTER(fp4_fwd_ctx), vp, sz, vp]
+        L.fp8_host_round_codes.argtypes = [vp, i64, vp]
+        for name in ("fp8_quantize", "fp4_gemm_mixed", "fp4_linear_fwd_mixed", "fp8_host_round_codes"):
             getattr(L, name).restype = i32
         L.fp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, vp, i32, i64, vp]
         L.fp4_unpack.argtypes = [vp, i64, i64, vp, vp]
@@ -380,6 +387,61 @@ def fp4_gemm(codes_l: torch.Tensor, gamma_l: Optional[torch.Tensor], codes_rt: t
             addend = pad
     _check(lib().fp4_gemm(_ptr(codes_l), _ptr(gamma_l), _ptr(codes_rt), _ptr(gamma_r), P, Q, 2 * kb,
                           _ptr(addend), _ptr(out), _dt(out), ldo, _stream()), "fp4_gemm")
+    return out
+
+
+def fp8_quantize(x: torch.Tensor, axis: int, ws: Optional[Workspace] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """E4M3 codes (one per byte; COL: transposed) and scales gamma = 448 / absmax."""
+    _dev_check(x)
+    rows, cols = x.shape
+    shape, n = ((rows, cols), rows) if axis == FP4_AXIS_ROW else ((cols, rows), cols)
+    codes = torch.empty(shape, dtype=torch.uint8, device=x.device)
+    gamma = torch.empty(n, dtype=torch.float32, device=x.device)
+    w = _ws(workspace_bytes(FP4_OP_QUANTIZE, rows, cols, 0, _dt(x)), ws)
+    _check(lib().fp8_quantize(_ptr(x), _dt(x), rows, cols, cols, axis, _ptr(codes), _ptr(gamma), _ptr(w), w.numel(),
+                              _stream()), "fp8_quantize")
+    return codes, gamma
+
+
+def fp4_gemm_mixed(codes_l: torch.Tensor, fmt_l: int, gamma_l: Optional[torch.Tensor], codes_rt: torch.Tensor, fmt_r: int,
+                   gamma_r: Optional[torch.Tensor], out_dtype=torch.float32, addend: Optional[torch.Tensor] = None):
+    _dev_check(codes_l, gamma_l, codes_rt, gamma_r, addend)
+    P, Q = codes_l.shape[0], codes_rt.shape[0]
+    Kc = codes_l.shape[1] * (1 if fmt_l == FP4_FMT_E4M3 else 2)
+    if Kc != codes_rt.shape[1] * (1 if fmt_r == FP4_FMT_E4M3 else 2):
+        raise ValueError("operands disagree in K")
+    if Q % 8:
+        raise ValueError("Q must be a multiple of 8 here")
+    out = torch.empty((P, Q), dtype=out_dtype, device=codes_l.device)
+    _check(lib().fp4_gemm_mixed(_ptr(codes_l), fmt_l, _ptr(gamma_l), _ptr(codes_rt), fmt_r, _ptr(gamma_r), P, Q, Kc,
+                                _ptr(addend), _ptr(out), _dt(out), Q, _stream()), "fp4_gemm_mixed")
+    return out
+
+
+def fp4_linear_fwd_mixed(A: torch.Tensor, W: torch.Tensor, act_fmt: int, wgt_fmt: int, alpha: float = 1.0,
+                         ctx: Optional[FwdCtx] = None, Y: Optional[torch.Tensor] = None, ws: Optional[Workspace] = None):
+    _dev_check(A, W, Y)
+    M, K = A.shape
+    K2, N = W.shape
+    if K2 != K or A.dtype != W.dtype:
+        raise ValueError("A [M,K] and W [K,N] must agree in K and dtype")
+    if ctx is None:
+        ctx = FwdCtx(M, K, N, alpha, A.device)
+    if Y is None:
+        Y = torch.empty((M, N), dtype=A.dtype, device=A.device)
+    w = _ws(workspace_bytes(FP4_OP_FWD_MIXED, M, K, N, _dt(A)), ws)
+    _check(lib().fp4_linear_fwd_mixed(_ptr(A), _ptr(W), _dt(A), M, K, N, act_fmt, wgt_fmt, float(alpha), _ptr(Y),
+                                      C.byref(ctx.c), _ptr(w), w.numel(), _stream()), "fp4_linear_fwd_mixed")
+    return Y, ctx
+
+
+def fp8_host_round_codes(x_host):
+    """numpy fp32 array (host) -> uint8 E4M3 codes, through the library's own rounding routine."""
+    import numpy as np
+    x = np.ascontiguousarray(x_host, dtype=np.float32)
+    out = np.empty(x.shape, dtype=np.uint8)
+    _check(lib().fp8_host_round_codes(x.ctypes.data_as(C.c_void_p), x.size, out.ctypes.data_as(C.c_void_p)),
+           "fp8_host_round_codes")
     return out
 
 

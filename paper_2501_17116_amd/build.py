@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfp4mi.so")
-SOURCES = ["gemm.hip", "quantize.hip", "occ.hip", "spmm.hip", "probe.hip", "api.hip"]
+SOURCES = ["gemm.hip", "gemm_mixed.hip", "quantize.hip", "occ.hip", "spmm.hip", "probe.hip", "api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"),
          "-I" + CSRC, "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

@@ -41,6 +41,13 @@ int fp4_launch_csr_transpose(const int64_t* row_ptr, const int32_t* col_idx, con
                              int32_t* t_idx, float* t_val, int32_t* u_idx, float* u_val, int32_t* scratch,
                              hipStream_t s);
 int64_t fp4_spmm_long_list_cap(int64_t capacity);
+int fp8_launch_quantize_rows(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, uint8_t* codes,
+                             float* gamma, hipStream_t s);
+int fp8_launch_quantize_cols(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, uint8_t* codes_t,
+                             float* gamma, uint32_t* amax_scratch, hipStream_t s);
+int fp4_launch_gemm_mixed(const uint8_t* L, const float* gl, const uint8_t* Rt, const float* gr, int l_fp8, int64_t P,
+                          int64_t Q, int64_t Kc, const float* addend, void* out, int out_bf16, int64_t ldo,
+                          hipStream_t stream);
 int64_t fp4_csr_transpose_scratch_words(int64_t P, int64_t Q);
 int fp4_launch_order_rows(const int64_t* row_ptr, int64_t rows, int64_t nidx, int64_t capacity,
                           const int32_t* u_idx, const float* u_val, int32_t* idx, float* val, hipStream_t s);
@@ -117,6 +124,19 @@ FwdWs carve_fwd(Carver& c, int64_t M, int64_t K, int64_t N, fp4_dtype dt) {
   return w;
 }
 
+// forward with one 8-bit operand: as FwdWs with room for one code per byte on either side
+FwdWs carve_fwd_mixed(Carver& c, int64_t M, int64_t K, int64_t N, fp4_dtype dt) {
+  FwdWs w;
+  w.qA = c.take<uint8_t>((size_t)(M * K));
+  w.gA = c.take<float>((size_t)M);
+  w.qWt = c.take<uint8_t>((size_t)(N * K));
+  w.amax = c.take<uint32_t>((size_t)fp4_quantize_cols_scratch_words(K, N));
+  w.occ = carve_occ(c, M, provisioned_entries(M, K));
+  w.R = dt == FP4_BF16 ? c.take<float>((size_t)(M * N)) : nullptr;
+  w.sp_scratch = c.take<int32_t>((size_t)fp4_spmm_scratch_words(fp4_spmm_long_list_cap(provisioned_entries(M, K)), K, N));
+  return w;
+}
+
 struct DgradWs { uint8_t* qdY; float* gdY; uint8_t* qW; float* gWk; };
 DgradWs carve_dgrad(Carver& c, int64_t M, int64_t K, int64_t N) {
   DgradWs w;
@@ -182,6 +202,7 @@ extern "C" size_t fp4_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, f
     case FP4_OP_DGRAD: carve_dgrad(c, M, K, N); break;
     case FP4_OP_WGRAD: carve_wgrad(c, M, K, N); break;
     case FP4_OP_PREPARE: c.take<uint32_t>((size_t)fp4_quantize_cols_scratch_words(K, N)); break;
+    case FP4_OP_FWD_MIXED: carve_fwd_mixed(c, M, K, N, dt); break;
     case FP4_OP_SPMM: c.take<int32_t>((size_t)fp4_spmm_scratch_words(M + 2, K, N)); break;   // long-row list: at most M rows
     default: return 0;
   }
@@ -393,6 +414,70 @@ extern "C" int fp4_linear_fwd(const void* A, const void* W, fp4_dtype dt, int64_
                               double alpha, void* Y, const fp4_fwd_ctx* saved, void* workspace,
                               size_t workspace_bytes, void* stream) {
   return fwd_impl(A, W, nullptr, dt, M, K, N, alpha, Y, saved, workspace, workspace_bytes, stream);
+}
+
+extern "C" int fp4_linear_fwd_mixed(const void* A, const void* W, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
+                                    fp4_format act_fmt, fp4_format wgt_fmt, double alpha, void* Y,
+                                    const fp4_fwd_ctx* saved, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!dtype_ok(dt)) return FP4_ERR_DTYPE;
+  const bool a8 = act_fmt == FP4_FMT_E4M3 && wgt_fmt == FP4_FMT_E2M1;   // W4A8
+  const bool w8 = act_fmt == FP4_FMT_E2M1 && wgt_fmt == FP4_FMT_E4M3;   // W8A4
+  if (!a8 && !w8) return FP4_ERR_DTYPE;
+  if (M <= 0 || K <= 0 || N <= 0 || (K % 128) != 0 || (N % 8) != 0) return FP4_ERR_SHAPE;
+  if (!(alpha > 0.5) || !(alpha <= 1.0) || (a8 && alpha != 1.0)) return FP4_ERR_ARG;   // the clamp belongs to 4-bit activations
+  if (!A || !W || !Y || !saved || !saved->gamma_W) return FP4_ERR_NULL;
+  if (!aligned16(A) || !aligned16(W) || !aligned16(Y)) return FP4_ERR_ARG;
+  const bool occ = alpha < 1.0;
+  const int64_t k = tail_count(M * K, alpha);
+  if (occ) {
+    if (saved->scope != FP4_OCC_TENSOR) return FP4_ERR_DTYPE;
+    if (!saved->thresholds || !saved->row_ptr || !saved->nnz) return FP4_ERR_NULL;
+    if (saved->capacity < 2 * k) return FP4_ERR_CAPACITY;
+    if (saved->capacity > 0 && (!saved->col_idx || !saved->val)) return FP4_ERR_NULL;
+    if (2 * k > provisioned_entries(M, K)) return FP4_ERR_ARG;
+  }
+  if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_FWD_MIXED, M, K, N, dt)) return FP4_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const int bf16 = dt == FP4_BF16;
+  Carver c(reinterpret_cast<void*>(align_up((size_t)(uintptr_t)workspace, 256)));
+  FwdWs w = carve_fwd_mixed(c, M, K, N, dt);
+  int rc;
+  if (w8) rc = fp8_launch_quantize_cols(W, bf16, K, N, N, w.qWt, saved->gamma_W, w.amax, s);
+  else rc = fp4_launch_quantize_cols(W, bf16, K, N, N, nullptr, 0, w.qWt, saved->gamma_W, w.amax, s);
+  if (rc) return rc;
+  const float* addend = nullptr;
+  if (a8) {
+    rc = fp8_launch_quantize_rows(A, bf16, M, K, K, w.qA, w.gA, s);
+    if (rc) return rc;
+  } else if (occ) {
+    const int64_t cap = std::min(saved->capacity, provisioned_entries(M, K));
+    rc = fp4_launch_thresholds(A, bf16, M, K, K, k, saved->thresholds, w.occ.select, w.occ.total, s);
+    if (!rc) rc = fp4_launch_occ_count(A, bf16, M, K, K, saved->thresholds, w.occ.row_cnt, s);
+    if (!rc) rc = fp4_launch_scan_rows(w.occ.row_cnt, M, saved->row_ptr, saved->nnz, s);
+    if (rc) return rc;
+    rc = fp4_launch_occ_rows(A, bf16, M, K, K, saved->thresholds, w.qA, w.gA, nullptr, saved->col_idx, saved->val,
+                             w.occ.tmp_col, w.occ.tmp_val, saved->row_ptr, cap, s);
+    if (rc == 1) {
+      rc = fp4_launch_order_rows(saved->row_ptr, M, K, cap, w.occ.tmp_col, w.occ.tmp_val, saved->col_idx, saved->val, s);
+      if (rc == 1)
+        rc = fp4_launch_csr_gather(w.occ.tmp_col, w.occ.tmp_val, M, cap, saved->row_ptr, saved->col_idx, saved->val, s);
+    }
+    if (rc) return rc;
+    float* R = bf16 ? w.R : reinterpret_cast<float*>(Y);
+    rc = fp4_launch_spmm(saved->row_ptr, saved->col_idx, saved->val, cap, M, K, W, bf16, N, R, w.sp_scratch,
+                         fp4_spmm_long_list_cap(provisioned_entries(M, K)), s);
+    if (rc) return rc;
+    addend = R;
+  } else {
+    rc = fp4_launch_quantize_rows(A, bf16, M, K, K, w.qA, w.gA, s);
+    if (rc) return rc;
+  }
+  if (!occ && (saved->thresholds || saved->row_ptr || saved->nnz)) {
+    hipLaunchKernelGGL(init_no_occ_kernel, dim3((unsigned)((M + 1 + 255) / 256)), dim3(256), 0, s, saved->thresholds,
+                       saved->row_ptr, M, saved->nnz);
+    if (hipGetLastError() != hipSuccess) return FP4_ERR_HIP;
+  }
+  return fp4_launch_gemm_mixed(w.qA, w.gA, w.qWt, saved->gamma_W, a8 ? 1 : 0, M, N, K, addend, Y, bf16, N, s);
 }
 
 extern "C" int fp4_linear_fwd_cached(const void* A, const void* W, const fp4_weight_cache* wq, fp4_dtype dt,

@@ -100,6 +100,40 @@ FP4_D float dge_factor(float w, float gamma, float pw, float inv_k, float cap) {
 }
 #endif  // __HIPCC__
 
+// Nearest E4M3 code (OCP FP8: bias 7, largest magnitude 448 = 0x7e, subnormal quantum 2^-9) of a
+// finite fp32 value: ties to the even mantissa, sign kept, magnitudes above 448 saturate.  The
+// 8-bit operand format of the mixed-format ablations (Sec. 4.3).
+FP4_HD uint32_t q_e4m3_code(float v) {
+  const uint32_t b = f2u(v);
+  const uint32_t s = (b >> 24) & 0x80u;
+  uint32_t a = b & 0x7fffffffu;
+  if (a > 0x43e00000u) a = 0x43e00000u;                 // 448
+  uint32_t code;
+  if (a >= 0x3c800000u) {                               // >= 2^-6: a normal number of the format
+    const uint32_t r = a + 0x7ffffu + ((a >> 20) & 1u); // nearest even at 3 mantissa bits; a carry moves the exponent
+    code = (r >> 20) - (120u << 3);                     // exponent field re-biased from 127 to 7
+  } else {                                              // below: multiples of 2^-9, 0 .. 8 (8 = the smallest normal)
+#if defined(__HIP_DEVICE_COMPILE__)
+    code = (uint32_t)__builtin_rintf(u2f(a) * 512.0f);
+#else
+    code = (uint32_t)__builtin_rintf(u2f(a) * 512.0f);  // default rounding mode: to nearest even
+#endif
+  }
+  return code | s;
+}
+
+// gamma = fl32(fmax / amax) with fmax the largest magnitude of the target format; 1 for amax == 0 or a
+// non-finite quotient.
+FP4_HD float absmax_to_gamma_of(float amax, float fmax) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  float g = __fdiv_rn(fmax, amax);
+#else
+  float g = fmax / amax;
+#endif
+  uint32_t gb = f2u(g) & 0x7fffffffu;
+  return (amax > 0.0f && gb < 0x7f800000u) ? g : 1.0f;
+}
+
 // gamma = fl32(6 / amax); 1 for amax == 0 or a non-finite quotient.
 FP4_HD float absmax_to_gamma(float amax) {
 #if defined(__HIP_DEVICE_COMPILE__)

@@ -740,7 +740,8 @@ __global__ __launch_bounds__(256) void col_absmax_kernel(ColArgs a) {
 
 // gamma[c] from the g partial rows of column maxima (bit patterns of non-negative floats order
 // like unsigned integers)
-__global__ __launch_bounds__(256) void amax_to_gamma_kernel(const uint32_t* part, int64_t g, float* gamma, int64_t n) {
+__global__ __launch_bounds__(256) void amax_to_gamma_kernel(const uint32_t* part, int64_t g, float* gamma, int64_t n,
+                                                            float fmax) {
   const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (c >= n) return;
   uint32_t m[16];
@@ -754,7 +755,7 @@ __global__ __launch_bounds__(256) void amax_to_gamma_kernel(const uint32_t* part
   for (; i < g; ++i) m[0] = max(m[0], part[i * n + c]);
 #pragma unroll
   for (int j = 1; j < 16; ++j) m[0] = max(m[0], m[j]);
-  gamma[c] = absmax_to_gamma(u2f(m[0]));
+  gamma[c] = absmax_to_gamma_of(u2f(m[0]), fmax);
 }
 
 constexpr int CT_ROWS = 256;
@@ -840,9 +841,106 @@ int launch_cols(const ColArgs& a, hipStream_t s) {
   hipLaunchKernelGGL((col_absmax_kernel<DT, CLAMP>), dim3((unsigned)((nunits + 63) / 64), (unsigned)rblocks), dim3(256),
                      0, s, a);
   hipLaunchKernelGGL(amax_to_gamma_kernel, dim3((unsigned)((a.cols + 255) / 256)), dim3(256), 0, s, a.amax_bits,
-                     rblocks, a.gamma, a.cols);
+                     rblocks, a.gamma, a.cols, 6.0f);
   hipLaunchKernelGGL((quantize_cols_kernel<DT, CLAMP>),
                      dim3((unsigned)((a.cols + CT_COLS - 1) / CT_COLS), (unsigned)((a.rows + CT_ROWS - 1) / CT_ROWS)),
+                     dim3(256), 0, s, a);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// FP8 (E4M3) vector-wise quantization for the mixed-format ablations (Sec. 4.3): same absmax
+// scaling with MAX = 448, one code per byte.  Not on the FP4 hot path: plain two-pass kernels.
+// ------------------------------------------------------------------------------------------
+FP4_D uint32_t pack4_e4m3(float a, float b, float c, float d, float gamma) {
+  return q_e4m3_code(__fmul_rn(a, gamma)) | (q_e4m3_code(__fmul_rn(b, gamma)) << 8) |
+         (q_e4m3_code(__fmul_rn(c, gamma)) << 16) | (q_e4m3_code(__fmul_rn(d, gamma)) << 24);
+}
+
+// One workgroup per row: absmax, then codes (the second read comes from L2).
+template <class DT>
+__global__ __launch_bounds__(256) void fp8_quantize_rows_kernel(const void* x, int64_t rows, int64_t cols, int64_t ld,
+                                                                uint8_t* codes, float* gamma) {
+  __shared__ float s_max[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t row = blockIdx.x;
+  const int64_t nunits = (cols + 7) / 8;
+  float amax = 0.0f;
+  for (int64_t u = tid; u < nunits; u += 256) {
+    float v[8];
+    load8<DT>(x, row * ld + u * 8, (int)min((int64_t)8, cols - u * 8), v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) amax = fmaxf(amax, fabsf(v[e]));
+  }
+  amax = wave_max(amax);
+  if (lane == 0) s_max[wave] = amax;
+  __syncthreads();
+  amax = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
+  const float g = absmax_to_gamma_of(amax, 448.0f);
+  if (tid == 0) gamma[row] = g;
+  const bool words_ok = (cols % 8) == 0;
+  for (int64_t u = tid; u < nunits; u += 256) {
+    const int valid = (int)min((int64_t)8, cols - u * 8);
+    float v[8];
+    load8<DT>(x, row * ld + u * 8, valid, v);
+    const uint32_t w0 = pack4_e4m3(v[0], v[1], v[2], v[3], g), w1 = pack4_e4m3(v[4], v[5], v[6], v[7], g);
+    uint8_t* dst = codes + row * cols + u * 8;
+    if (valid >= 8 && words_ok) {
+      *reinterpret_cast<u32x2*>(dst) = u32x2{w0, w1};
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (e < valid) dst[e] = (uint8_t)((e < 4 ? w0 >> (8 * e) : w1 >> (8 * (e - 4))) & 255u);
+    }
+  }
+}
+
+// Column-wise, transposing: 64 x 64 tiles through LDS; the scales come from the shared absmax pass.
+template <class DT>
+__global__ __launch_bounds__(256) void fp8_quantize_cols_kernel(ColArgs a) {
+  __shared__ __attribute__((aligned(16))) uint8_t s_b[64][80];   // [column][row], 16 bytes of padding per column
+  const int tid = threadIdx.x;
+  const int chunk = tid & 7, rg = tid >> 3;       // 8 columns; rows 2 rg, 2 rg + 1
+  const int64_t c0 = (int64_t)blockIdx.x * 64, r0 = (int64_t)blockIdx.y * 64;
+  const int64_t col = c0 + chunk * 8;
+  const int valid = col < a.cols ? (int)min((int64_t)8, a.cols - col) : 0;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int64_t r = r0 + rg * 2 + i;
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = 0.0f;
+    if (valid > 0 && r < a.rows) load8<DT>(a.x, r * a.ld + col, valid, v);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float g = e < valid ? a.gamma[col + e] : 1.0f;
+      s_b[chunk * 8 + e][rg * 2 + i] = (uint8_t)q_e4m3_code(__fmul_rn(v[e], g));
+    }
+  }
+  __syncthreads();
+  const int oc = tid >> 2, part = tid & 3;        // 4 threads per column, 16 rows (bytes) each
+  const int64_t ocol = c0 + oc;
+  if (ocol >= a.cols) return;
+  const int64_t rb = r0 + part * 16;
+  if (rb >= a.rows) return;
+  uint8_t* dst = a.codes_t + ocol * a.rows + rb;
+  const int n = (int)min((int64_t)16, a.rows - rb);
+  if (n == 16 && (a.rows % 16) == 0) {
+    *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(&s_b[oc][part * 16]);
+  } else {
+    for (int b = 0; b < n; ++b) dst[b] = s_b[oc][part * 16 + b];
+  }
+}
+
+template <class DT>
+int launch_cols_fp8(const ColArgs& a, hipStream_t s) {
+  const int64_t nunits = (a.cols + 7) / 8;
+  const int64_t rblocks = (a.rows + CA_ROWS - 1) / CA_ROWS;
+  hipLaunchKernelGGL((col_absmax_kernel<DT, false>), dim3((unsigned)((nunits + 63) / 64), (unsigned)rblocks), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(amax_to_gamma_kernel, dim3((unsigned)((a.cols + 255) / 256)), dim3(256), 0, s, a.amax_bits, rblocks,
+                     a.gamma, a.cols, 448.0f);
+  hipLaunchKernelGGL((fp8_quantize_cols_kernel<DT>), dim3((unsigned)((a.cols + 63) / 64), (unsigned)((a.rows + 63) / 64)),
                      dim3(256), 0, s, a);
   FP4_CHECK_LAUNCH();
   return FP4_OK;
@@ -971,6 +1069,46 @@ int fp4_launch_quantize_cols(const void* x, int bf16, int64_t rows, int64_t cols
   a.rows = rows; a.cols = cols; a.ld = ld;
   if (clamp_thr) return bf16 ? launch_cols<BF16, true>(a, s) : launch_cols<F32, true>(a, s);
   return bf16 ? launch_cols<BF16, false>(a, s) : launch_cols<F32, false>(a, s);
+}
+
+int fp8_launch_quantize_rows(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, uint8_t* codes,
+                             float* gamma, hipStream_t s) {
+  if (rows == 0 || cols == 0) return FP4_OK;
+  if (bf16) hipLaunchKernelGGL((fp8_quantize_rows_kernel<BF16>), dim3((unsigned)rows), dim3(256), 0, s, x, rows, cols, ld, codes, gamma);
+  else hipLaunchKernelGGL((fp8_quantize_rows_kernel<F32>), dim3((unsigned)rows), dim3(256), 0, s, x, rows, cols, ld, codes, gamma);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
+
+int fp8_launch_quantize_cols(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, uint8_t* codes_t,
+                             float* gamma, uint32_t* amax_scratch, hipStream_t s) {
+  if (rows == 0 || cols == 0) return FP4_OK;
+  ColArgs a = {};
+  a.x = x; a.codes_t = codes_t; a.gamma = gamma; a.amax_bits = amax_scratch;
+  a.rows = rows; a.cols = cols; a.ld = ld;
+  return bf16 ? launch_cols_fp8<BF16>(a, s) : launch_cols_fp8<F32>(a, s);
+}
+
+extern "C" int fp8_quantize(const void* x, fp4_dtype dt, int64_t rows, int64_t cols, int64_t ld, fp4_axis axis,
+                            uint8_t* codes, float* gamma, void* workspace, size_t workspace_bytes, void* stream) {
+  if (dt != FP4_F32 && dt != FP4_BF16) return FP4_ERR_DTYPE;
+  if (axis != FP4_AXIS_ROW && axis != FP4_AXIS_COL) return FP4_ERR_DTYPE;
+  if (rows < 0 || cols < 0 || ld < cols) return FP4_ERR_SHAPE;
+  if (rows == 0 || cols == 0) return FP4_OK;
+  if (!x || !codes || !gamma) return FP4_ERR_NULL;
+  if (!aligned16(x) || !aligned16(codes) || (ld % 8) != 0) return FP4_ERR_ARG;
+  if (axis == FP4_AXIS_ROW)
+    return fp8_launch_quantize_rows(x, dt == FP4_BF16, rows, cols, ld, codes, gamma, (hipStream_t)stream);
+  if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_QUANTIZE, rows, cols, 0, dt)) return FP4_ERR_WORKSPACE;
+  return fp8_launch_quantize_cols(x, dt == FP4_BF16, rows, cols, ld, codes, gamma, reinterpret_cast<uint32_t*>(workspace),
+                                  (hipStream_t)stream);
+}
+
+extern "C" int fp8_host_round_codes(const float* x_host, int64_t n, uint8_t* codes_host) {
+  if (n < 0) return FP4_ERR_SHAPE;
+  if (n && (!x_host || !codes_host)) return FP4_ERR_NULL;
+  for (int64_t i = 0; i < n; ++i) codes_host[i] = (uint8_t)q_e4m3_code(x_host[i]);
+  return FP4_OK;
 }
 
 extern "C" int fp4_quantize(const void* x, fp4_dtype dt, int64_t rows, int64_t cols, int64_t ld,

@@ -103,3 +103,18 @@ def test_library_rounding_equals_the_oracle_bit_for_bit(L):
     for sign in (0, 0x80000000):
         x = (near | np.uint32(sign)).view(np.float32)
         assert np.array_equal(b.fp4_host_round_codes(x), o.q_e2m1(x))
+
+
+def test_library_fp8_rounding_equals_the_oracle_bit_for_bit(L):
+    rng = np.random.default_rng(1)
+    grid = o.e4m3_decode(np.arange(0x7F, dtype=np.uint8)).astype(np.float64)
+    mids = ((grid[:-1] + grid[1:]) / 2).astype(np.float32)
+    edge = np.concatenate([grid.astype(np.float32), mids, np.nextafter(mids, np.float32(np.inf)),
+                           np.nextafter(mids, np.float32(-np.inf)),
+                           np.array([0.0, -0.0, 448, 449, 464, 480, 1e9, 1e-45, 2.0 ** -10, 2.0 ** -9 * 7.5], np.float32)])
+    edge = np.concatenate([edge, -edge])
+    assert np.array_equal(b.fp8_host_round_codes(edge), o.q_e4m3(edge))
+    for x in (rng.uniform(-460, 460, 2_000_000), rng.normal(size=2_000_000) * 0.02,
+              np.exp(rng.uniform(-25, 8, 2_000_000)) * rng.choice([-1, 1], 2_000_000)):
+        x = x.astype(np.float32)
+        assert np.array_equal(b.fp8_host_round_codes(x), o.q_e4m3(x))
