@@ -50,19 +50,27 @@ def build_layers(cfg, torch, b):
     return layers
 
 
-def run_step(cfg, layers, b, ws, ctx_key="ctx", alpha=None, cached=False):
-    """One pass of the whole path over every layer.  ctx_key picks the saved-state buffers (their
-    capacity and threshold scope go with an operating point); cached = W's quantizations come from
-    the per-layer weight cache (valid between optimizer steps) instead of being redone."""
+def run_step(cfg, layers, b, ws, ctx_key="ctx", alpha=None, cached=False, combined=True):
+    """One pass of the whole path over every layer: forward, activation gradient, weight gradient.
+    ctx_key picks the saved-state buffers (their capacity and threshold scope go with an operating
+    point); cached = W's quantizations come from the per-layer weight cache (valid between optimizer
+    steps) instead of being redone; combined = both gradients through fp4_linear_bwd (dY read once for
+    its two quantizations) instead of the two separate entry points -- same results bit for bit."""
     alpha = cfg.alpha if alpha is None else alpha
     for L in layers:
+        wq = L["wq"] if cached else None
         if cached:
-            b.fp4_linear_fwd_cached(L["A"], L["W"], L["wq"], alpha, ctx=L[ctx_key], Y=L["Y"], ws=ws)
-            b.fp4_linear_bwd_dgrad_cached(L["dY"], L["wq"], dA=L["dA"], ws=ws)
+            b.fp4_linear_fwd_cached(L["A"], L["W"], wq, alpha, ctx=L[ctx_key], Y=L["Y"], ws=ws)
         else:
             b.fp4_linear_fwd(L["A"], L["W"], alpha, ctx=L[ctx_key], Y=L["Y"], ws=ws)
-            b.fp4_linear_bwd_dgrad(L["dY"], L["W"], dA=L["dA"], ws=ws)
-        b.fp4_linear_bwd_wgrad(L["A"], L["dY"], L["W"], L[ctx_key], cfg.dge_k, cfg.dge_cap, dW=L["dW"], ws=ws)
+        if combined:
+            b.fp4_linear_bwd(L["dY"], L["A"], L["W"], L[ctx_key], cfg.dge_k, cfg.dge_cap, wq=wq, dA=L["dA"], dW=L["dW"], ws=ws)
+        else:
+            if cached:
+                b.fp4_linear_bwd_dgrad_cached(L["dY"], wq, dA=L["dA"], ws=ws)
+            else:
+                b.fp4_linear_bwd_dgrad(L["dY"], L["W"], dA=L["dA"], ws=ws)
+            b.fp4_linear_bwd_wgrad(L["A"], L["dY"], L["W"], L[ctx_key], cfg.dge_k, cfg.dge_cap, dW=L["dW"], ws=ws)
 
 
 def time_steps(fn, torch, steps, warmup=1):
@@ -247,9 +255,26 @@ def operating_points(cfg, layers, b, torch, ws, step_flops, steps=3):
         del R
         for L in layers:
             del L["ctx_tok"]
+    # the mixed-format GEMM of the W4A8 / W8A4 ablations on the first layer's forward shape (8-bit operands
+    # run the matrix cores at the FP8 rate: 5 PFLOP/s published)
+    L0 = layers[0]
+    l = L0["shape"]
+    if l.K % 128 == 0:
+        a8, ga8 = b.fp8_quantize(L0["A"], b.FP4_AXIS_ROW, ws=ws)
+        w4, gw4 = b.fp4_quantize(L0["W"], b.FP4_AXIS_COL, ws=ws)
+        t = _time(lambda: b.fp4_gemm_mixed(a8, b.FP4_FMT_E4M3, ga8, w4, b.FP4_FMT_E2M1, gw4, out_dtype=L0["Y"].dtype), torch,
+                  n=5)
+        fl = 2.0 * l.M * l.K * l.N
+        out["mixed_gemm(W4A8, layer 0 fwd)"] = {"us": t * 1e6, "TFLOP/s": fl / t / 1e12, "frac_of_fp8_mfma_peak": fl / t / 5.0e15}
+        del a8, w4
+        ctx8 = b.FwdCtx(l.M, l.K, l.N, 1.0)
+        t = _time(lambda: b.fp4_linear_fwd_mixed(L0["A"], L0["W"], b.FP4_FMT_E4M3, b.FP4_FMT_E2M1, 1.0, ctx=ctx8, Y=L0["Y"],
+                                                 ws=ws), torch, n=5)
+        out["fwd_mixed(W4A8, layer 0)"] = {"us": t * 1e6, "TFLOP/s": fl / t / 1e12}
     for L in layers:
         L["wq"] = b.fp4_prepare_weights(L["W"], ws=ws)
     leg("cached_W_quantizations", cached=True)
+    leg("separate_dgrad_and_wgrad_calls", combined=False)
     for L in layers:
         del L["wq"]
     run_step(cfg, layers, b, ws)   # leave the default saved state behind

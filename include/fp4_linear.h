@@ -94,7 +94,8 @@ typedef enum {
   FP4_OP_WGRAD = 4,
   FP4_OP_SPMM = 5,     /* (M=P rows of S, K=Q, N)                                        */
   FP4_OP_PREPARE = 6,  /* fp4_prepare_weights (M ignored)                                 */
-  FP4_OP_FWD_MIXED = 7 /* fp4_linear_fwd_mixed                                            */
+  FP4_OP_FWD_MIXED = 7,/* fp4_linear_fwd_mixed                                            */
+  FP4_OP_BWD = 8       /* fp4_linear_bwd                                                  */
 } fp4_op;
 
 /* What the forward pass leaves for the weight-gradient pass (Sec. 3.1 needs the
@@ -227,6 +228,17 @@ int fp4_linear_bwd_wgrad(const void* A, const void* dY, const void* W, fp4_dtype
                          int64_t M, int64_t K, int64_t N, const fp4_fwd_ctx* saved,
                          float dge_k, float dge_cap, float* dW,
                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* Both gradients in one call, bit-identical to fp4_linear_bwd_dgrad followed by
+ * fp4_linear_bwd_wgrad.  The axis rule of Sec. 4.1 makes dY's scales per token in one GEMM and per
+ * output channel in the other; here dY is read once for its row-wise codes and the column maxima
+ * together (bf16 masters, N <= 16384; other cases run the two passes), so the column-wise
+ * quantization that follows needs no absmax pass.  wq: optional cache of W's quantizations (NULL:
+ * W is quantized per input channel here).  M, N multiples of 32, K of 8.
+ * Workspace: fp4_workspace_bytes(FP4_OP_BWD, M, K, N, dt). */
+int fp4_linear_bwd(const void* dY, const void* A, const void* W, const fp4_weight_cache* wq, fp4_dtype dt,
+                   int64_t M, int64_t K, int64_t N, const fp4_fwd_ctx* saved, float dge_k, float dge_cap,
+                   void* dA, float* dW, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- building blocks, exported for parity tests and per-kernel measurement ---- */
 

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libfp4mi.so")
 FP4_F32, FP4_BF16 = 0, 1
 FP4_AXIS_ROW, FP4_AXIS_COL = 0, 1
 FP4_OCC_TENSOR, FP4_OCC_TOKEN = 0, 1
-FP4_OP_QUANTIZE, FP4_OP_OCC, FP4_OP_FWD, FP4_OP_DGRAD, FP4_OP_WGRAD, FP4_OP_SPMM, FP4_OP_PREPARE, FP4_OP_FWD_MIXED = range(8)
+FP4_OP_QUANTIZE, FP4_OP_OCC, FP4_OP_FWD, FP4_OP_DGRAD, FP4_OP_WGRAD, FP4_OP_SPMM, FP4_OP_PREPARE, FP4_OP_FWD_MIXED, FP4_OP_BWD = range(9)
 FP4_FMT_E2M1, FP4_FMT_E4M3 = 0, 1
 
 _lib = None
@@ -75,6 +75,9 @@ def lib() -> C.CDLL:
         L.fp4_linear_bwd_dgrad_cached.argtypes = [vp, C.POINTER(fp4_weight_cache), i32, i64, i64, i64, vp, vp, sz, vp]
         for name in ("fp4_prepare_weights", "fp4_linear_fwd_cached", "fp4_linear_bwd_dgrad_cached"):
             getattr(L, name).restype = i32
+        L.fp4_linear_bwd.argtypes = [vp, vp, vp, C.POINTER(fp4_weight_cache), i32, i64, i64, i64, C.POINTER(fp4_fwd_ctx),
+                                     f32, f32, vp, vp, vp, sz, vp]
+        L.fp4_linear_bwd.restype = i32
         L.fp8_quantize.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, vp, sz, vp]
         L.fp4_gemm_mixed.argtypes = [vp, i32, vp, vp, i32, vp, i64, i64, i64, vp, vp, i32, i64, vp]
         L.fp4_linear_fwd_mixed.argtypes = [vp, vp, i32, i64, i64, i64, i32, i32, f64, vp, C.POINTER(fp4_fwd_ctx), vp, sz, vp]
@@ -366,6 +369,26 @@ def fp4_linear_bwd_wgrad(A: torch.Tensor, dY: torch.Tensor, W: torch.Tensor, ctx
                                       float(dge_k), float(dge_cap), _ptr(dW), _ptr(w), w.numel(), _stream()),
            "fp4_linear_bwd_wgrad")
     return dW
+
+
+def fp4_linear_bwd(dY: torch.Tensor, A: torch.Tensor, W: torch.Tensor, ctx: FwdCtx, dge_k: float = 5.0, dge_cap: float = 3.0,
+                   wq: Optional["WeightCache"] = None, dA: Optional[torch.Tensor] = None, dW: Optional[torch.Tensor] = None,
+                   ws: Optional[Workspace] = None):
+    """Both gradients in one call (dY read once for both of its quantizations).  Returns (dA, dW)."""
+    _dev_check(dY, A, W, dA, dW)
+    M, K = A.shape
+    _, N = W.shape
+    if dY.shape != (M, N) or W.shape != (K, N) or not (A.dtype == dY.dtype == W.dtype):
+        raise ValueError("shape / dtype mismatch")
+    if dA is None:
+        dA = torch.empty((M, K), dtype=dY.dtype, device=dY.device)
+    if dW is None:
+        dW = torch.empty((K, N), dtype=torch.float32, device=dY.device)
+    w = _ws(workspace_bytes(FP4_OP_BWD, M, K, N, _dt(A)), ws)
+    _check(lib().fp4_linear_bwd(_ptr(dY), _ptr(A), _ptr(W), C.byref(wq.c) if wq is not None else None, _dt(A), M, K, N,
+                                C.byref(ctx.c), float(dge_k), float(dge_cap), _ptr(dA), _ptr(dW), _ptr(w), w.numel(),
+                                _stream()), "fp4_linear_bwd")
+    return dA, dW
 
 
 def fp4_gemm(codes_l: torch.Tensor, gamma_l: Optional[torch.Tensor], codes_rt: torch.Tensor,

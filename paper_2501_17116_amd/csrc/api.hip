@@ -26,6 +26,11 @@ int fp4_launch_quantize_cols(const void* x, int bf16, int64_t rows, int64_t cols
 int fp4_launch_occ_rows_token(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, int64_t tail_k,
                               float* thr_out, uint8_t* codes, float* gamma, void* x_clamped, int32_t* tmp_col,
                               float* tmp_val, int32_t* row_cnt, hipStream_t s);
+int64_t fp4_dual_axis_part_elems(int64_t rows, int64_t cols);
+int fp4_launch_quantize_rows_colmax(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, uint8_t* codes,
+                                    float* gamma, uint16_t* part, hipStream_t s);
+int fp4_launch_quantize_cols_known_max(const void* x, int64_t rows, int64_t cols, int64_t ld, const uint16_t* part,
+                                       uint8_t* codes_t, float* gamma, hipStream_t s);
 int fp4_launch_compact_rows(const int32_t* tmp_col, const float* tmp_val, const int32_t* row_cnt, int64_t stride,
                             const int64_t* row_ptr, int64_t rows, int64_t capacity, int32_t* col_idx, float* val,
                             hipStream_t s);
@@ -203,6 +208,11 @@ extern "C" size_t fp4_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, f
     case FP4_OP_WGRAD: carve_wgrad(c, M, K, N); break;
     case FP4_OP_PREPARE: c.take<uint32_t>((size_t)fp4_quantize_cols_scratch_words(K, N)); break;
     case FP4_OP_FWD_MIXED: carve_fwd_mixed(c, M, K, N, dt); break;
+    case FP4_OP_BWD:
+      carve_dgrad(c, M, K, N);
+      carve_wgrad(c, M, K, N);
+      c.take<uint16_t>((size_t)fp4_dual_axis_part_elems(M, N));
+      break;
     case FP4_OP_SPMM: c.take<int32_t>((size_t)fp4_spmm_scratch_words(M + 2, K, N)); break;   // long-row list: at most M rows
     default: return 0;
   }
@@ -558,6 +568,65 @@ extern "C" int fp4_linear_bwd_wgrad(const void* A, const void* dY, const void* W
   }
   return fp4_launch_gemm(w.qAt, w.gAk, w.qdYt, w.gdYn, K, N, M, addend, dW, 0, N, W, bf16, N, saved->gamma_W,
                          dge_k, dge_cap, s);
+}
+
+// Both gradients of a layer in one call: dY is read once for its row-wise codes (activation gradient)
+// and its column maxima (weight gradient) together; everything else as the two separate entry points.
+extern "C" int fp4_linear_bwd(const void* dY, const void* A, const void* W, const fp4_weight_cache* wq, fp4_dtype dt,
+                              int64_t M, int64_t K, int64_t N, const fp4_fwd_ctx* saved, float dge_k, float dge_cap,
+                              void* dA, float* dW, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!dtype_ok(dt)) return FP4_ERR_DTYPE;
+  if (M <= 0 || K <= 0 || N <= 0 || (M % 32) != 0 || (N % 32) != 0 || (K % 8) != 0) return FP4_ERR_SHAPE;
+  if (!dY || !A || !W || !dA || !dW || !saved || !saved->gamma_W) return FP4_ERR_NULL;
+  if (wq && !cache_ok(wq)) return FP4_ERR_ARG;
+  if (dge_k > 0.0f && !(dge_cap > 0.0f)) return FP4_ERR_ARG;
+  if (!aligned16(dY) || !aligned16(A) || !aligned16(W) || !aligned16(dA) || !aligned16(dW)) return FP4_ERR_ARG;
+  if (saved->scope != FP4_OCC_TENSOR && saved->scope != FP4_OCC_TOKEN) return FP4_ERR_DTYPE;
+  if (!workspace || workspace_bytes < fp4_workspace_bytes(FP4_OP_BWD, M, K, N, dt)) return FP4_ERR_WORKSPACE;
+  const bool occ = saved->capacity > 0 && saved->row_ptr && saved->col_idx && saved->val && saved->nnz && saved->thresholds;
+  const int token = occ && saved->scope == FP4_OCC_TOKEN;
+  hipStream_t s = (hipStream_t)stream;
+  const int bf16 = dt == FP4_BF16;
+  Carver c(reinterpret_cast<void*>(align_up((size_t)(uintptr_t)workspace, 256)));
+  DgradWs d = carve_dgrad(c, M, K, N);
+  WgradWs w = carve_wgrad(c, M, K, N);
+  uint16_t* part = c.take<uint16_t>((size_t)fp4_dual_axis_part_elems(M, N));
+  // dY: per token (codes for the activation gradient) and, in the same read, per-block column maxima
+  int rc = fp4_launch_quantize_rows_colmax(dY, bf16, M, N, N, d.qdY, d.gdY, part, s);
+  const bool dual = rc == 0;
+  if (rc == 1) rc = fp4_launch_quantize_rows(dY, bf16, M, N, N, d.qdY, d.gdY, s);
+  if (rc) return rc;
+  // activation gradient
+  const uint8_t* qW = d.qW;
+  const float* gWk = d.gWk;
+  if (wq) { qW = wq->qWk; gWk = wq->gamma_Wk; }
+  else {
+    rc = fp4_launch_quantize_rows(W, bf16, K, N, N, d.qW, d.gWk, s);
+    if (rc) return rc;
+  }
+  rc = fp4_launch_gemm(d.qdY, d.gdY, qW, gWk, M, K, N, nullptr, dA, bf16, K, nullptr, 0, 0, nullptr, 0.0f, 0.0f, s);
+  if (rc) return rc;
+  // weight gradient
+  const int64_t cap = occ ? std::min(saved->capacity, provisioned_entries(M, K)) : 0;
+  if (occ) {
+    rc = fp4_launch_csr_transpose(saved->row_ptr, saved->col_idx, saved->val, saved->nnz, M, K, cap, w.t_ptr, w.t_idx,
+                                  w.t_val, w.u_idx, w.u_val, w.t_scratch, s);
+    if (rc) return rc;
+  }
+  rc = fp4_launch_quantize_cols(A, bf16, M, K, K, occ ? saved->thresholds : nullptr, token, w.qAt, w.gAk, w.amax, s);
+  if (rc) return rc;
+  if (dual) rc = fp4_launch_quantize_cols_known_max(dY, M, N, N, part, w.qdYt, w.gdYn, s);
+  else rc = fp4_launch_quantize_cols(dY, bf16, M, N, N, nullptr, 0, w.qdYt, w.gdYn, w.amax, s);
+  if (rc) return rc;
+  const float* addend = nullptr;
+  if (occ) {
+    rc = fp4_launch_spmm(w.t_ptr, w.t_idx, w.t_val, cap, K, M, dY, bf16, N, dW, w.sp_scratch,
+                         fp4_spmm_long_list_cap(provisioned_entries(M, K)), s);
+    if (rc) return rc;
+    addend = dW;
+  }
+  return fp4_launch_gemm(w.qAt, w.gAk, w.qdYt, w.gdYn, K, N, M, addend, dW, 0, N, W, bf16, N, saved->gamma_W, dge_k,
+                         dge_cap, s);
 }
 
 extern "C" int fp4_residual_spmm(const int64_t* row_ptr, const int32_t* col_idx, const float* val,

@@ -850,6 +850,106 @@ int launch_cols(const ColArgs& a, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Dual-axis pass over a bf16 tensor (Sec. 4.1: the backward pass needs dY scaled per token for the
+// activation gradient and per output channel for the weight gradient): row-wise codes and scales
+// as quantize_rows_kernel, and in the same read the column maxima of every block of DA_ROWS rows,
+// so that the column-wise quantization that follows needs no absmax pass of its own.
+// A workgroup walks DA_ROWS consecutive rows; a thread keeps its NV units of the row in flight
+// one row ahead and the running maxima of its 8 NV columns as packed 16-bit magnitude patterns
+// (for bf16 the magnitude's bit pattern orders like the value: one packed integer max per pair).
+// ------------------------------------------------------------------------------------------
+constexpr int DA_ROWS = 32;
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+FP4_D uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+  union { uint32_t u; u16x2 v; } x, y, r;
+  x.u = a; y.u = b;
+  r.v = __builtin_elementwise_max(x.v, y.v);
+  return r.u;
+}
+
+template <int NV>
+__global__ __launch_bounds__(256) void quantize_rows_colmax_kernel(const uint16_t* __restrict__ x, int64_t rows,
+                                                                   int64_t cols, int64_t ld, uint8_t* __restrict__ codes,
+                                                                   float* __restrict__ gamma, uint16_t* __restrict__ part) {
+  __shared__ float s_max[2][4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t nunits = cols / 8;                 // cols % 8 == 0 (checked by the launcher)
+  const int64_t r0 = (int64_t)blockIdx.x * DA_ROWS;
+  const int nrows = (int)min((int64_t)DA_ROWS, rows - r0);
+  u32x4 cm[NV];
+#pragma unroll
+  for (int u = 0; u < NV; ++u) cm[u] = u32x4{0u, 0u, 0u, 0u};
+  u32x4 buf[2][NV];
+  auto fetch = [&](int r, u32x4 (&dst)[NV]) {
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+      const int64_t unit = (int64_t)u * 256 + tid;
+      dst[u] = u32x4{0u, 0u, 0u, 0u};
+      if (r < nrows && unit < nunits) dst[u] = *reinterpret_cast<const u32x4*>(x + (r0 + r) * ld + unit * 8);
+    }
+  };
+  auto process = [&](int r, const u32x4 (&cur)[NV]) {
+    if (r >= nrows) return;
+    uint32_t am = 0;                               // packed magnitude maxima of this thread's elements
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+      const u32x4 m = u32x4{cur[u].x & 0x7fff7fffu, cur[u].y & 0x7fff7fffu, cur[u].z & 0x7fff7fffu, cur[u].w & 0x7fff7fffu};
+      cm[u] = u32x4{pk_max_u16(cm[u].x, m.x), pk_max_u16(cm[u].y, m.y), pk_max_u16(cm[u].z, m.z), pk_max_u16(cm[u].w, m.w)};
+      am = pk_max_u16(am, pk_max_u16(pk_max_u16(m.x, m.y), pk_max_u16(m.z, m.w)));
+    }
+    float amax = u2f(max(am & 0xffffu, am >> 16) << 16);
+    amax = wave_max(amax);
+    if (lane == 0) s_max[r & 1][wave] = amax;
+    __syncthreads();                               // one barrier per row: the two slots alternate
+    amax = fmaxf(fmaxf(s_max[r & 1][0], s_max[r & 1][1]), fmaxf(s_max[r & 1][2], s_max[r & 1][3]));
+    const float g = absmax_to_gamma(amax);
+    if (tid == 0) gamma[r0 + r] = g;
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+      const int64_t unit = (int64_t)u * 256 + tid;
+      if (unit < nunits) {
+        float v[8];
+        v[0] = u2f(cur[u].x << 16); v[1] = u2f(cur[u].x & 0xffff0000u); v[2] = u2f(cur[u].y << 16); v[3] = u2f(cur[u].y & 0xffff0000u);
+        v[4] = u2f(cur[u].z << 16); v[5] = u2f(cur[u].z & 0xffff0000u); v[6] = u2f(cur[u].w << 16); v[7] = u2f(cur[u].w & 0xffff0000u);
+        *reinterpret_cast<uint32_t*>(codes + (r0 + r) * (cols / 2) + unit * 4) = pack8(v, g);
+      }
+    }
+  };
+  fetch(0, buf[0]);
+  for (int r = 0; r < DA_ROWS; r += 2) {           // two rows per turn: the buffers are indexed statically
+    fetch(r + 1, buf[1]);
+    process(r, buf[0]);
+    fetch(r + 2, buf[0]);
+    process(r + 1, buf[1]);
+  }
+  uint16_t* prow = part + (int64_t)blockIdx.x * cols;
+#pragma unroll
+  for (int u = 0; u < NV; ++u) {
+    const int64_t unit = (int64_t)u * 256 + tid;
+    if (unit < nunits) *reinterpret_cast<u32x4*>(prow + unit * 8) = cm[u];
+  }
+}
+
+// gamma[c] from g rows of packed bf16 magnitude patterns (as the dual-axis pass leaves them)
+__global__ __launch_bounds__(256) void amax16_to_gamma_kernel(const uint16_t* part, int64_t g, float* gamma, int64_t n) {
+  const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (c >= n) return;
+  uint32_t m[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) m[j] = 0;
+  int64_t i = 0;
+  for (; i + 15 < g; i += 16) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) m[j] = max(m[j], (uint32_t)part[(i + j) * n + c]);
+  }
+  for (; i < g; ++i) m[0] = max(m[0], (uint32_t)part[i * n + c]);
+#pragma unroll
+  for (int j = 1; j < 16; ++j) m[0] = max(m[0], m[j]);
+  gamma[c] = absmax_to_gamma(u2f(m[0] << 16));
+}
+
+// ------------------------------------------------------------------------------------------
 // FP8 (E4M3) vector-wise quantization for the mixed-format ablations (Sec. 4.3): same absmax
 // scaling with MAX = 448, one code per byte.  Not on the FP4 hot path: plain two-pass kernels.
 // ------------------------------------------------------------------------------------------
@@ -1033,6 +1133,41 @@ int fp4_launch_occ_rows(const void* x, int bf16, int64_t rows, int64_t cols, int
   a.rows = rows; a.cols = cols; a.ld = ld; a.capacity = capacity;
   const int rc = bf16 ? launch_rows<BF16, true>(a, s) : launch_rows<F32, true>(a, s);
   return rc ? rc : (ordered ? 0 : 1);
+}
+
+// Dual-axis pass (bf16, cols a multiple of 8 and at most 16384, dense rows): returns 1 when the shape
+// is not covered (the caller then runs the two passes separately).  part: [ceil(rows / 32)][cols] uint16.
+int64_t fp4_dual_axis_part_elems(int64_t rows, int64_t cols) { return (rows + DA_ROWS - 1) / DA_ROWS * cols; }
+
+int fp4_launch_quantize_rows_colmax(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, uint8_t* codes,
+                                    float* gamma, uint16_t* part, hipStream_t s) {
+  if (!bf16 || (cols % 8) != 0 || cols > 256 * 8 * 8 || rows == 0 || cols == 0) return 1;
+  const int64_t nunits = cols / 8;
+  const dim3 grid((unsigned)((rows + DA_ROWS - 1) / DA_ROWS)), block(256);
+  const uint16_t* xp = reinterpret_cast<const uint16_t*>(x);
+  if (nunits <= 256 * 2) hipLaunchKernelGGL((quantize_rows_colmax_kernel<2>), grid, block, 0, s, xp, rows, cols, ld, codes, gamma, part);
+  else if (nunits <= 256 * 4) hipLaunchKernelGGL((quantize_rows_colmax_kernel<4>), grid, block, 0, s, xp, rows, cols, ld, codes, gamma, part);
+  else if (nunits <= 256 * 6) hipLaunchKernelGGL((quantize_rows_colmax_kernel<6>), grid, block, 0, s, xp, rows, cols, ld, codes, gamma, part);
+  else hipLaunchKernelGGL((quantize_rows_colmax_kernel<8>), grid, block, 0, s, xp, rows, cols, ld, codes, gamma, part);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
+
+// Column-wise quantization of a bf16 tensor whose column maxima per row block are already known
+// (from the dual-axis pass): scales, then the transposing pass; the tensor is read once.
+int fp4_launch_quantize_cols_known_max(const void* x, int64_t rows, int64_t cols, int64_t ld, const uint16_t* part,
+                                       uint8_t* codes_t, float* gamma, hipStream_t s) {
+  if (rows == 0 || cols == 0) return FP4_OK;
+  ColArgs a = {};
+  a.x = x; a.codes_t = codes_t; a.gamma = gamma;
+  a.rows = rows; a.cols = cols; a.ld = ld;
+  hipLaunchKernelGGL(amax16_to_gamma_kernel, dim3((unsigned)((cols + 255) / 256)), dim3(256), 0, s, part,
+                     (rows + DA_ROWS - 1) / DA_ROWS, gamma, cols);
+  hipLaunchKernelGGL((quantize_cols_kernel<BF16, false>),
+                     dim3((unsigned)((cols + CT_COLS - 1) / CT_COLS), (unsigned)((rows + CT_ROWS - 1) / CT_ROWS)), dim3(256),
+                     0, s, a);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
 }
 
 // Per-token variant of the fused pass: thresholds found per row (thr_out [rows][2]), entries to

@@ -594,6 +594,25 @@ def test_layer_with_per_token_thresholds(name, M, K, N, dtype, alpha):
                  "dW (per-token)")
 
 
+@pytest.mark.parametrize("M,K,N,dtype,alpha", [(288, 544, 1056, "bf16", 0.98), (1120, 1056, 160, "bf16", 0.98),
+                                                (64, 128, 16384, "bf16", 0.97), (256, 512, 512, "f32", 0.99),
+                                                (96, 128, 96, "bf16", 1.0), (2304, 64, 96, "bf16", 0.97)])
+def test_combined_backward_equals_the_two_entry_points(M, K, N, dtype, alpha):
+    """fp4_linear_bwd (dY read once for its row-wise codes and its column maxima) against dgrad + wgrad:
+    bit-identical, with and without the weight cache; fp32 masters take the unfused passes."""
+    A, W, dY = synth.small_case(M, K, N, dtype, seed=M + N)
+    Ad, Wd, dYd = dev(A, dtype), dev(W, dtype), dev(dY, dtype)
+    _, ctx = b.fp4_linear_fwd(Ad, Wd, alpha)
+    dA0 = b.fp4_linear_bwd_dgrad(dYd, Wd)
+    dW0 = b.fp4_linear_bwd_wgrad(Ad, dYd, Wd, ctx, 5.0, 3.0)
+    dA1, dW1 = b.fp4_linear_bwd(dYd, Ad, Wd, ctx, 5.0, 3.0)
+    assert torch.equal(dA0, dA1) and torch.equal(dW0, dW1)
+    wq = b.fp4_prepare_weights(Wd)
+    dA2, dW2 = b.fp4_linear_bwd(dYd, Ad, Wd, ctx, 5.0, 3.0, wq=wq)
+    assert torch.equal(dA0, dA2) and torch.equal(dW0, dW2)
+    assert_close(dW1, o.fp4_linear_bwd_wgrad(A.numpy(), dY.numpy(), W.numpy(), alpha, 5.0, 3.0), "f32", "dW")
+
+
 def test_forward_is_deterministic_and_keeps_guard_bands():
     A, W, _ = synth.small_case(256, 512, 520, "bf16", seed=1)
     Ad, Wd = dev(A, "bf16"), dev(W, "bf16")
