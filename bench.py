@@ -278,6 +278,19 @@ def operating_points(cfg, layers, b, torch, ws, step_flops, steps=3):
     for L in layers:
         del L["wq"]
     run_step(cfg, layers, b, ws)   # leave the default saved state behind
+    # the same step recorded once in a HIP graph and replayed: the entry points only enqueue kernels
+    # on the caller's stream, so the whole step is capturable (tests/test_gpu_graph.py checks the results)
+    try:
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run_step(cfg, layers, b, ws)
+        ms = time_steps(graph.replay, torch, steps)
+        out["step_replayed_from_hip_graph"] = {"ms_per_step": ms, "TFLOP/s": step_flops / (ms * 1e-3) / 1e12}
+        del graph
+    except Exception as e:   # reported, never fatal: the headline does not depend on it
+        out["step_replayed_from_hip_graph"] = {"error": str(e)[:200]}
+    torch.cuda.synchronize()
     return out
 
 
