@@ -34,8 +34,14 @@ constexpr int NLD = BM * 8 / NTHREADS;  // 16-byte chunks per thread, per operan
 constexpr int GROUP_P = 8;       // tile-rows per L2 reuse group
 constexpr int TILE_BYTES = BM * BKB;              // one operand, one stage (rows unpadded)
 constexpr int EPI_LD = QI * 32 + 4;               // floats per row of the epilogue staging tile
-constexpr int EPI_BYTES = NWAVES * 64 * EPI_LD * 4;
-constexpr int SMEM_BYTES = 4 * TILE_BYTES > EPI_BYTES ? 4 * TILE_BYTES : EPI_BYTES;
+constexpr int EPI_ROWS = 32;                      // rows of a wave's tile parked at a time
+constexpr int EPI_BYTES = NWAVES * EPI_ROWS * EPI_LD * 4;
+// Stage b of the operands sits at [b * 2 * TILE_BYTES, +2 * TILE_BYTES): L, then Rt.  The epilogue's
+// staging area lies behind stage 0, over stage 1, so the next tile's stage 0 can be fetched while
+// the epilogue of this one runs.
+constexpr int STAGE_BYTES = 2 * TILE_BYTES;
+constexpr int EPI_BASE = STAGE_BYTES;
+constexpr int SMEM_BYTES = 2 * STAGE_BYTES > EPI_BASE + EPI_BYTES ? 2 * STAGE_BYTES : EPI_BASE + EPI_BYTES;
 static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
 
 // LDS layout of an operand stage: row r occupies bytes [128 r, 128 r + 128); its 16-byte
@@ -76,8 +82,8 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
     const float* __restrict__ gr, const float* addend, void* outp, const void* __restrict__ Wp,
     const float* __restrict__ gamma_w, GemmShape g) {
   __shared__ __attribute__((aligned(16))) uint8_t smem[SMEM_BYTES];
-  uint8_t* const sL = smem;                    // [2][BM * LDS_ROW]
-  uint8_t* const sR = smem + 2 * TILE_BYTES;   // [2][BN * LDS_ROW]
+  uint8_t* const sL = smem;                // stage b of L at sL + b * STAGE_BYTES
+  uint8_t* const sR = smem + TILE_BYTES;   // stage b of Rt at sR + b * STAGE_BYTES
 
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of the
   // tile sequence so that tiles sharing operand rows meet in the same L2.
@@ -97,30 +103,20 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
   const int xcd = (int)(blockIdx.x % 8);
   const int wg_in_xcd = (int)(blockIdx.x / 8), wgs_per_xcd = (int)(gridDim.x / 8);
   const int run_end = min(total, (xcd + 1) * per_xcd);
-  for (int lid = xcd * per_xcd + wg_in_xcd; lid < run_end; lid += wgs_per_xcd) {
-  const int in_group = GROUP_P * g.tiles_q;
-  const int group = lid / in_group;
-  const int first_p = group * GROUP_P;
-  const int gsz = min(g.tiles_p - first_p, GROUP_P);
-  const int tp = first_p + (lid % in_group) % gsz;
-  const int tq = (lid % in_group) / gsz;
+  int lid = xcd * per_xcd + wg_in_xcd;
+  if (lid >= run_end) return;
 
-  const int64_t P0 = (int64_t)tp * BM;
-  const int64_t Q0 = (int64_t)tq * BN;
-
+  // Per-tile state.  The scalars (tile origin, base pointers, buffer descriptors) of the tile whose
+  // operands are being fetched; they move on to the next tile as soon as this tile's main loop is
+  // over, so the epilogue keeps its own copy of the origin.
+  int64_t P0 = 0, Q0 = 0;
+  const uint8_t* tileL = nullptr;
+  const uint8_t* tileR = nullptr;
+  __amdgpu_buffer_rsrc_t rsrcL, rsrcR;
   // Operand staging.  Load instruction j of wave w fills the KiB [(w*NLD + j) * 1024, +1024) of a
   // stage = tile rows 8*(w*NLD+j) .. +7; lane i owns slot i & 7 of row (i >> 3) of that group and
   // therefore fetches logical chunk (i & 7) ^ ((row >> 1) & 7) of its row.
   uint32_t goffL[NLD], goffR[NLD];   // byte offset of this lane's chunk from the tile's first row
-#pragma unroll
-  for (int j = 0; j < NLD; ++j) {
-    const int row = 8 * (wave * NLD + j) + (lane >> 3);
-    const int chunk = (lane & 7) ^ ((row >> 1) & 7);
-    const int64_t rp = min(P0 + row, g.P - 1) - P0;   // rows past the edge re-read the last row
-    const int64_t rq = min(Q0 + row, g.Q - 1) - Q0;
-    goffL[j] = (uint32_t)(rp * g.Kb + chunk * 16);
-    goffR[j] = (uint32_t)(rq * g.Kb + chunk * 16);
-  }
   // tile base pointers are workgroup-uniform; say so, so descriptors and offsets stay scalar
   auto uniform_ptr = [](const uint8_t* p) {
     const uint64_t v = (uint64_t)p;
@@ -128,27 +124,46 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
     const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
     return (const uint8_t*)(((uint64_t)hi << 32) | lo);
   };
-  const uint8_t* const tileL = uniform_ptr(Lp + P0 * g.Kb);
-  const uint8_t* const tileR = uniform_ptr(Rp + Q0 * g.Kb);
+  auto tile_scalars = [&](int id) {
+    const int in_group = GROUP_P * g.tiles_q;
+    const int group = id / in_group;
+    const int first_p = group * GROUP_P;
+    const int gsz = min(g.tiles_p - first_p, GROUP_P);
+    const int tp = first_p + (id % in_group) % gsz;
+    const int tq = (id % in_group) / gsz;
+    P0 = (int64_t)tp * BM;
+    Q0 = (int64_t)tq * BN;
+    tileL = uniform_ptr(Lp + P0 * g.Kb);
+    tileR = uniform_ptr(Rp + Q0 * g.Kb);
+    // buffer descriptors over the tile's rows: loads past the end of the matrix return zero
+    const uint64_t bytesL = (uint64_t)(g.P - P0) * (uint64_t)g.Kb, bytesR = (uint64_t)(g.Q - Q0) * (uint64_t)g.Kb;
+    rsrcL = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(tileL), 0,
+        __builtin_amdgcn_readfirstlane((int)(bytesL > 0xffffffffull ? 0xffffffffu : (uint32_t)bytesL)), 0x00020000);
+    rsrcR = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(tileR), 0,
+        __builtin_amdgcn_readfirstlane((int)(bytesR > 0xffffffffull ? 0xffffffffu : (uint32_t)bytesR)), 0x00020000);
+  };
+  // The per-lane offsets are recomputed where they are needed (after the main loop for the early
+  // fetch of the next tile, and again at the top of that tile) from a copy of the lane id the
+  // optimizer cannot see through: kept alive across the epilogue they would cost registers there.
+  auto tile_offsets = [&]() {
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+      const int row = 8 * (wave * NLD + j) + (ln >> 3);
+      const int chunk = (ln & 7) ^ ((row >> 1) & 7);
+      const int64_t rp = min(P0 + row, g.P - 1) - P0;   // rows past the edge re-read the last row
+      const int64_t rq = min(Q0 + row, g.Q - 1) - Q0;
+      goffL[j] = (uint32_t)(rp * g.Kb + chunk * 16);
+      goffR[j] = (uint32_t)(rq * g.Kb + chunk * 16);
+    }
+  };
   const int lds_lane = (wave * NLD) * 1024 + lane * 16;
-  // buffer descriptors over the tile's rows: loads past the end of the matrix return zero
-  const uint64_t bytesL = (uint64_t)(g.P - P0) * (uint64_t)g.Kb, bytesR = (uint64_t)(g.Q - Q0) * (uint64_t)g.Kb;
-  const __amdgpu_buffer_rsrc_t rsrcL = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint8_t*>(tileL), 0,
-      __builtin_amdgcn_readfirstlane((int)(bytesL > 0xffffffffull ? 0xffffffffu : (uint32_t)bytesL)), 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsrcR = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint8_t*>(tileR), 0,
-      __builtin_amdgcn_readfirstlane((int)(bytesR > 0xffffffffull ? 0xffffffffu : (uint32_t)bytesR)), 0x00020000);
+  const int KT = (int)((g.Kb + BKB - 1) / BKB);
 
   f32x16 acc[QI][4];
-#pragma unroll
-  for (int i = 0; i < QI; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-  const int KT = (int)((g.Kb + BKB - 1) / BKB);
 
   // Fast path: global -> LDS without passing through registers.  Ragged K (K step overhanging
   // the row): through registers, blanking the overhang.
@@ -159,10 +174,10 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
 #pragma unroll
       for (int j = jb; j < je; ++j) {
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rsrcL, (__attribute__((address_space(3))) void*)(sL + buf * TILE_BYTES + (wave * NLD + j) * 1024), 16,
+            rsrcL, (__attribute__((address_space(3))) void*)(sL + buf * STAGE_BYTES + (wave * NLD + j) * 1024), 16,
             goffL[j], kt * BKB, 0, 0);
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            rsrcR, (__attribute__((address_space(3))) void*)(sR + buf * TILE_BYTES + (wave * NLD + j) * 1024), 16,
+            rsrcR, (__attribute__((address_space(3))) void*)(sR + buf * STAGE_BYTES + (wave * NLD + j) * 1024), 16,
             goffR[j], kt * BKB, 0, 0);
       }
     } else {
@@ -177,8 +192,8 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
           a = *reinterpret_cast<const u32x4*>(bL + goffL[j]);
           b = *reinterpret_cast<const u32x4*>(bR + goffR[j]);
         }
-        *reinterpret_cast<u32x4*>(sL + buf * TILE_BYTES + lds_lane + j * 1024) = a;
-        *reinterpret_cast<u32x4*>(sR + buf * TILE_BYTES + lds_lane + j * 1024) = b;
+        *reinterpret_cast<u32x4*>(sL + buf * STAGE_BYTES + lds_lane + j * 1024) = a;
+        *reinterpret_cast<u32x4*>(sR + buf * STAGE_BYTES + lds_lane + j * 1024) = b;
       }
     }
   };
@@ -201,10 +216,10 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
       const int ks = 2 * half + s2;
 #pragma unroll
       for (int j = 0; j < QI; ++j)
-        fr[s2][j] = *reinterpret_cast<const u32x4*>(sR + buf * TILE_BYTES + frag_r[ks] + j * 32 * BKB);
+        fr[s2][j] = *reinterpret_cast<const u32x4*>(sR + buf * STAGE_BYTES + frag_r[ks] + j * 32 * BKB);
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        fl[s2][j] = *reinterpret_cast<const u32x4*>(sL + buf * TILE_BYTES + frag_l[ks] + j * 32 * BKB);
+        fl[s2][j] = *reinterpret_cast<const u32x4*>(sL + buf * STAGE_BYTES + frag_l[ks] + j * 32 * BKB);
     }
   };
   const int one = 0x7f7f7f7f;  // E8M0 127 = 2^0 in every byte: hardware block scale off
@@ -222,10 +237,34 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
       }
   };
 
+  // The first stage of a tile is requested before the epilogue of the tile before it (for the
+  // first tile: here), the second at the top of the tile; only the first has to have landed when
+  // the main loop starts, the second is awaited inside it like every later one.
+  tile_scalars(lid);
+  tile_offsets();
   load_tile(0, 0, 0, NLD);
+  while (true) {
+  const int64_t eP0 = P0, eQ0 = Q0;   // this tile's origin, for its epilogue
+  tile_offsets();
+#pragma unroll
+  for (int i = 0; i < QI; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
   load_tile(min(1, KT - 1), 1, 0, NLD);
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
+  if constexpr (KRAGGED) {
+    __builtin_amdgcn_s_waitcnt(0);
+  } else {
+    // all but the 2 NLD loads just issued: stage 0 and, before it in issue order, whatever the
+    // previous epilogue left in flight
+    constexpr int n = 2 * NLD;
+    static_assert(n < 64, "vmcnt field");
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (n & 15) | ((n >> 4) << 14));
+  }
+  // a bare barrier: the workgroup-wide fence of __syncthreads() would wait for the second stage too
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
   read_frags(0, 0);
 
   // Ping-pong with two k-slices per phase: the two waves of a SIMD (wave w and w + 4) alternate
@@ -271,15 +310,25 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
   if (!second_group) __builtin_amdgcn_s_barrier();
   __syncthreads();   // every wave is done with the operand buffers
 
+  // the next tile's first stage travels while this tile's epilogue runs
+  const int next = lid + wgs_per_xcd;
+  const bool has_next = next < run_end;
+  if (has_next) {
+    tile_scalars(next);
+    tile_offsets();
+    load_tile(0, 0, 0, NLD);
+  }
+
   // ---- epilogue --------------------------------------------------------------------------
-  // Phase A (MFMA layout): scale by 1/gamma_l[p] * 1/gamma_r[q] and park the wave's tile, 64
-  // rows at a time, in its own LDS region.  Phase B (row layout): each lane takes 8
+  // Phase A (MFMA layout): scale by 1/gamma_l[p] * 1/gamma_r[q] and park the wave's tile, 32
+  // rows at a time, in its own LDS region (behind the operands' stage 0, which is being filled).  Phase B (row layout): each lane takes 8
   // consecutive columns of a row, adds the addend, applies the DGE factor, converts and
   // stores 16 / 32 contiguous bytes, 16 lanes per row.
-  float* const stage = reinterpret_cast<float*>(smem) + wave * 64 * EPI_LD;
+  float* const stage = reinterpret_cast<float*>(smem + EPI_BASE) + wave * EPI_ROWS * EPI_LD;
   constexpr int WCOLS = QI * 32;        // columns per wave
   constexpr int LPR = WCOLS / 8;        // lanes per row in phase B (8 columns each)
   constexpr int RPP = 64 / LPR;         // rows per pass
+  static_assert(EPI_ROWS % RPP == 0, "passes per parked block");
   const bool scaled = gl != nullptr;
   float ir[QI][4][4];
   if (scaled) {
@@ -289,7 +338,7 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
       for (int g4 = 0; g4 < 4; ++g4)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int64_t q = min(Q0 + wave_q * WCOLS + qi * 32 + g4 * 8 + lhi * 4 + e, g.Q - 1);
+          const int64_t q = min(eQ0 + wave_q * WCOLS + qi * 32 + g4 * 8 + lhi * 4 + e, g.Q - 1);
           ir[qi][g4][e] = __builtin_amdgcn_rcpf(gr[q]);
         }
   } else {
@@ -301,7 +350,7 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
         for (int e = 0; e < 4; ++e) ir[qi][g4][e] = 1.0f;
   }
   const int bcol = (lane % LPR) * 8;                    // phase B: this lane's 8 columns
-  const int64_t q0 = Q0 + wave_q * WCOLS + bcol;
+  const int64_t q0 = eQ0 + wave_q * WCOLS + bcol;
   const bool q_full = q0 + 7 < g.Q;
   float gw[8];
   const float inv_k = DGE ? 1.0f / g.dge_k : 1.0f;
@@ -310,31 +359,29 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
 #pragma unroll
     for (int e = 0; e < 8; ++e) gw[e] = gamma_w[min(q0 + e, g.Q - 1)];
   }
-#pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    static_for<2>([&](auto pc) {
-      constexpr int pjl = decltype(pc)::value;
-      const int pj = half * 2 + pjl;
-      const int64_t p = min(P0 + wave_p * 128 + pj * 32 + l32, g.P - 1);
+  static_for<4>([&](auto pc) {
+    constexpr int pj = decltype(pc)::value;
+    {
+      const int64_t p = min(eP0 + wave_p * 128 + pj * 32 + l32, g.P - 1);
       float il = 1.0f;
       if (scaled) il = __builtin_amdgcn_rcpf(gl[p]);
       static_for<4 * QI>([&](auto ic) {
         constexpr int qi = decltype(ic)::value / 4, g4 = decltype(ic)::value % 4;
         f32x4 y;
-        const f32x16& a16 = half == 0 ? acc[qi][pjl] : acc[qi][2 + pjl];
+        const f32x16& a16 = acc[qi][pj];
         y.x = a16[g4 * 4 + 0] * il * ir[qi][g4][0];
         y.y = a16[g4 * 4 + 1] * il * ir[qi][g4][1];
         y.z = a16[g4 * 4 + 2] * il * ir[qi][g4][2];
         y.w = a16[g4 * 4 + 3] * il * ir[qi][g4][3];
-        *reinterpret_cast<f32x4*>(stage + (pjl * 32 + l32) * EPI_LD + qi * 32 + g4 * 8 + lhi * 4) = y;
+        *reinterpret_cast<f32x4*>(stage + l32 * EPI_LD + qi * 32 + g4 * 8 + lhi * 4) = y;
       });
-    });
+    }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-#pragma unroll 4
-    for (int pass = 0; pass < 64 / RPP; ++pass) {
+#pragma unroll
+    for (int pass = 0; pass < EPI_ROWS / RPP; ++pass) {
       const int rloc = pass * RPP + lane / LPR;
-      const int64_t p = P0 + wave_p * 128 + half * 64 + rloc;
+      const int64_t p = eP0 + wave_p * 128 + pj * EPI_ROWS + rloc;
       const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + rloc * EPI_LD + bcol);
       const f32x4 v1 = *reinterpret_cast<const f32x4*>(stage + rloc * EPI_LD + bcol + 4);
       float y[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
@@ -401,8 +448,10 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-  }
-  __syncthreads();   // the staging regions overlap the operand stages of the next tile
+  });
+  __syncthreads();   // the staging regions overlap stage 1 of the operands, which the next tile fills first thing
+  if (!has_next) break;
+  lid = next;
   }  // tiles
 }
 

@@ -1,6 +1,7 @@
 // Outlier clamping and compensation (Sec. 3.2): exact per-tensor quantile thresholds by
-// radix selection, canonical CSR of the clamped-away residual, its transpose for the weight
-// gradient, and the sparse x dense high-precision product.
+// radix selection, and the ordering of the clamped-away residual of long rows into canonical
+// CSR.  (The clamp itself is fused into the quantization pass; the transpose for the weight
+// gradient and the sparse x dense product live with the sparse kernels.)
 #include "fp4_common.h"
 
 #include <algorithm>
