@@ -578,7 +578,7 @@ extern "C" int fp4_linear_bwd(const void* dY, const void* A, const void* W, cons
   if (!dtype_ok(dt)) return FP4_ERR_DTYPE;
   if (M <= 0 || K <= 0 || N <= 0 || (M % 32) != 0 || (N % 32) != 0 || (K % 8) != 0) return FP4_ERR_SHAPE;
   if (!dY || !A || !W || !dA || !dW || !saved || !saved->gamma_W) return FP4_ERR_NULL;
-  if (wq && !cache_ok(wq)) return FP4_ERR_ARG;
+  if (wq && !cache_ok(wq)) return wq->qWt && wq->gamma_W && wq->qWk && wq->gamma_Wk ? FP4_ERR_ARG : FP4_ERR_NULL;
   if (dge_k > 0.0f && !(dge_cap > 0.0f)) return FP4_ERR_ARG;
   if (!aligned16(dY) || !aligned16(A) || !aligned16(W) || !aligned16(dA) || !aligned16(dW)) return FP4_ERR_ARG;
   if (saved->scope != FP4_OCC_TENSOR && saved->scope != FP4_OCC_TOKEN) return FP4_ERR_DTYPE;

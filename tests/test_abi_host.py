@@ -45,8 +45,15 @@ def test_status_strings_and_queries(L):
     assert b.occ_capacity(16384, 4096, 0.999) == 2 * o.occ_tail_count(16384 * 4096, 0.999)
     assert b.occ_capacity(4, 4, 1.0) == 0
     assert b.occ_capacity(4, 4, 0.3) == -1
-    for op in range(6):
+    for op in range(9):
         assert b.workspace_bytes(op, 256, 512, 512, b.FP4_F32) > 0
+    # the one-call backward needs at least what either gradient needs alone
+    for dt in (b.FP4_F32, b.FP4_BF16):
+        both = b.workspace_bytes(b.FP4_OP_BWD, 256, 512, 512, dt)
+        assert both >= b.workspace_bytes(b.FP4_OP_DGRAD, 256, 512, 512, dt)
+        assert both >= b.workspace_bytes(b.FP4_OP_WGRAD, 256, 512, 512, dt)
+    assert L.fp4_occ_capacity_token(100, 1000, 0.99) == 100 * 2 * o.occ_tail_count(1000, 0.99) == 2000
+    assert L.fp4_occ_capacity_token(4, 8, 1.0) == 0 and L.fp4_occ_capacity_token(4, 8, 0.2) == -1
     assert b.workspace_bytes(99, 256, 512, 512, b.FP4_F32) == 0
     # forward workspace holds at least both packed operands and the fp32 residual product
     M, K, N = 16384, 4096, 12288
@@ -77,6 +84,65 @@ def test_argument_validation_happens_on_the_host(L):
     assert L.occ_clamp_residual(one, 0, 8, 8, 8, 0.9, one, None, None, None, one, one, one, 0, one, one, big,
                                 None) == -6
     assert L.fp4_dge_apply(one, one, 0, one, 8, 12, 5.0, 3.0, one, None) == -2
+
+
+def test_argument_validation_of_the_wider_entry_points(L):
+    # same rule: every call fails on the host, before anything could be enqueued
+    one = C.c_void_p(16)
+    big = 1 << 40
+    roomy = b.fp4_fwd_ctx(16, 16, 16, 16, 16, 1 << 30, 16, b.FP4_OCC_TENSOR)
+    token = b.fp4_fwd_ctx(16, 16, 16, 16, 16, 1 << 30, 16, b.FP4_OCC_TOKEN)
+    noscope = b.fp4_fwd_ctx(16, 16, 16, 16, 16, 1 << 30, 16, 5)
+    wq = b.fp4_weight_cache(16, 16, 16, 16)
+    holed = b.fp4_weight_cache(16, 16, 0, 16)
+    bwd = lambda dY, wqp, M, N, ctx, cap, ws: L.fp4_linear_bwd(dY, one, one, wqp, 0, M, 64, N, C.byref(ctx), 5.0, cap,
+                                                               one, one, one, ws, None)
+    assert bwd(None, None, 64, 64, roomy, 3.0, big) == -1
+    assert bwd(one, None, 48, 64, roomy, 3.0, big) == -2             # tokens are contracted: M % 32
+    assert bwd(one, None, 64, 48, roomy, 3.0, big) == -2             # output channels are contracted: N % 32
+    assert bwd(one, None, 64, 64, roomy, 0.0, big) == -4             # cap <= 0
+    assert bwd(one, None, 64, 64, roomy, 3.0, 8) == -5
+    assert bwd(one, None, 64, 64, noscope, 3.0, big) == -3
+    assert bwd(one, C.byref(holed), 64, 64, roomy, 3.0, big) == -1
+    assert L.fp4_prepare_weights(one, 0, 48, 64, C.byref(wq), one, big, None) == -2
+    assert L.fp4_prepare_weights(one, 0, 64, 64, C.byref(holed), one, big, None) == -1
+    assert L.fp4_prepare_weights(one, 0, 64, 64, C.byref(wq), one, 8, None) == -5
+    assert L.fp4_linear_fwd_cached(one, one, None, 0, 8, 64, 64, 0.99, one, C.byref(roomy), one, big, None) == -1
+    assert L.fp4_linear_fwd_cached(one, one, C.byref(wq), 0, 8, 48, 64, 0.99, one, C.byref(roomy), one, big, None) == -2
+    assert L.fp4_linear_bwd_dgrad_cached(one, C.byref(wq), 0, 8, 64, 48, one, one, big, None) == -2
+    assert L.fp4_linear_bwd_dgrad_cached(one, None, 0, 8, 64, 64, one, one, big, None) == -1
+    # per-token thresholds: rows have to fit the registers of a workgroup
+    tok = lambda cols, alpha, cap: L.occ_clamp_residual_token(one, 0, 8, cols, cols, alpha, one, None, None, None, one,
+                                                              one, one, cap, one, one, big, None)
+    assert tok(16392, 0.99, big) == -2
+    assert tok(64, 0.9, 0) == -6
+    assert tok(64, 0.7, big) == -4
+    assert L.fp4_linear_fwd(one, one, 0, 8, 16416, 8, 0.99, one, C.byref(token), one, big, None) == -2
+    assert L.fp4_linear_fwd(one, one, 0, 8, 64, 8, 0.99, one, C.byref(noscope), one, big, None) == -3
+    # FP8 quantizer and the mixed-format calls
+    assert L.fp8_quantize(None, 0, 4, 8, 8, 0, one, one, one, big, None) == -1
+    assert L.fp8_quantize(one, 0, 4, 8, 4, 0, one, one, one, big, None) == -2
+    assert L.fp8_quantize(one, 9, 4, 8, 8, 0, one, one, one, big, None) == -3
+    assert L.fp8_quantize(one, 0, 4, 8, 8, 1, one, one, None, 0, None) == -5
+    assert L.fp8_quantize(one, 0, 0, 8, 8, 0, one, one, one, 0, None) == 0
+    mixed = lambda fl, fr, P, Kc: L.fp4_gemm_mixed(one, fl, one, one, fr, one, P, 4, Kc, None, one, 0, 8, None)
+    assert mixed(b.FP4_FMT_E2M1, b.FP4_FMT_E2M1, 4, 128) == -3      # exactly one operand is 8-bit
+    assert mixed(b.FP4_FMT_E4M3, b.FP4_FMT_E4M3, 4, 128) == -3
+    assert mixed(3, b.FP4_FMT_E2M1, 4, 128) == -3
+    assert mixed(b.FP4_FMT_E4M3, b.FP4_FMT_E2M1, 4, 64) == -2       # K % 128
+    assert mixed(b.FP4_FMT_E4M3, b.FP4_FMT_E2M1, 0, 128) == 0
+    fwdm = lambda K, fa, fw, alpha, ws: L.fp4_linear_fwd_mixed(one, one, 0, 8, K, 8, fa, fw, alpha, one,
+                                                               C.byref(roomy), one, ws, None)
+    assert fwdm(128, b.FP4_FMT_E4M3, b.FP4_FMT_E2M1, 0.99, big) == -4   # FP8 activations run without the clamp
+    assert fwdm(64, b.FP4_FMT_E4M3, b.FP4_FMT_E2M1, 1.0, big) == -2
+    assert fwdm(128, b.FP4_FMT_E2M1, b.FP4_FMT_E2M1, 1.0, big) == -3
+    assert fwdm(128, b.FP4_FMT_E4M3, b.FP4_FMT_E2M1, 1.0, 8) == -5
+    # the entry point that allocates nothing refuses what its built-in scratch cannot hold
+    assert L.fp4_quantize_noalloc(None, 0, 4, 8, 8, 0, one, one, None) == -1
+    assert L.fp4_quantize_noalloc(one, 0, 4, 7, 8, 0, one, one, None) == -2
+    assert L.fp4_quantize_noalloc(one, 1, 1 << 20, 16384, 16384, 1, one, one, None) == -8
+    assert L.fp4_quantize_noalloc(one, 0, 0, 8, 8, 0, one, one, None) == 0
+    assert "scratch" in b.status_string(-8) or "limit" in b.status_string(-8)
 
 
 def test_library_rounding_equals_the_oracle_bit_for_bit(L):
