@@ -321,17 +321,18 @@ __global__ __launch_bounds__(1024) void find_long_rows_kernel(const int64_t* row
 }
 
 // The first LD_CAP long rows (outlier channels of the transposed residual: nearly dense) are
-// multiplied as a small dense matrix so that D is streamed once for all of them instead of once
-// per row: a workgroup takes LD_SLICE rows of D x 512 columns x LD_LB long rows, scatters those
+// multiplied as a small dense matrix so that D is streamed once per group of LD_LB of them instead
+// of once per row: a workgroup takes LD_SLICE rows of D x 512 columns x LD_LB long rows, scatters those
 // rows' values for its slice into an LDS table V[slice row][long row] (zero where a row has no
 // entry), and every lane keeps LD_LB x 8 accumulators for its 8 columns while the eight waves
 // split the slice's rows.  Partial sums per slice go to a scratch array and are added in slice
 // order by a second kernel, so the result does not depend on scheduling.
-constexpr int LD_LB = 16;        // long rows per workgroup pass
-constexpr int LD_SLICE = 1024;   // rows of D per workgroup
+constexpr int LD_LB = 8;         // long rows per workgroup pass (64 accumulators a lane: two workgroups share a CU)
+constexpr int LD_SLICE = 512;    // rows of D per workgroup
 constexpr int LD_CAP = 32;       // long rows the dense path takes; the rest go row by row
 constexpr int LD_COLS = 512;     // columns per workgroup (64 lanes x 8)
 constexpr int LD_WAVES = 8;      // waves per workgroup; they split the slice's rows
+constexpr int LD_TABLE = LD_SLICE * LD_LB > LD_WAVES * 2 * LD_COLS ? LD_SLICE * LD_LB : LD_WAVES * 2 * LD_COLS;   // floats
 
 // Main loop and wave reduction of spmm_long_dense_kernel for NL accumulated long rows.
 template <class DT, int NL>
@@ -344,45 +345,71 @@ FP4_D void long_dense_body(float* V, const void* D, int64_t m0, int rows_here, i
   for (int l = 0; l < NL; ++l)
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[l][e] = 0.0f;
-  if (valid > 0) {
-    constexpr int UN = NL <= 4 ? 8 : (NL <= 8 ? 4 : 2);   // rows in flight per wave
+  constexpr int UN = NL <= 4 ? 6 : 4;   // rows in flight per wave
+  auto fma_row = [&](int row, const float (&d)[8]) {
+    const f32x4* vr = reinterpret_cast<const f32x4*>(&V[row * LD_LB]);
+#pragma unroll
+    for (int q = 0; q < NL / 4; ++q) {
+      const f32x4 v4 = vr[q];   // same address in every lane: an LDS broadcast
+      const float v[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[q * 4 + i][e] = fmaf(v[i], d[e], acc[q * 4 + i][e]);
+    }
+  };
+  bool done = false;
+  if constexpr (__is_same(DT, BF16)) {
+    if (valid == 8) {
+      // Whole 16-byte units of bf16: the rows of the next turn are requested before the FMAs of this
+      // one, as raw words (four registers a row), so a wave always has a turn's loads in flight.
+      done = true;
+      const uint16_t* const base = reinterpret_cast<const uint16_t*>(D) + m0 * N + col;
+      u32x4 cur[UN], nxt[UN];
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      auto request = [&](u32x4 (&dst)[UN], int r0) {
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+          const int row = r0 + LD_WAVES * u;   // wave-uniform
+          dst[u] = row < rows_here ? *reinterpret_cast<const u32x4*>(base + (int64_t)row * N) : zero;
+        }
+      };
+      request(cur, wave);
+      for (int r = wave; r < rows_here; r += LD_WAVES * UN) {
+        request(nxt, r + LD_WAVES * UN);
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+          const int row = r + LD_WAVES * u;
+          if (row < rows_here) {
+            const u32x4 w = cur[u];
+            const float d[8] = {u2f(w.x << 16), u2f(w.x & 0xffff0000u), u2f(w.y << 16), u2f(w.y & 0xffff0000u),
+                                u2f(w.z << 16), u2f(w.z & 0xffff0000u), u2f(w.w << 16), u2f(w.w & 0xffff0000u)};
+            fma_row(row, d);
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) cur[u] = nxt[u];
+      }
+    }
+  }
+  if (!done && valid > 0) {
     int r = wave;
     for (; r + LD_WAVES * (UN - 1) < rows_here; r += LD_WAVES * UN) {
       float d[UN][8];
 #pragma unroll
       for (int u = 0; u < UN; ++u) load8g<DT>(D, (m0 + r + LD_WAVES * u) * N + col, valid, d[u]);
 #pragma unroll
-      for (int u = 0; u < UN; ++u) {
-        const f32x4* vr = reinterpret_cast<const f32x4*>(&V[(r + LD_WAVES * u) * LD_LB]);
-#pragma unroll
-        for (int q = 0; q < NL / 4; ++q) {
-          const f32x4 v4 = vr[q];   // same address in every lane: an LDS broadcast
-          const float v[4] = {v4.x, v4.y, v4.z, v4.w};
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[q * 4 + i][e] = fmaf(v[i], d[u][e], acc[q * 4 + i][e]);
-        }
-      }
+      for (int u = 0; u < UN; ++u) fma_row(r + LD_WAVES * u, d[u]);
     }
     for (; r < rows_here; r += LD_WAVES) {
       float d[8];
       load8g<DT>(D, (m0 + r) * N + col, valid, d);
-      const f32x4* vr = reinterpret_cast<const f32x4*>(&V[r * LD_LB]);
-#pragma unroll
-      for (int q = 0; q < NL / 4; ++q) {
-        const f32x4 v4 = vr[q];
-        const float v[4] = {v4.x, v4.y, v4.z, v4.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[q * 4 + i][e] = fmaf(v[i], d[e], acc[q * 4 + i][e]);
-      }
+      fma_row(r, d);
     }
   }
   // add the waves' sums, two long rows at a time, in wave order
-  float* red = V;   // [LD_WAVES][2 rows][512 columns] = the table's 64 KiB
-  static_assert(LD_WAVES * 2 * LD_COLS <= LD_SLICE * LD_LB, "reduction buffer fits the table");
+  float* red = V;   // [LD_WAVES][2 rows][512 columns]
+  static_assert(LD_WAVES * 2 * LD_COLS <= LD_TABLE, "reduction buffer fits the table");
 #pragma unroll
   for (int q = 0; q < NL / 2; ++q) {
     __syncthreads();
@@ -408,11 +435,12 @@ FP4_D void long_dense_body(float* V, const void* D, int64_t m0, int rows_here, i
 }
 
 template <class DT>
-__global__ __launch_bounds__(LD_WAVES * 64) void spmm_long_dense_kernel(const int64_t* row_ptr, const int32_t* col_idx,
+__global__ __launch_bounds__(LD_WAVES * 64, 4) void spmm_long_dense_kernel(const int64_t* row_ptr, const int32_t* col_idx,
                                                               const float* val, int64_t capacity,
                                                               const int32_t* list, const int32_t* count,
                                                               const void* D, int64_t Q, int64_t N, float* part) {
-  __shared__ __attribute__((aligned(16))) float V[LD_SLICE * LD_LB];   // 64 KiB, reused for the wave reduction
+  __shared__ __attribute__((aligned(16))) float V[LD_TABLE];   // 32 KiB, reused for the wave reduction
+  __shared__ int64_t s_lo[LD_LB], s_en[LD_LB];
   const int n_long = min(*count, LD_CAP);
   const int g0 = blockIdx.z * LD_LB;
   if (g0 >= n_long) return;
@@ -421,9 +449,9 @@ __global__ __launch_bounds__(LD_WAVES * 64) void spmm_long_dense_kernel(const in
   const int64_t m0 = (int64_t)blockIdx.y * LD_SLICE;
   const int rows_here = (int)min((int64_t)LD_SLICE, Q - m0);
   for (int i = tid; i < LD_SLICE * LD_LB; i += LD_WAVES * 64) V[i] = 0.0f;
-  __syncthreads();
-  for (int l = wave; l < nl; l += LD_WAVES) {
-    const int64_t row = list[g0 + l];
+  // where each long row's entries for this slice begin: one lane per long row searches
+  if (tid < nl) {
+    const int64_t row = list[g0 + tid];
     int64_t lo = row_ptr[row];
     const int64_t en = min(row_ptr[row + 1], capacity);
     int64_t hi = en;
@@ -431,17 +459,37 @@ __global__ __launch_bounds__(LD_WAVES * 64) void spmm_long_dense_kernel(const in
       const int64_t mid = (lo + hi) >> 1;
       if (col_idx[mid] < m0) lo = mid + 1; else hi = mid;
     }
-    for (int64_t i = lo + lane; i < en; i += 64) {
-      const int64_t c = col_idx[i];
-      if (c >= m0 + rows_here) break;
-      V[(c - m0) * LD_LB + l] = val[i];
+    s_lo[tid] = lo;
+    s_en[tid] = en;
+  }
+  __syncthreads();   // table zeroed, starts known
+  // All threads place the values: item j = (long row j / LD_SLICE, offset j % LD_SLICE from its start).
+  // Columns ascend and are distinct inside a row, so the entries of this slice are among the first
+  // LD_SLICE from the start.  Four items a thread at a time, their loads issued together.
+  const int items = nl * LD_SLICE;
+  const int64_t m_end = m0 + rows_here;
+  for (int j0 = tid; j0 < items; j0 += 4 * LD_WAVES * 64) {
+    int32_t c[4];
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * LD_WAVES * 64;
+      const int l = min(j / LD_SLICE, nl - 1);
+      const int64_t i = s_lo[l] + (j % LD_SLICE);
+      const bool ok = j < items && i < s_en[l];
+      c[u] = ok ? col_idx[i] : 0x7fffffff;
+      v[u] = ok ? val[i] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * LD_WAVES * 64;
+      if (c[u] < m_end) V[(c[u] - m0) * LD_LB + min(j / LD_SLICE, nl - 1)] = v[u];
     }
   }
   __syncthreads();
   float* const pout = part + (int64_t)blockIdx.y * LD_CAP * N + (int64_t)g0 * N;
-  // accumulators only for as many long rows as there are (4, 8 or 16): usually a handful
+  // accumulators only for as many long rows as there are (4 or 8): usually a handful
   if (nl <= 4) long_dense_body<DT, 4>(V, D, m0, rows_here, N, nl, pout);
-  else if (nl <= 8) long_dense_body<DT, 8>(V, D, m0, rows_here, N, nl, pout);
   else long_dense_body<DT, LD_LB>(V, D, m0, rows_here, N, nl, pout);
 }
 
