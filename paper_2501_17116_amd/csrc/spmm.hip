@@ -648,6 +648,25 @@ FP4_D int mb_row_of(const long long* s_rp, long long e) {
   return lo;
 }
 
+// sets, for every entry e of the block's range [b, e_end), bit (row of e) of its column's mask; four
+// column loads a thread in flight
+FP4_D void mb_build_masks(const int32_t* col_idx, const long long* s_rp, long long b, long long e_end, uint32_t* mb_mask) {
+  for (long long i0 = b + threadIdx.x; i0 < e_end; i0 += 4 * MB_THREADS) {
+    int32_t c[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const long long i = i0 + (long long)u * MB_THREADS;
+      c[u] = i < e_end ? col_idx[i] : -1;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (c[u] < 0) continue;
+      const int r = mb_row_of(s_rp, i0 + (long long)u * MB_THREADS);
+      atomicOr(&mb_mask[2 * c[u] + (r >> 5)], 1u << (r & 31));
+    }
+  }
+}
+
 template <int QMAX>   // columns the LDS masks are laid out for (the launcher picks the smallest that fits)
 __global__ __launch_bounds__(MB_THREADS) void csr_mask_count_kernel(const int64_t* row_ptr, const int32_t* col_idx,
                                                              int64_t rows, int64_t Q, int64_t capacity,
@@ -659,10 +678,7 @@ __global__ __launch_bounds__(MB_THREADS) void csr_mask_count_kernel(const int64_
   mb_load_rows(row_ptr, rows, capacity, r0, s_rp);
   __syncthreads();
   const long long b = s_rp[0], e = s_rp[MB_ROWS];
-  for (long long i = b + threadIdx.x; i < e; i += MB_THREADS) {
-    const int r = mb_row_of(s_rp, i);
-    atomicOr(&mb_mask[2 * col_idx[i] + (r >> 5)], 1u << (r & 31));
-  }
+  mb_build_masks(col_idx, s_rp, b, e, mb_mask);
   __syncthreads();
   uint8_t* out = cnt8 + (int64_t)blockIdx.x * Q;
   for (int c = threadIdx.x; c < Q; c += MB_THREADS) out[c] = (uint8_t)(__popc(mb_mask[2 * c]) + __popc(mb_mask[2 * c + 1]));
@@ -717,21 +733,34 @@ __global__ __launch_bounds__(MB_THREADS) void csr_mask_fill_kernel(const int64_t
   mb_load_rows(row_ptr, rows, capacity, r0, s_rp);
   __syncthreads();
   const long long b = s_rp[0], e = s_rp[MB_ROWS];
-  for (long long i = b + threadIdx.x; i < e; i += MB_THREADS) {
-    const int r = mb_row_of(s_rp, i);
-    atomicOr(&mb_mask[2 * col_idx[i] + (r >> 5)], 1u << (r & 31));
-  }
+  mb_build_masks(col_idx, s_rp, b, e, mb_mask);
   __syncthreads();
+  // Placement, four entries a thread at a time: every step of the chain column -> (segment start,
+  // block offset) -> store is a round trip to memory, so the four chains run side by side.
   const uint32_t* exb = ex + (int64_t)blockIdx.x * Q;
-  for (long long i = b + threadIdx.x; i < e; i += MB_THREADS) {
-    const int r = mb_row_of(s_rp, i);
-    const int32_t c = col_idx[i];
-    const uint32_t lo = mb_mask[2 * c], hi = mb_mask[2 * c + 1];
-    const uint32_t below = r < 32 ? __popc(lo & ((1u << r) - 1u)) : __popc(lo) + __popc(hi & ((1u << (r - 32)) - 1u));
-    const int64_t pos = t_ptr[c] + exb[c] + below;
-    if (pos < capacity) {
-      t_idx[pos] = (int32_t)(r0 + r);
-      t_val[pos] = val[i];
+  for (long long i0 = b + threadIdx.x; i0 < e; i0 += 4 * MB_THREADS) {
+    int32_t c[4];
+    float v[4];
+    int64_t pos[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const long long i = i0 + (long long)u * MB_THREADS;
+      c[u] = i < e ? col_idx[i] : -1;
+      v[u] = i < e ? val[i] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) pos[u] = c[u] >= 0 ? t_ptr[c[u]] + exb[c[u]] : capacity;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (c[u] < 0) continue;
+      const int r = mb_row_of(s_rp, i0 + (long long)u * MB_THREADS);
+      const uint32_t lo = mb_mask[2 * c[u]], hi = mb_mask[2 * c[u] + 1];
+      const uint32_t below = r < 32 ? __popc(lo & ((1u << r) - 1u)) : __popc(lo) + __popc(hi & ((1u << (r - 32)) - 1u));
+      const int64_t p = pos[u] + below;
+      if (p < capacity) {
+        t_idx[p] = (int32_t)(r0 + r);
+        t_val[p] = v[u];
+      }
     }
   }
 }
