@@ -542,6 +542,33 @@ def test_layer_forward_backward(name, M, K, N, dtype, alpha):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_layer_with_outlier_tokens(dtype):
+    """Two tokens far larger than the rest: nearly all of their elements are clamped, so their rows of
+    the residual exceed the long-row threshold of the sparse product in the forward pass (the other
+    layer cases only have long rows in the transposed residual of the weight gradient)."""
+    M, K, N, alpha = 96, 4160, 96, 0.97
+    A, W, dY = synth.small_case(M, K, N, dtype, seed=4160)
+    A[5] *= 200.0
+    A[77] *= 300.0
+    A = synth._finish(A, dtype)
+    Ad, Wd, dYd = dev(A, dtype), dev(W, dtype), dev(dY, dtype)
+    Y, ctx = b.fp4_linear_fwd(Ad, Wd, alpha)
+    torch.cuda.synchronize()
+    Yref, st = o.fp4_linear_fwd(A.numpy(), W.numpy(), alpha, "f32")
+    per_row = np.diff(st.csr.row_ptr)
+    assert per_row[5] > 2048 and per_row[77] > 2048 and np.median(per_row) < 2048
+    nnz = int(ctx.nnz.item())
+    assert nnz == st.csr.val.size
+    assert np.array_equal(ctx.row_ptr.cpu().numpy(), st.csr.row_ptr)
+    assert np.array_equal(ctx.col_idx.cpu().numpy()[:nnz], st.csr.col_idx)
+    assert np.array_equal(ctx.val.cpu().numpy()[:nnz].view(np.uint32), st.csr.val.view(np.uint32))
+    assert_close(Y, Yref, dtype, "Y")
+    dA, dW = b.fp4_linear_bwd(dYd, Ad, Wd, ctx, 5.0, 3.0)
+    assert_close(dA, o.fp4_linear_bwd_dgrad(dY.numpy(), W.numpy(), "f32"), dtype, "dA")
+    assert_close(dW, o.fp4_linear_bwd_wgrad(A.numpy(), dY.numpy(), W.numpy(), alpha, 5.0, 3.0), "f32", "dW")
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_cached_weight_quantizations_equal_the_plain_entry_points(dtype):
     """W's two quantizations prepared once: codes and scales bit-exact against the oracle, and forward /
     activation gradient through the cache bit-identical to the entry points that quantize W themselves."""
