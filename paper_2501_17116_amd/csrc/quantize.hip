@@ -336,11 +336,14 @@ FP4_D void select_row_thresholds(Raw8<DT> (&cache)[NV], bool row_ok, int t, int6
 // TOKEN: the thresholds are the row's own order statistics, found here (the row is in registers
 // anyway), so the tensor is read exactly once; a row's entries go to its own run of stride_e slots
 // and the row's entry count to row_cnt (the caller compacts).
-template <class DT, bool OCC, int TPR, int NV, bool TOKEN = false>
+// FULL: cols is a multiple of 8 (every unit is whole or absent), which spares the clamp its
+// per-element bounds tests -- with them the kernel is bound by vector instructions, not by memory.
+template <class DT, bool OCC, int TPR, int NV, bool TOKEN = false, bool FULL = false>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
   constexpr int RPB = 256 / TPR;
   constexpr bool CACHED = NV > 0;
   static_assert(!TOKEN || (OCC && CACHED), "per-token thresholds need the row in registers");
+  static_assert(!FULL || (OCC && CACHED), "the whole-unit variant exists for the fused clamp only");
   __shared__ float s_max[4];
   __shared__ int s_cnt[4];
   __shared__ int s_round[CACHED ? NV : 1][4];
@@ -359,6 +362,11 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
 
   float lo = 0.0f, hi = 0.0f;
   if (OCC && !TOKEN) { lo = a.thr[0]; hi = a.thr[1]; }
+  auto valid_of = [&](int64_t unit) -> int {
+    if (!(row_ok && unit < nunits)) return 0;
+    if constexpr (FULL) return 8;
+    else return (int)min((int64_t)8, a.cols - unit * 8);
+  };
 
   Raw8<DT> cache[CACHED ? NV : 1];
   float amax = 0.0f;
@@ -380,7 +388,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
       const int64_t unit = (int64_t)u * TPR + t;
-      const int valid = (row_ok && unit < nunits) ? (int)min((int64_t)8, a.cols - unit * 8) : 0;
+      const int valid = valid_of(unit);
       load_raw8<DT>(a.x, xoff + unit * 8, valid, cache[u]);   // valid <= 0 reads nothing and yields zeros
     }
     if constexpr (TOKEN) {
@@ -391,20 +399,35 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
       const int64_t unit = (int64_t)u * TPR + t;
-      const int valid = (row_ok && unit < nunits) ? (int)min((int64_t)8, a.cols - unit * 8) : 0;
+      const int valid = valid_of(unit);
       float v[8];
       widen8<DT>(cache[u], v);
       int cu = 0;
+      if constexpr (FULL) {
+        // a unit is whole or absent: clamp and count without looking at valid, then drop an absent
+        // unit's zeros as a whole (they would count as outliers of a one-sided tensor)
+        float um = 0.0f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float x = v[e];
-        if (OCC) {
-          bool out = (x < lo) | (x > hi);
-          cu += (out && e < valid) ? 1 : 0;
-          x = x < lo ? lo : (x > hi ? hi : x);
-          if (e >= valid) x = 0.0f;
+        for (int e = 0; e < 8; ++e) {
+          const float x = v[e];
+          const bool below = x < lo, above = x > hi;
+          cu += (below | above) ? 1 : 0;
+          um = fmaxf(um, fabsf(below ? lo : (above ? hi : x)));
         }
-        amax = fmaxf(amax, fabsf(x));
+        if (valid == 0) { cu = 0; um = 0.0f; }
+        amax = fmaxf(amax, um);
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float x = v[e];
+          if (OCC) {
+            bool out = (x < lo) | (x > hi);
+            cu += (out && e < valid) ? 1 : 0;
+            x = x < lo ? lo : (x > hi ? hi : x);
+            if (e >= valid) x = 0.0f;
+          }
+          amax = fmaxf(amax, fabsf(x));
+        }
       }
       cnt += cu;
       cpk |= (uint32_t)cu << (4 * u);   // 0..8 outliers per unit
@@ -546,6 +569,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
   const bool word_ok = (a.cols % 8) == 0;
   auto finish = [&](int u, float (&v)[8], int valid) {
     if (valid <= 0) return;
+    if constexpr (FULL) valid = 8;   // known at compile time from here on
     const int64_t unit = (int64_t)u * TPR + t;
     if (OCC) {
       if constexpr (CACHED) wr = upos[u];
@@ -558,7 +582,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
         const float x = v[e];
         x0[e] = x;
         const bool below = x < lo, above = x > hi;
-        om |= ((below | above) && e < valid) ? (1u << e) : 0u;
+        om |= ((below | above) && (FULL || e < valid)) ? (1u << e) : 0u;   // finish() is not entered for an absent unit
         v[e] = below ? lo : (above ? hi : x);
       }
       while (om) {
@@ -584,7 +608,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
       const int64_t unit = (int64_t)u * TPR + t;
-      int valid = (row_ok && unit < nunits) ? (int)min((int64_t)8, a.cols - unit * 8) : 0;
+      const int valid = valid_of(unit);
       float v[8];
       widen8<DT>(cache[u], v);
       finish(u, v, valid);
@@ -625,22 +649,27 @@ __global__ __launch_bounds__(256) void occ_count_rows_kernel(const void* x, int6
 template <class DT, bool OCC>
 int launch_rows(const RowArgs& a, hipStream_t s) {
   const int64_t nunits = (a.cols + 7) / 8;
+  const dim3 g4((unsigned)((a.rows + 3) / 4)), g1((unsigned)a.rows), b(256);
+  // the fused clamp has a variant for rows made of whole units
+  auto go = [&](auto tpr, auto nv, dim3 grid) {
+    constexpr int TPR = decltype(tpr)::value, NV = decltype(nv)::value;
+    if constexpr (OCC && NV > 0) {
+      if ((a.cols % 8) == 0) {
+        hipLaunchKernelGGL((quantize_rows_kernel<DT, true, TPR, NV, false, true>), grid, b, 0, s, a);
+        return;
+      }
+    }
+    hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, TPR, NV>), grid, b, 0, s, a);
+  };
+  using std::integral_constant;
   // one wave per row while the row fits 64 lanes x 8 units, else the whole workgroup
-  if (nunits <= 64 * 2) {
-    hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 64, 2>), dim3((unsigned)((a.rows + 3) / 4)), dim3(256), 0, s, a);
-  } else if (nunits <= 64 * 4) {
-    hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 64, 4>), dim3((unsigned)((a.rows + 3) / 4)), dim3(256), 0, s, a);
-  } else if (nunits <= 64 * 8) {
-    hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 64, 8>), dim3((unsigned)((a.rows + 3) / 4)), dim3(256), 0, s, a);
-  } else if (nunits <= 256 * 4) {
-    hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 256, 4>), dim3((unsigned)a.rows), dim3(256), 0, s, a);
-  } else if (nunits <= 256 * 6) {
-    hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 256, 6>), dim3((unsigned)a.rows), dim3(256), 0, s, a);
-  } else if (nunits <= 256 * 8) {
-    hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 256, 8>), dim3((unsigned)a.rows), dim3(256), 0, s, a);
-  } else {
-    hipLaunchKernelGGL((quantize_rows_kernel<DT, OCC, 256, 0>), dim3((unsigned)a.rows), dim3(256), 0, s, a);
-  }
+  if (nunits <= 64 * 2) go(integral_constant<int, 64>{}, integral_constant<int, 2>{}, g4);
+  else if (nunits <= 64 * 4) go(integral_constant<int, 64>{}, integral_constant<int, 4>{}, g4);
+  else if (nunits <= 64 * 8) go(integral_constant<int, 64>{}, integral_constant<int, 8>{}, g4);
+  else if (nunits <= 256 * 4) go(integral_constant<int, 256>{}, integral_constant<int, 4>{}, g1);
+  else if (nunits <= 256 * 6) go(integral_constant<int, 256>{}, integral_constant<int, 6>{}, g1);
+  else if (nunits <= 256 * 8) go(integral_constant<int, 256>{}, integral_constant<int, 8>{}, g1);
+  else go(integral_constant<int, 256>{}, integral_constant<int, 0>{}, g1);
   FP4_CHECK_LAUNCH();
   return FP4_OK;
 }
@@ -650,12 +679,18 @@ template <class DT>
 int launch_rows_token(const RowArgs& a, hipStream_t s) {
   const int64_t nunits = (a.cols + 7) / 8;
   const dim3 g4((unsigned)((a.rows + 3) / 4)), g1((unsigned)a.rows), b(256);
-  if (nunits <= 64 * 2) hipLaunchKernelGGL((quantize_rows_kernel<DT, true, 64, 2, true>), g4, b, 0, s, a);
-  else if (nunits <= 64 * 4) hipLaunchKernelGGL((quantize_rows_kernel<DT, true, 64, 4, true>), g4, b, 0, s, a);
-  else if (nunits <= 64 * 8) hipLaunchKernelGGL((quantize_rows_kernel<DT, true, 64, 8, true>), g4, b, 0, s, a);
-  else if (nunits <= 256 * 4) hipLaunchKernelGGL((quantize_rows_kernel<DT, true, 256, 4, true>), g1, b, 0, s, a);
-  else if (nunits <= 256 * 6) hipLaunchKernelGGL((quantize_rows_kernel<DT, true, 256, 6, true>), g1, b, 0, s, a);
-  else if (nunits <= 256 * 8) hipLaunchKernelGGL((quantize_rows_kernel<DT, true, 256, 8, true>), g1, b, 0, s, a);
+  auto go = [&](auto tpr, auto nv, dim3 grid) {
+    constexpr int TPR = decltype(tpr)::value, NV = decltype(nv)::value;
+    if ((a.cols % 8) == 0) hipLaunchKernelGGL((quantize_rows_kernel<DT, true, TPR, NV, true, true>), grid, b, 0, s, a);
+    else hipLaunchKernelGGL((quantize_rows_kernel<DT, true, TPR, NV, true, false>), grid, b, 0, s, a);
+  };
+  using std::integral_constant;
+  if (nunits <= 64 * 2) go(integral_constant<int, 64>{}, integral_constant<int, 2>{}, g4);
+  else if (nunits <= 64 * 4) go(integral_constant<int, 64>{}, integral_constant<int, 4>{}, g4);
+  else if (nunits <= 64 * 8) go(integral_constant<int, 64>{}, integral_constant<int, 8>{}, g4);
+  else if (nunits <= 256 * 4) go(integral_constant<int, 256>{}, integral_constant<int, 4>{}, g1);
+  else if (nunits <= 256 * 6) go(integral_constant<int, 256>{}, integral_constant<int, 6>{}, g1);
+  else if (nunits <= 256 * 8) go(integral_constant<int, 256>{}, integral_constant<int, 8>{}, g1);
   else return FP4_ERR_SHAPE;
   FP4_CHECK_LAUNCH();
   return FP4_OK;
