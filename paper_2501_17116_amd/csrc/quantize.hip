@@ -416,6 +416,11 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
         }
         if (valid == 0) { cu = 0; um = 0.0f; }
         amax = fmaxf(amax, um);
+        // Pin the unit's count here.  Left alone, the optimizer sinks the counting to where the counts are
+        // first needed (the scan below) and keeps every element's two comparison masks alive until then:
+        // 128 lane masks a thread, parked in vector registers lane by lane and fetched back.
+        asm volatile("" : "+v"(cu));
+        __builtin_amdgcn_sched_barrier(0);
       } else {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -428,6 +433,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
           }
           amax = fmaxf(amax, fabsf(x));
         }
+        if (OCC) asm volatile("" : "+v"(cu));   // as above
       }
       cnt += cu;
       cpk |= (uint32_t)cu << (4 * u);   // 0..8 outliers per unit
