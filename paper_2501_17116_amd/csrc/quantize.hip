@@ -121,6 +121,12 @@ FP4_D void store8(void* base, int64_t off, int valid, const float (&v)[8]) {
   }
 }
 
+// clamp(x, lo, hi) for finite x and lo <= hi as one instruction (the median of the three).  Equal in
+// value to the select form x < lo ? lo : (x > hi ? hi : x); where a threshold is a zero of the other
+// sign than x the sign of the zero may differ, which no code, scale or residual entry depends on.
+// x lies outside [lo, hi] exactly when the result differs from x.
+FP4_D float clamp3(float x, float lo, float hi) { return __builtin_amdgcn_fmed3f(x, lo, hi); }
+
 FP4_D float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
@@ -410,9 +416,9 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const float x = v[e];
-          const bool below = x < lo, above = x > hi;
-          cu += (below | above) ? 1 : 0;
-          um = fmaxf(um, fabsf(below ? lo : (above ? hi : x)));
+          const float c = clamp3(x, lo, hi);
+          cu += c != x ? 1 : 0;
+          um = fmaxf(um, fabsf(c));
         }
         if (valid == 0) { cu = 0; um = 0.0f; }
         amax = fmaxf(amax, um);
@@ -426,10 +432,9 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
         for (int e = 0; e < 8; ++e) {
           float x = v[e];
           if (OCC) {
-            bool out = (x < lo) | (x > hi);
-            cu += (out && e < valid) ? 1 : 0;
-            x = x < lo ? lo : (x > hi ? hi : x);
-            if (e >= valid) x = 0.0f;
+            const float c = clamp3(x, lo, hi);
+            cu += (c != x && e < valid) ? 1 : 0;
+            x = e < valid ? c : 0.0f;
           }
           amax = fmaxf(amax, fabsf(x));
         }
@@ -447,10 +452,9 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
       for (int e = 0; e < 8; ++e) {
         float x = v[e];
         if (OCC) {
-          bool out = (x < lo) | (x > hi);
-          cnt += (out && e < valid) ? 1 : 0;
-          x = x < lo ? lo : (x > hi ? hi : x);
-          if (e >= valid) x = 0.0f;
+          const float c = clamp3(x, lo, hi);
+          cnt += (c != x && e < valid) ? 1 : 0;
+          x = e < valid ? c : 0.0f;
         }
         amax = fmaxf(amax, fabsf(x));
       }
@@ -587,9 +591,9 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
       for (int e = 0; e < 8; ++e) {
         const float x = v[e];
         x0[e] = x;
-        const bool below = x < lo, above = x > hi;
-        om |= ((below | above) && (FULL || e < valid)) ? (1u << e) : 0u;   // finish() is not entered for an absent unit
-        v[e] = below ? lo : (above ? hi : x);
+        const float c = clamp3(x, lo, hi);
+        om |= (c != x && (FULL || e < valid)) ? (1u << e) : 0u;   // finish() is not entered for an absent unit
+        v[e] = c;
       }
       while (om) {
         const int e = __builtin_ctz(om);
@@ -759,7 +763,7 @@ __global__ __launch_bounds__(256) void col_absmax_kernel(ColArgs a) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         float x = v[e];
-        if (CLAMP) x = x < lo ? lo : (x > hi ? hi : x);
+        if (CLAMP) x = clamp3(x, lo, hi);
         m[e] = fmaxf(m[e], fabsf(x));
       }
     }
@@ -842,8 +846,8 @@ __global__ __launch_bounds__(256) void quantize_cols_kernel(ColArgs a) {
     for (int e = 0; e < 8; ++e) {
       float x0 = v0[e], x1 = v1[e];
       if (CLAMP) {
-        x0 = x0 < lo ? lo : (x0 > hi ? hi : x0);
-        x1 = x1 < lo1 ? lo1 : (x1 > hi1 ? hi1 : x1);
+        x0 = clamp3(x0, lo, hi);
+        x1 = clamp3(x1, lo1, hi1);
         if (r >= a.rows || e >= valid) x0 = 0.0f;       // nothing there: code 0, whatever the thresholds
         if (r + 1 >= a.rows || e >= valid) x1 = 0.0f;
       }
