@@ -413,6 +413,12 @@ def main():
             if line.startswith("TRAFFIC_BYTES_PER_LAUNCH="):
                 out["roofline"]["traffic"] = float(line.split("=", 1)[1])
                 out["roofline"]["traffic_source"] = os.path.relpath(tfile, ROOT)
+    mfile = os.path.join(ROOT, "profiles", "fp4_gemm_nt_kernel_%s_mfma_busy.md" % args.workload)
+    if os.path.exists(mfile):   # likewise: share of the kernel's CU-cycles in which the matrix cores were busy
+        for line in open(mfile):
+            if line.startswith("MFMA_BUSY_FRACTION="):
+                out["roofline"]["matrix_core_busy"] = float(line.split("=", 1)[1])
+                out["roofline"]["matrix_core_busy_source"] = os.path.relpath(mfile, ROOT)
     if not args.no_kernel_report:
         out["kernels"] = kernel_report(cfg, layers, b, torch, ws)
         if cfg.alpha < 1.0 and args.alpha is None:
