@@ -976,22 +976,37 @@ __global__ __launch_bounds__(256) void quantize_rows_colmax_kernel(const uint16_
   }
 }
 
-// gamma[c] from g rows of packed bf16 magnitude patterns (as the dual-axis pass leaves them)
-__global__ __launch_bounds__(256) void amax16_to_gamma_kernel(const uint16_t* part, int64_t g, float* gamma, int64_t n) {
-  const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (c >= n) return;
-  uint32_t m[16];
+// gamma[c] from g rows of packed bf16 magnitude patterns (as the dual-axis pass leaves them; n a
+// multiple of 8).  A lane folds a pair of columns (one 4-byte load a row, packed 16-bit maxima), the
+// sixteen waves of a workgroup split the rows and meet in LDS: with one thread per column and all rows
+// the fold ran on a sixth of the chip and took four times as long.
+constexpr int A16_WAVES = 16;
+__global__ __launch_bounds__(A16_WAVES * 64) void amax16_to_gamma_kernel(const uint16_t* part, int64_t g, float* gamma,
+                                                                        int64_t n) {
+  __shared__ uint32_t s_m[A16_WAVES][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t c0 = ((int64_t)blockIdx.x * 64 + lane) * 2;
+  uint32_t m = 0;
+  if (c0 < n) {
+    const uint16_t* const p = part + c0;
+    int64_t i = wave;
+    for (; i + 7 * A16_WAVES < g; i += 8 * A16_WAVES) {   // eight independent loads at a time
+      uint32_t v[8];
 #pragma unroll
-  for (int j = 0; j < 16; ++j) m[j] = 0;
-  int64_t i = 0;
-  for (; i + 15 < g; i += 16) {
+      for (int j = 0; j < 8; ++j) v[j] = *reinterpret_cast<const uint32_t*>(p + (i + j * A16_WAVES) * n);
 #pragma unroll
-    for (int j = 0; j < 16; ++j) m[j] = max(m[j], (uint32_t)part[(i + j) * n + c]);
+      for (int j = 0; j < 8; ++j) m = pk_max_u16(m, v[j]);
+    }
+    for (; i < g; i += A16_WAVES) m = pk_max_u16(m, *reinterpret_cast<const uint32_t*>(p + i * n));
   }
-  for (; i < g; ++i) m[0] = max(m[0], (uint32_t)part[i * n + c]);
+  s_m[wave][lane] = m;
+  __syncthreads();
+  if (wave == 0 && c0 < n) {
 #pragma unroll
-  for (int j = 1; j < 16; ++j) m[0] = max(m[0], m[j]);
-  gamma[c] = absmax_to_gamma(u2f(m[0] << 16));
+    for (int w = 1; w < A16_WAVES; ++w) m = pk_max_u16(m, s_m[w][lane]);
+    gamma[c0] = absmax_to_gamma(u2f(m << 16));
+    gamma[c0 + 1] = absmax_to_gamma(u2f(m & 0xffff0000u));
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1206,7 +1221,7 @@ int fp4_launch_quantize_cols_known_max(const void* x, int64_t rows, int64_t cols
   ColArgs a = {};
   a.x = x; a.codes_t = codes_t; a.gamma = gamma;
   a.rows = rows; a.cols = cols; a.ld = ld;
-  hipLaunchKernelGGL(amax16_to_gamma_kernel, dim3((unsigned)((cols + 255) / 256)), dim3(256), 0, s, part,
+  hipLaunchKernelGGL(amax16_to_gamma_kernel, dim3((unsigned)((cols + 127) / 128)), dim3(A16_WAVES * 64), 0, s, part,
                      (rows + DA_ROWS - 1) / DA_ROWS, gamma, cols);
   hipLaunchKernelGGL((quantize_cols_kernel<BF16, false>),
                      dim3((unsigned)((cols + CT_COLS - 1) / CT_COLS), (unsigned)((rows + CT_ROWS - 1) / CT_ROWS)), dim3(256),
