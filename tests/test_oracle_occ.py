@@ -177,3 +177,19 @@ def test_per_token_reading_keeps_the_order_of_table_1():
             for a, c in ((None, False), (0.999, False), (0.999, True), (0.99, True), (0.97, True))]
     for prev, nxt in zip(rows, rows[1:]):
         assert nxt[0] > prev[0] and nxt[1] < prev[1] and nxt[2] > prev[2], (prev, nxt)
+
+
+def test_fidelity_table_of_the_two_threshold_scopes():
+    """The table the design notes quote (synthetic activations of the benchmark recipes): with the
+    residual added back both readings reconstruct far better than without the clamp, and they differ
+    from each other by a fraction of a dB."""
+    from oracle import fidelity_table
+    for name in ("c3", "c4"):
+        _, table = fidelity_table.rows(name, tokens=128)
+        snr = {(what, alpha, scope): s for what, alpha, scope, _, _, s in table}
+        base = snr[("no clamp", "-", "-")]
+        for alpha in ("0.999", "0.99", "0.97"):
+            t, k = snr[("clamp + residual", alpha, "tensor")], snr[("clamp + residual", alpha, "token")]
+            assert t > base + 5.0 and k > base + 5.0
+            assert abs(t - k) < 1.5
+            assert t > snr[("clamp", alpha, "tensor")] and k > snr[("clamp", alpha, "token")]
