@@ -370,6 +370,75 @@ def linear_fwd_mixed(A: np.ndarray, W: np.ndarray, act_fp8: bool, wgt_fp8: bool,
 
 
 # ----------------------------------------------------------------------------------
+# Granularity ablation (Sec. 4.3 "Granularity"; App. C.2: sf a scalar for tensor-wise
+# quantization): one scale for the whole tensor instead of one per token / channel.
+# ----------------------------------------------------------------------------------
+def quantize_tensor(x: np.ndarray) -> Tuple[np.ndarray, np.float32]:
+    """Tensor-wise absmax quantization: gamma = fl32(6 / max|x|) for the whole tensor (same
+    conventions as absmax_scale), codes[r, c] = Q(fl32(x[r, c] * gamma)).  Returns (codes [R, C],
+    gamma as an fp32 scalar)."""
+    x = np.asarray(x, dtype=F32)
+    amax = np.max(np.abs(x)) if x.size else F32(0.0)
+    gamma = absmax_scale(np.asarray(amax, dtype=F32)).reshape(())
+    return q_e2m1((x * gamma).astype(F32)), F32(gamma)
+
+
+def linear_fwd_granularity(A: np.ndarray, W: np.ndarray, act_tensorwise: bool, wgt_tensorwise: bool,
+                           alpha: float = 1.0, out_dtype: str = "f32") -> np.ndarray:
+    """The forward pass of the granularity ablation: as fp4_linear_fwd, with the scale of the
+    activations and / or of the weights taken over the whole (clamped) tensor.  The clamp and the
+    residual are those of the per-tensor reading, unchanged."""
+    A = np.asarray(A, dtype=F32)
+    W = np.asarray(W, dtype=F32)
+    lo, hi = occ_thresholds(A, alpha)
+    Ac, csr = occ_clamp_residual(A, lo, hi)
+    if act_tensorwise:
+        ca, g = quantize_tensor(Ac)
+        ga = np.full(A.shape[0], g, dtype=F32)
+    else:
+        ca, ga = quantize_rows(Ac)
+    if wgt_tensorwise:
+        cw, g = quantize_tensor(W)
+        cwt, gw = np.ascontiguousarray(cw.T), np.full(W.shape[1], g, dtype=F32)
+    else:
+        cwt, gw = quantize_cols(W)
+    Y = dequant_gemm(ca, ga, cwt, gw)
+    if csr.val.size:
+        Y = Y + csr.to_dense() @ W.astype(np.float64)
+    return round_to_dtype(Y, out_dtype)
+
+
+# ----------------------------------------------------------------------------------
+# The other two 4-bit formats of App. A's format table (E1M2, E3M0): grids only, for the
+# format comparison of Sec. 4.3 on the CPU; no kernel uses them.
+# ----------------------------------------------------------------------------------
+FP4_GRIDS = {
+    "e1m2": np.array([0.0, 0.5, 1.0, 1.5, 2.0, 2.5, 3.0, 3.5], dtype=F32),
+    "e2m1": E2M1_MAGNITUDES,
+    "e3m0": np.array([0.0, 0.25, 0.5, 1.0, 2.0, 4.0, 8.0, 16.0], dtype=F32),
+}
+
+
+def quantize_rows_grid(x: np.ndarray, fmt: str) -> Tuple[np.ndarray, np.ndarray]:
+    """Row-wise absmax quantization to one of the 4-bit grids: gamma = fl32(MAX_fmt / absmax) (Eq. 1
+    with the format's largest magnitude), then the nearest grid value with a midpoint going to its
+    upper neighbour, as the App. A listing does for E2M1.  Returns (grid VALUES [R, C], gamma [R])."""
+    x = np.asarray(x, dtype=F32)
+    mags = FP4_GRIDS[fmt]
+    grid = np.concatenate([-mags[:0:-1], mags]).astype(F32)            # 15 signed values, ascending
+    mids = ((grid[:-1].astype(np.float64) + grid[1:]) / 2).astype(F32)   # exact in fp32
+    amax = np.max(np.abs(x), axis=1) if x.shape[1] else np.zeros(x.shape[0], F32)
+    with np.errstate(divide="ignore", over="ignore", invalid="ignore"):
+        g = (mags[-1] / amax).astype(F32)
+    gamma = np.where(np.isfinite(g) & (amax > 0), g, F32(1.0)).astype(F32)
+    scaled = (x * gamma[:, None]).astype(F32)
+    pos = np.zeros(scaled.shape, dtype=np.int64)
+    for t in mids:
+        pos += ~(scaled < t)
+    return grid[pos] + F32(0.0), gamma
+
+
+# ----------------------------------------------------------------------------------
 # The linear layer: forward, dgrad, wgrad
 # ----------------------------------------------------------------------------------
 class FwdState(NamedTuple):
