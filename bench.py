@@ -271,6 +271,14 @@ def operating_points(cfg, layers, b, torch, ws, step_flops, steps=3):
         t = _time(lambda: b.fp4_linear_fwd_mixed(L0["A"], L0["W"], b.FP4_FMT_E4M3, b.FP4_FMT_E2M1, 1.0, ctx=ctx8, Y=L0["Y"],
                                                  ws=ws), torch, n=5)
         out["fwd_mixed(W4A8, layer 0)"] = {"us": t * 1e6, "TFLOP/s": fl / t / 1e12}
+    # the granularity ablation's forward pass (tensor-wise scales on both operands) beside the vector-wise one
+    L0 = layers[0]
+    l = L0["shape"]
+    fl = 2.0 * l.M * l.K * l.N
+    ctxg = b.FwdCtx(l.M, l.K, l.N, cfg.alpha)
+    t = _time(lambda: b.fp4_linear_fwd_granularity(L0["A"], L0["W"], True, True, cfg.alpha, ctx=ctxg, Y=L0["Y"], ws=ws), torch, n=5)
+    out["fwd_tensorwise_scales(layer 0)"] = {"us": t * 1e6, "TFLOP/s": fl / t / 1e12}
+    del ctxg
     for L in layers:
         L["wq"] = b.fp4_prepare_weights(L["W"], ws=ws)
     leg("cached_W_quantizations", cached=True)

@@ -76,8 +76,10 @@ typedef enum { FP4_F32 = 0, FP4_BF16 = 1 } fp4_dtype;
 typedef enum { FP4_FMT_E2M1 = 0, FP4_FMT_E4M3 = 1 } fp4_format;
 
 typedef enum {
-  FP4_AXIS_ROW = 0, /* one scale per row;    codes [rows x cols/2], cols contiguous       */
-  FP4_AXIS_COL = 1  /* one scale per column; codes TRANSPOSED [cols x rows/2]             */
+  FP4_AXIS_ROW = 0,   /* one scale per row;    codes [rows x cols/2], cols contiguous       */
+  FP4_AXIS_COL = 1,   /* one scale per column; codes TRANSPOSED [cols x rows/2]             */
+  FP4_AXIS_TENSOR = 2 /* one scale for the whole tensor (the coarse granularity of the Sec. 4.3
+                         ablation; App. C.2 with a scalar sf): codes as ROW, gamma [1]        */
 } fp4_axis;
 
 /* Scope of the clamp thresholds of Sec. 3.2 (the paper does not name the axis of the quantile):
@@ -272,6 +274,18 @@ int fp4_gemm_mixed(const uint8_t* codes_l, fp4_format fmt_l, const float* gamma_
 int fp4_linear_fwd_mixed(const void* A, const void* W, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
                          fp4_format act_fmt, fp4_format wgt_fmt, double alpha, void* Y,
                          const fp4_fwd_ctx* saved, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- granularity: tensor-wise scaling (Sec. 4.3 "Granularity") ----
+ * fp4_linear_fwd with the scale of the activations and / or of the weights taken over the whole tensor
+ * instead of per token / per output channel (fp4_quantize offers the same as FP4_AXIS_TENSOR):
+ * gamma_A = 6 / max|A_c| over the clamped activation tensor, gamma_W = 6 / max|W|.  Clamp, residual and
+ * everything else as in fp4_linear_fwd with per-tensor thresholds (a per-token saved->scope together with
+ * act_tensorwise is refused with FP4_ERR_ARG).  saved->gamma_W receives the scales used, N copies of the
+ * scalar when wgt_tensorwise.  Workspace: fp4_workspace_bytes(FP4_OP_FWD, M, K, N, dt).  The backward
+ * passes stay vector-wise. */
+int fp4_linear_fwd_granularity(const void* A, const void* W, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
+                               int act_tensorwise, int wgt_tensorwise, double alpha, void* Y,
+                               const fp4_fwd_ctx* saved, void* workspace, size_t workspace_bytes, void* stream);
 
 /* One 4-bit code per output byte (for inspecting packed tensors). */
 int fp4_unpack(const uint8_t* codes, int64_t rows, int64_t cols, uint8_t* one_per_byte,

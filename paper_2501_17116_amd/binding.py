@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfp4mi.so")
 
 FP4_F32, FP4_BF16 = 0, 1
-FP4_AXIS_ROW, FP4_AXIS_COL = 0, 1
+FP4_AXIS_ROW, FP4_AXIS_COL, FP4_AXIS_TENSOR = 0, 1, 2
 FP4_OCC_TENSOR, FP4_OCC_TOKEN = 0, 1
 FP4_OP_QUANTIZE, FP4_OP_OCC, FP4_OP_FWD, FP4_OP_DGRAD, FP4_OP_WGRAD, FP4_OP_SPMM, FP4_OP_PREPARE, FP4_OP_FWD_MIXED, FP4_OP_BWD = range(9)
 FP4_FMT_E2M1, FP4_FMT_E4M3 = 0, 1
@@ -81,6 +81,9 @@ def lib() -> C.CDLL:
         L.fp8_quantize.argtypes = [vp, i32, i64, i64, i64, i32, vp, vp, vp, sz, vp]
         L.fp4_gemm_mixed.argtypes = [vp, i32, vp, vp, i32, vp, i64, i64, i64, vp, vp, i32, i64, vp]
         L.fp4_linear_fwd_mixed.argtypes = [vp, vp, i32, i64, i64, i64, i32, i32, f64, vp, C.POINTER(fp4_fwd_ctx), vp, sz, vp]
+        L.fp4_linear_fwd_granularity.argtypes = [vp, vp, i32, i64, i64, i64, i32, i32, f64, vp, C.POINTER(fp4_fwd_ctx), vp, sz,
+                                                 vp]
+        L.fp4_linear_fwd_granularity.restype = i32
         L.fp8_host_round_codes.argtypes = [vp, i64, vp]
         for name in ("fp8_quantize", "fp4_gemm_mixed", "fp4_linear_fwd_mixed", "fp8_host_round_codes"):
             getattr(L, name).restype = i32
@@ -210,6 +213,9 @@ def fp4_quantize(x: torch.Tensor, axis: int, ws: Optional[Workspace] = None) -> 
     if axis == FP4_AXIS_ROW:
         codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=x.device)
         gamma = torch.empty(rows, dtype=torch.float32, device=x.device)
+    elif axis == FP4_AXIS_TENSOR:   # one scale for the whole tensor, codes laid out as for ROW
+        codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=x.device)
+        gamma = torch.empty(1, dtype=torch.float32, device=x.device)
     else:
         codes = torch.empty((cols, rows // 2), dtype=torch.uint8, device=x.device)
         gamma = torch.empty(cols, dtype=torch.float32, device=x.device)
@@ -455,6 +461,26 @@ def fp4_linear_fwd_mixed(A: torch.Tensor, W: torch.Tensor, act_fmt: int, wgt_fmt
     w = _ws(workspace_bytes(FP4_OP_FWD_MIXED, M, K, N, _dt(A)), ws)
     _check(lib().fp4_linear_fwd_mixed(_ptr(A), _ptr(W), _dt(A), M, K, N, act_fmt, wgt_fmt, float(alpha), _ptr(Y),
                                       C.byref(ctx.c), _ptr(w), w.numel(), _stream()), "fp4_linear_fwd_mixed")
+    return Y, ctx
+
+
+def fp4_linear_fwd_granularity(A: torch.Tensor, W: torch.Tensor, act_tensorwise: bool, wgt_tensorwise: bool,
+                               alpha: float = 1.0, ctx: Optional[FwdCtx] = None, Y: Optional[torch.Tensor] = None,
+                               ws: Optional[Workspace] = None):
+    """Forward pass with tensor-wise scaling of the activations and / or the weights."""
+    _dev_check(A, W, Y)
+    M, K = A.shape
+    K2, N = W.shape
+    if K2 != K or A.dtype != W.dtype:
+        raise ValueError("A [M,K] and W [K,N] must agree in K and dtype")
+    if ctx is None:
+        ctx = FwdCtx(M, K, N, alpha, A.device)
+    if Y is None:
+        Y = torch.empty((M, N), dtype=A.dtype, device=A.device)
+    w = _ws(workspace_bytes(FP4_OP_FWD, M, K, N, _dt(A)), ws)
+    _check(lib().fp4_linear_fwd_granularity(_ptr(A), _ptr(W), _dt(A), M, K, N, int(bool(act_tensorwise)),
+                                            int(bool(wgt_tensorwise)), float(alpha), _ptr(Y), C.byref(ctx.c), _ptr(w),
+                                            w.numel(), _stream()), "fp4_linear_fwd_granularity")
     return Y, ctx
 
 

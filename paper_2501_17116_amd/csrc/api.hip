@@ -19,7 +19,15 @@ int fp4_launch_occ_count(const void* x, int bf16, int64_t rows, int64_t cols, in
                          int32_t* row_cnt, hipStream_t s);
 int fp4_launch_occ_rows(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, const float* thr,
                         uint8_t* codes, float* gamma, void* x_clamped, int32_t* col_idx, float* val,
-                        int32_t* tmp_col, float* tmp_val, const int64_t* row_ptr, int64_t capacity, hipStream_t s);
+                        int32_t* tmp_col, float* tmp_val, const int64_t* row_ptr, int64_t capacity, const float* gamma_in,
+                        hipStream_t s);
+int64_t fp4_tensor_gamma_scratch_words();
+int fp4_launch_tensor_gamma(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, const float* thr,
+                            uint32_t* scratch, float* scalar, float* bcast, int64_t n, hipStream_t s);
+int fp4_launch_quantize_rows_fixed(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, const float* gamma_in,
+                                   uint8_t* codes, float* gamma, hipStream_t s);
+int fp4_launch_quantize_cols_given_gamma(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
+                                         uint8_t* codes_t, float* gamma, hipStream_t s);
 int fp4_launch_quantize_cols(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
                              const float* clamp_thr, int per_row_thr, uint8_t* codes_t, float* gamma,
                              uint32_t* amax_scratch, hipStream_t s);
@@ -114,7 +122,9 @@ OccTemps carve_occ(Carver& c, int64_t rows, int64_t capacity) {
 
 struct FwdWs {
   uint8_t* qA; float* gA; uint8_t* qWt; uint32_t* amax; OccTemps occ; float* R; int32_t* sp_scratch;
+  uint32_t* tg;   // tensor-wise scaling: partial maxima, then (at word TG_SCALAR) the scale itself
 };
+const int64_t TG_SCALAR = fp4_tensor_gamma_scratch_words() - 32;
 FwdWs carve_fwd(Carver& c, int64_t M, int64_t K, int64_t N, fp4_dtype dt) {
   FwdWs w;
   w.qA = c.take<uint8_t>((size_t)(M * K / 2));
@@ -126,6 +136,7 @@ FwdWs carve_fwd(Carver& c, int64_t M, int64_t K, int64_t N, fp4_dtype dt) {
   w.occ = carve_occ(c, M, provisioned_entries(M, K));
   w.R = dt == FP4_BF16 ? c.take<float>((size_t)(M * N)) : nullptr;
   w.sp_scratch = c.take<int32_t>((size_t)fp4_spmm_scratch_words(fp4_spmm_long_list_cap(provisioned_entries(M, K)), K, N));
+  w.tg = c.take<uint32_t>((size_t)fp4_tensor_gamma_scratch_words());
   return w;
 }
 
@@ -139,6 +150,7 @@ FwdWs carve_fwd_mixed(Carver& c, int64_t M, int64_t K, int64_t N, fp4_dtype dt) 
   w.occ = carve_occ(c, M, provisioned_entries(M, K));
   w.R = dt == FP4_BF16 ? c.take<float>((size_t)(M * N)) : nullptr;
   w.sp_scratch = c.take<int32_t>((size_t)fp4_spmm_scratch_words(fp4_spmm_long_list_cap(provisioned_entries(M, K)), K, N));
+  w.tg = nullptr;
   return w;
 }
 
@@ -201,7 +213,9 @@ extern "C" size_t fp4_workspace_bytes(int op, int64_t M, int64_t K, int64_t N, f
   if (M < 0 || K < 0 || N < 0 || !dtype_ok(dt)) return 0;
   Carver c(nullptr);
   switch (op) {
-    case FP4_OP_QUANTIZE: c.take<uint32_t>((size_t)fp4_quantize_cols_scratch_words(M, K)); break;  // partial column maxima
+    case FP4_OP_QUANTIZE:   // partial column maxima, or the partial maxima of the tensor-wise scale
+      c.take<uint32_t>((size_t)std::max(fp4_quantize_cols_scratch_words(M, K), fp4_tensor_gamma_scratch_words()));
+      break;
     case FP4_OP_OCC: carve_occ(c, M, provisioned_entries(M, K)); break;
     case FP4_OP_FWD: carve_fwd(c, M, K, N, dt); break;
     case FP4_OP_DGRAD: carve_dgrad(c, M, K, N); break;
@@ -293,7 +307,7 @@ extern "C" int occ_clamp_residual(const void* x, fp4_dtype dt, int64_t rows, int
   rc = fp4_launch_scan_rows(t.row_cnt, rows, row_ptr, nnz, s);
   if (rc) return rc;
   rc = fp4_launch_occ_rows(x, dt == FP4_BF16, rows, cols, ld, thresholds, codes, gamma, x_clamped, col_idx, val,
-                           t.tmp_col, t.tmp_val, row_ptr, capacity, s);
+                           t.tmp_col, t.tmp_val, row_ptr, capacity, nullptr, s);
   if (rc == 1) {   // streamed rows: entries unordered in the temporaries
     rc = fp4_launch_order_rows(row_ptr, rows, cols, capacity, t.tmp_col, t.tmp_val, col_idx, val, s);
     if (rc == 1) rc = fp4_launch_csr_gather(t.tmp_col, t.tmp_val, rows, capacity, row_ptr, col_idx, val, s);
@@ -312,8 +326,11 @@ bool cache_ok(const fp4_weight_cache* wq) {
 }
 
 // Forward pass; wq == nullptr: W is quantized here, into the workspace and saved->gamma_W.
+// act_tensor / wgt_tensor: one scale for the whole operand instead of one per token / output channel
+// (granularity ablation); everything else, clamp and residual included, is the same path.
 int fwd_impl(const void* A, const void* W, const fp4_weight_cache* wq, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
-             double alpha, void* Y, const fp4_fwd_ctx* saved, void* workspace, size_t workspace_bytes, void* stream) {
+             double alpha, void* Y, const fp4_fwd_ctx* saved, void* workspace, size_t workspace_bytes, void* stream,
+             bool act_tensor = false, bool wgt_tensor = false) {
   if (!dtype_ok(dt)) return FP4_ERR_DTYPE;
   if (M <= 0 || K <= 0 || N <= 0 || (K % 32) != 0 || (N % 8) != 0) return FP4_ERR_SHAPE;
   if (!(alpha > 0.5) || !(alpha <= 1.0)) return FP4_ERR_ARG;
@@ -322,6 +339,7 @@ int fwd_impl(const void* A, const void* W, const fp4_weight_cache* wq, fp4_dtype
   const bool occ = alpha < 1.0;
   if (saved->scope != FP4_OCC_TENSOR && saved->scope != FP4_OCC_TOKEN) return FP4_ERR_DTYPE;
   const bool token = occ && saved->scope == FP4_OCC_TOKEN;
+  if (token && act_tensor) return FP4_ERR_ARG;      // one scale per tensor goes with the per-tensor clamp
   const int64_t k = tail_count(M * K, alpha);       // per tail of the tensor
   const int64_t k_row = tail_count(K, alpha);       // per tail of a token
   const int64_t need = token ? M * 2 * k_row : 2 * k;
@@ -348,6 +366,10 @@ int fwd_impl(const void* A, const void* W, const fp4_weight_cache* wq, fp4_dtype
       hipLaunchKernelGGL(copy_f32_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, wq->gamma_W, saved->gamma_W, N);
       if (hipGetLastError() != hipSuccess) return FP4_ERR_HIP;
     }
+  } else if (wgt_tensor) {
+    rc = fp4_launch_tensor_gamma(W, bf16, K, N, N, nullptr, w.tg, nullptr, saved->gamma_W, N, s);
+    if (!rc) rc = fp4_launch_quantize_cols_given_gamma(W, bf16, K, N, N, w.qWt, saved->gamma_W, s);
+    if (rc) return rc;
   } else {
     rc = fp4_launch_quantize_cols(W, bf16, K, N, N, nullptr, 0, w.qWt, saved->gamma_W, w.amax, s);
     if (rc) return rc;
@@ -365,8 +387,15 @@ int fwd_impl(const void* A, const void* W, const fp4_weight_cache* wq, fp4_dtype
       if (rc) return rc;
       rc = fp4_launch_scan_rows(w.occ.row_cnt, M, saved->row_ptr, saved->nnz, s);
       if (rc) return rc;
+      const float* g_all = nullptr;   // tensor-wise activations: one scale, from the clamped tensor's absmax
+      if (act_tensor) {
+        rc = fp4_launch_tensor_gamma(A, bf16, M, K, K, saved->thresholds, w.tg, reinterpret_cast<float*>(w.tg + TG_SCALAR),
+                                     nullptr, 0, s);
+        if (rc) return rc;
+        g_all = reinterpret_cast<const float*>(w.tg + TG_SCALAR);
+      }
       rc = fp4_launch_occ_rows(A, bf16, M, K, K, saved->thresholds, w.qA, w.gA, nullptr, saved->col_idx, saved->val,
-                               w.occ.tmp_col, w.occ.tmp_val, saved->row_ptr, cap, s);
+                               w.occ.tmp_col, w.occ.tmp_val, saved->row_ptr, cap, g_all, s);
       if (rc == 1) {   // streamed rows: entries unordered in the temporaries
         rc = fp4_launch_order_rows(saved->row_ptr, M, K, cap, w.occ.tmp_col, w.occ.tmp_val, saved->col_idx, saved->val, s);
         if (rc == 1)
@@ -381,7 +410,13 @@ int fwd_impl(const void* A, const void* W, const fp4_weight_cache* wq, fp4_dtype
     if (rc) return rc;
     addend = R;
   } else {
-    rc = fp4_launch_quantize_rows(A, bf16, M, K, K, w.qA, w.gA, s);
+    if (act_tensor) {
+      float* const g_all = reinterpret_cast<float*>(w.tg + TG_SCALAR);
+      rc = fp4_launch_tensor_gamma(A, bf16, M, K, K, nullptr, w.tg, g_all, nullptr, 0, s);
+      if (!rc) rc = fp4_launch_quantize_rows_fixed(A, bf16, M, K, K, g_all, w.qA, w.gA, s);
+    } else {
+      rc = fp4_launch_quantize_rows(A, bf16, M, K, K, w.qA, w.gA, s);
+    }
     if (rc) return rc;
     if (saved->thresholds || saved->row_ptr || saved->nnz) {
       hipLaunchKernelGGL(init_no_occ_kernel, dim3((unsigned)((M + 1 + 255) / 256)), dim3(256), 0, s,
@@ -466,7 +501,7 @@ extern "C" int fp4_linear_fwd_mixed(const void* A, const void* W, fp4_dtype dt, 
     if (!rc) rc = fp4_launch_scan_rows(w.occ.row_cnt, M, saved->row_ptr, saved->nnz, s);
     if (rc) return rc;
     rc = fp4_launch_occ_rows(A, bf16, M, K, K, saved->thresholds, w.qA, w.gA, nullptr, saved->col_idx, saved->val,
-                             w.occ.tmp_col, w.occ.tmp_val, saved->row_ptr, cap, s);
+                             w.occ.tmp_col, w.occ.tmp_val, saved->row_ptr, cap, nullptr, s);
     if (rc == 1) {
       rc = fp4_launch_order_rows(saved->row_ptr, M, K, cap, w.occ.tmp_col, w.occ.tmp_val, saved->col_idx, saved->val, s);
       if (rc == 1)
@@ -513,6 +548,13 @@ extern "C" int fp4_prepare_weights(const void* W, fp4_dtype dt, int64_t K, int64
   int rc = fp4_launch_quantize_cols(W, bf16, K, N, N, nullptr, 0, wq->qWt, wq->gamma_W, amax, s);   // forward's operand
   if (rc) return rc;
   return fp4_launch_quantize_rows(W, bf16, K, N, N, wq->qWk, wq->gamma_Wk, s);                   // dgrad's operand
+}
+
+extern "C" int fp4_linear_fwd_granularity(const void* A, const void* W, fp4_dtype dt, int64_t M, int64_t K, int64_t N,
+                                          int act_tensorwise, int wgt_tensorwise, double alpha, void* Y,
+                                          const fp4_fwd_ctx* saved, void* workspace, size_t workspace_bytes, void* stream) {
+  return fwd_impl(A, W, nullptr, dt, M, K, N, alpha, Y, saved, workspace, workspace_bytes, stream, act_tensorwise != 0,
+                  wgt_tensorwise != 0);
 }
 
 extern "C" int fp4_linear_bwd_dgrad(const void* dY, const void* W, fp4_dtype dt, int64_t M, int64_t K,

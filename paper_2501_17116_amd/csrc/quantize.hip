@@ -173,6 +173,8 @@ struct RowArgs {
   int32_t* row_cnt;        // [rows] entries the row produced; they start at slot row * stride_e
   int64_t tail_k;          // elements allowed in each tail of a row
   int64_t stride_e;        // entry slots reserved per row (2 tail_k)
+  // tensor-wise scaling (granularity ablation, Sec. 4.3): one scale, computed beforehand, for every row
+  const float* gamma_in;   // null: each row's own absmax scale
 };
 
 // ------------------------------------------------------------------------------------------
@@ -478,7 +480,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(RowArgs a) {
     __syncthreads();
     amax = fmaxf(fmaxf(s_max[0], s_max[1]), fmaxf(s_max[2], s_max[3]));
   }
-  const float gamma = absmax_to_gamma(amax);
+  const float gamma = a.gamma_in ? a.gamma_in[0] : absmax_to_gamma(amax);
   if (row_ok && t == 0 && a.gamma) a.gamma[row] = gamma;
 
   // ---- OCC: where this thread's entries go inside the row's segment of the entry list.
@@ -1153,6 +1155,67 @@ __global__ __launch_bounds__(256) void dge_apply_kernel(const float* G, const vo
 
 }  // namespace
 
+// ------------------------------------------------------------------------------------------
+// Tensor-wise scaling (granularity ablation, Sec. 4.3; App. C.2 with a scalar sf): the absmax of the
+// whole (optionally clamped) tensor, then gamma = 6 / absmax as one scalar, also broadcast into a
+// scale vector so that the GEMM epilogue runs unchanged.  At most TG_PARTS workgroups, each walking
+// rows blockIdx.x, blockIdx.x + gridDim.x, ...; one wave per row at a time.
+// ------------------------------------------------------------------------------------------
+constexpr int TG_PARTS = 1024;
+template <class DT, bool CLAMP>
+__global__ __launch_bounds__(256) void tensor_absmax_kernel(const void* x, int64_t rows, int64_t cols, int64_t ld,
+                                                            const float* thr, uint32_t* part) {
+  __shared__ float s_m[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t nunits = (cols + 7) / 8;
+  float lo = 0.0f, hi = 0.0f;
+  if (CLAMP) { lo = thr[0]; hi = thr[1]; }
+  float m = 0.0f;
+  for (int64_t row = (int64_t)blockIdx.x * 4 + wave; row < rows; row += (int64_t)gridDim.x * 4) {
+    for (int64_t u = lane; u < nunits; u += 64) {
+      const int valid = (int)min((int64_t)8, cols - u * 8);
+      float v[8];
+      load8<DT>(x, row * ld + u * 8, valid, v);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float c = v[e];
+        if (CLAMP) c = clamp3(c, lo, hi);
+        if (e < valid) m = fmaxf(m, fabsf(c));
+      }
+    }
+  }
+  m = wave_max(m);
+  if (lane == 0) s_m[wave] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) part[blockIdx.x] = f2u(fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3])));
+}
+
+// one workgroup: fold the partial maxima, form the scale, write it (scalar) and n copies (vector)
+__global__ __launch_bounds__(1024) void tensor_gamma_kernel(const uint32_t* part, int nparts, float* scalar, float* bcast,
+                                                            int64_t n) {
+  __shared__ uint32_t s_m[16];
+  __shared__ float s_g;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t m = 0;
+  for (int i = threadIdx.x; i < nparts; i += 1024) m = max(m, part[i]);   // non-negative floats order like their patterns
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, o, 64));
+  if (lane == 0) s_m[wave] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t mm = 0;
+    for (int w = 0; w < 16; ++w) mm = max(mm, s_m[w]);
+    const float g = absmax_to_gamma(u2f(mm));
+    s_g = g;
+    if (scalar) scalar[0] = g;
+  }
+  __syncthreads();
+  if (bcast) {
+    const float g = s_g;
+    for (int64_t i = threadIdx.x; i < n; i += 1024) bcast[i] = g;
+  }
+}
+
 // ---- internal launchers used by the layer entry points --------------------------------------
 // words of scratch fp4_launch_quantize_cols needs
 int64_t fp4_quantize_cols_scratch_words(int64_t rows, int64_t cols) { return (rows + CA_ROWS - 1) / CA_ROWS * cols; }
@@ -1162,6 +1225,35 @@ int fp4_launch_quantize_rows(const void* x, int bf16, int64_t rows, int64_t cols
   if (rows == 0 || cols == 0) return FP4_OK;
   RowArgs a = {};
   a.x = x; a.codes = codes; a.gamma = gamma; a.rows = rows; a.cols = cols; a.ld = ld;
+  return bf16 ? launch_rows<BF16, false>(a, s) : launch_rows<F32, false>(a, s);
+}
+
+// words of scratch fp4_launch_tensor_gamma needs
+int64_t fp4_tensor_gamma_scratch_words() { return TG_PARTS + 64; }
+
+// gamma = 6 / max|x| over the whole tensor (x clamped at thr = {lo, hi} first when thr is given), written as
+// a scalar to *scalar (optional) and n times to bcast (optional).  An empty tensor gives gamma = 1.
+int fp4_launch_tensor_gamma(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, const float* thr,
+                            uint32_t* scratch, float* scalar, float* bcast, int64_t n, hipStream_t s) {
+  const int parts = (int)std::max<int64_t>(1, std::min<int64_t>(TG_PARTS, (rows + 3) / 4));
+  auto go = [&](auto dt, auto cl) {
+    hipLaunchKernelGGL((tensor_absmax_kernel<decltype(dt), decltype(cl)::value>), dim3(parts), dim3(256), 0, s, x, rows, cols, ld,
+                       thr, scratch);
+  };
+  if (bf16) { if (thr) go(BF16{}, std::true_type{}); else go(BF16{}, std::false_type{}); }
+  else { if (thr) go(F32{}, std::true_type{}); else go(F32{}, std::false_type{}); }
+  hipLaunchKernelGGL(tensor_gamma_kernel, dim3(1), dim3(1024), 0, s, scratch, parts, scalar, bcast, n);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
+
+// Row-wise pass with one given scale for all rows (gamma_in, a device scalar); gamma (optional)
+// receives a copy per row.
+int fp4_launch_quantize_rows_fixed(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld, const float* gamma_in,
+                                   uint8_t* codes, float* gamma, hipStream_t s) {
+  if (rows == 0 || cols == 0) return FP4_OK;
+  RowArgs a = {};
+  a.x = x; a.codes = codes; a.gamma = gamma; a.rows = rows; a.cols = cols; a.ld = ld; a.gamma_in = gamma_in;
   return bf16 ? launch_rows<BF16, false>(a, s) : launch_rows<F32, false>(a, s);
 }
 
@@ -1182,11 +1274,11 @@ int fp4_launch_occ_count(const void* x, int bf16, int64_t rows, int64_t cols, in
 int fp4_launch_occ_rows(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
                         const float* thr, uint8_t* codes, float* gamma, void* x_clamped,
                         int32_t* col_idx, float* val, int32_t* tmp_col, float* tmp_val,
-                        const int64_t* row_ptr, int64_t capacity, hipStream_t s) {
+                        const int64_t* row_ptr, int64_t capacity, const float* gamma_in, hipStream_t s) {
   if (rows == 0 || cols == 0) return FP4_OK;
   const bool ordered = (cols + 7) / 8 <= 256 * 8;   // the variants launch_rows picks with a register cache
   RowArgs a = {};
-  a.x = x; a.codes = codes; a.gamma = gamma; a.x_clamped = x_clamped; a.thr = thr;
+  a.x = x; a.codes = codes; a.gamma = gamma; a.x_clamped = x_clamped; a.thr = thr; a.gamma_in = gamma_in;
   a.tmp_col = ordered ? col_idx : tmp_col;
   a.tmp_val = ordered ? val : tmp_val;
   a.row_ptr = row_ptr;
@@ -1209,6 +1301,20 @@ int fp4_launch_quantize_rows_colmax(const void* x, int bf16, int64_t rows, int64
   else if (nunits <= 256 * 4) hipLaunchKernelGGL((quantize_rows_colmax_kernel<4>), grid, block, 0, s, xp, rows, cols, ld, codes, gamma, part);
   else if (nunits <= 256 * 6) hipLaunchKernelGGL((quantize_rows_colmax_kernel<6>), grid, block, 0, s, xp, rows, cols, ld, codes, gamma, part);
   else hipLaunchKernelGGL((quantize_rows_colmax_kernel<8>), grid, block, 0, s, xp, rows, cols, ld, codes, gamma, part);
+  FP4_CHECK_LAUNCH();
+  return FP4_OK;
+}
+
+// The transposing column pass alone, with the scales already in gamma[cols] (tensor-wise scaling: all equal).
+int fp4_launch_quantize_cols_given_gamma(const void* x, int bf16, int64_t rows, int64_t cols, int64_t ld,
+                                         uint8_t* codes_t, float* gamma, hipStream_t s) {
+  if (rows == 0 || cols == 0) return FP4_OK;
+  ColArgs a = {};
+  a.x = x; a.codes_t = codes_t; a.gamma = gamma;
+  a.rows = rows; a.cols = cols; a.ld = ld;
+  const dim3 grid((unsigned)((cols + CT_COLS - 1) / CT_COLS), (unsigned)((rows + CT_ROWS - 1) / CT_ROWS));
+  if (bf16) hipLaunchKernelGGL((quantize_cols_kernel<BF16, false>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((quantize_cols_kernel<F32, false>), grid, dim3(256), 0, s, a);
   FP4_CHECK_LAUNCH();
   return FP4_OK;
 }
@@ -1310,9 +1416,9 @@ extern "C" int fp4_quantize(const void* x, fp4_dtype dt, int64_t rows, int64_t c
                             fp4_axis axis, uint8_t* codes, float* gamma, void* workspace,
                             size_t workspace_bytes, void* stream) {
   if (dt != FP4_F32 && dt != FP4_BF16) return FP4_ERR_DTYPE;
-  if (axis != FP4_AXIS_ROW && axis != FP4_AXIS_COL) return FP4_ERR_DTYPE;
+  if (axis != FP4_AXIS_ROW && axis != FP4_AXIS_COL && axis != FP4_AXIS_TENSOR) return FP4_ERR_DTYPE;
   if (rows < 0 || cols < 0 || ld < cols) return FP4_ERR_SHAPE;
-  if (axis == FP4_AXIS_ROW ? (cols & 1) : (rows & 1)) return FP4_ERR_SHAPE;
+  if (axis == FP4_AXIS_COL ? (rows & 1) : (cols & 1)) return FP4_ERR_SHAPE;
   if (rows == 0 || cols == 0) return FP4_OK;
   if (!x || !codes || !gamma) return FP4_ERR_NULL;
   if (!aligned16(x) || !aligned16(codes) || (ld % 8) != 0) return FP4_ERR_ARG;
@@ -1320,6 +1426,12 @@ extern "C" int fp4_quantize(const void* x, fp4_dtype dt, int64_t rows, int64_t c
     return fp4_launch_quantize_rows(x, dt == FP4_BF16, rows, cols, ld, codes, gamma, (hipStream_t)stream);
   const size_t need = fp4_workspace_bytes(FP4_OP_QUANTIZE, rows, cols, 0, dt);
   if (!workspace || workspace_bytes < need) return FP4_ERR_WORKSPACE;
+  if (axis == FP4_AXIS_TENSOR) {
+    const int rc = fp4_launch_tensor_gamma(x, dt == FP4_BF16, rows, cols, ld, nullptr, reinterpret_cast<uint32_t*>(workspace),
+                                           gamma, nullptr, 0, (hipStream_t)stream);
+    if (rc) return rc;
+    return fp4_launch_quantize_rows_fixed(x, dt == FP4_BF16, rows, cols, ld, gamma, codes, nullptr, (hipStream_t)stream);
+  }
   return fp4_launch_quantize_cols(x, dt == FP4_BF16, rows, cols, ld, nullptr, 0, codes, gamma,
                                   reinterpret_cast<uint32_t*>(workspace), (hipStream_t)stream);
 }

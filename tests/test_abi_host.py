@@ -137,6 +137,16 @@ def test_argument_validation_of_the_wider_entry_points(L):
     assert fwdm(64, b.FP4_FMT_E4M3, b.FP4_FMT_E2M1, 1.0, big) == -2
     assert fwdm(128, b.FP4_FMT_E2M1, b.FP4_FMT_E2M1, 1.0, big) == -3
     assert fwdm(128, b.FP4_FMT_E4M3, b.FP4_FMT_E2M1, 1.0, 8) == -5
+    # tensor-wise scaling: an axis of fp4_quantize and a forward pass of its own
+    assert L.fp4_quantize(one, 0, 4, 7, 8, b.FP4_AXIS_TENSOR, one, one, one, 1 << 20, None) == -2     # odd cols
+    assert L.fp4_quantize(one, 0, 4, 8, 8, b.FP4_AXIS_TENSOR, one, one, None, 0, None) == -5          # needs a workspace
+    assert L.fp4_quantize(one, 0, 4, 8, 8, 3, one, one, one, 1 << 20, None) == -3
+    gran = lambda K, a_t, w_t, alpha, ctx, ws: L.fp4_linear_fwd_granularity(one, one, 0, 8, K, 8, a_t, w_t, alpha, one,
+                                                                           C.byref(ctx), one, ws, None)
+    assert gran(48, 1, 0, 0.99, roomy, big) == -2
+    assert gran(64, 1, 0, 0.2, roomy, big) == -4
+    assert gran(64, 1, 0, 0.99, token, big) == -4        # per-token thresholds with one scale per tensor
+    assert gran(64, 1, 1, 0.99, roomy, 8) == -5
     # the entry point that allocates nothing refuses what its built-in scratch cannot hold
     assert L.fp4_quantize_noalloc(None, 0, 4, 8, 8, 0, one, one, None) == -1
     assert L.fp4_quantize_noalloc(one, 0, 4, 7, 8, 0, one, one, None) == -2
