@@ -758,7 +758,27 @@ __global__ __launch_bounds__(256) void col_absmax_kernel(ColArgs a) {
   for (int e = 0; e < 8; ++e) m[e] = 0.0f;
   const int valid = unit < nunits ? (int)min((int64_t)8, a.cols - unit * 8) : 0;
   if (valid > 0) {
-    for (int64_t r = r0 + wave; r < r1; r += 4) {
+    // four rows a wave at a time, their loads (and, with per-row thresholds, those) issued together
+    constexpr int UN = 4;
+    int64_t r = r0 + wave;
+    for (; r + 4 * (UN - 1) < r1; r += 4 * UN) {
+      float v[UN][8], l4[UN], h4[UN];
+#pragma unroll
+      for (int u = 0; u < UN; ++u) {
+        load8<DT>(a.x, (r + 4 * u) * a.ld + unit * 8, valid, v[u]);
+        l4[u] = lo; h4[u] = hi;
+        if (CLAMP && a.thr_stride) { l4[u] = a.thr[(r + 4 * u) * a.thr_stride]; h4[u] = a.thr[(r + 4 * u) * a.thr_stride + 1]; }
+      }
+#pragma unroll
+      for (int u = 0; u < UN; ++u)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float x = v[u][e];
+          if (CLAMP) x = clamp3(x, l4[u], h4[u]);
+          m[e] = fmaxf(m[e], fabsf(x));
+        }
+    }
+    for (; r < r1; r += 4) {
       float v[8];
       load8<DT>(a.x, r * a.ld + unit * 8, valid, v);
       if (CLAMP && a.thr_stride) { lo = a.thr[r * a.thr_stride]; hi = a.thr[r * a.thr_stride + 1]; }
