@@ -16,6 +16,7 @@
 #include "fp4_measure.h"
 
 #include <algorithm>
+#include <type_traits>
 #include <utility>
 
 typedef int i32x8 __attribute__((ext_vector_type(8)));
@@ -320,16 +321,134 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
   }
 
   // ---- epilogue --------------------------------------------------------------------------
-  // Phase A (MFMA layout): scale by 1/gamma_l[p] * 1/gamma_r[q] and park the wave's tile, 32
-  // rows at a time, in its own LDS region (behind the operands' stage 0, which is being filled).  Phase B (row layout): each lane takes 8
-  // consecutive columns of a row, adds the addend, applies the DGE factor, converts and
-  // stores 16 / 32 contiguous bytes, 16 lanes per row.
+  // Phase A (MFMA layout): scale by 1/gamma_l[p] (edge tiles: and by 1/gamma_r[q]) and park the
+  // wave's tile, 32 rows at a time, in its own LDS region (behind the operands' stage 0, which
+  // is being filled).  Phase B (row layout): each lane takes 8 consecutive columns of a row
+  // (interior tiles: scales them by 1/gamma_r[q] here, the same product in the same order),
+  // adds the addend, applies the DGE factor, converts and stores 16 / 32 contiguous bytes.
   float* const stage = reinterpret_cast<float*>(smem + EPI_BASE) + wave * EPI_ROWS * EPI_LD;
   constexpr int WCOLS = QI * 32;        // columns per wave
   constexpr int LPR = WCOLS / 8;        // lanes per row in phase B (8 columns each)
   constexpr int RPP = 64 / LPR;         // rows per pass
   static_assert(EPI_ROWS % RPP == 0, "passes per parked block");
   const bool scaled = gl != nullptr;
+  // Tiles that lie wholly inside the matrix take a branch-free epilogue.  What a wave reads from
+  // memory here (addend, W for the DGE factor) and what it writes count on the same in-order
+  // counter, so a load issued after a store is only usable once that store has completed: pass
+  // by pass (load, add, store) the epilogue is a chain of sixteen memory round trips.  Instead
+  // the scales are fetched up front and each pass's loads are issued a quarter ahead, before the
+  // store of the pass whose registers they take over.
+  constexpr bool FAST_OK = !DGE || W_BF16;
+  constexpr int NP = EPI_ROWS / RPP;   // passes per parked block
+  if (FAST_OK && eP0 + BM <= g.P && eQ0 + BN <= g.Q) {
+    // lane-derived values are rebuilt here from a copy of the lane id the optimizer cannot see
+    // through: computed at kernel entry they would sit in registers across the main loop
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const int el32 = ln & 31, elhi = ln >> 5;
+    const int bcol = (ln % LPR) * 8;
+    const int64_t q0 = eQ0 + wave_q * WCOLS + bcol;
+    const int64_t prow = eP0 + wave_p * 128 + ln / LPR;
+    float il4[4], ir8[8];
+    [[maybe_unused]] float gw[8];
+#pragma unroll
+    for (int pj = 0; pj < 4; ++pj) il4[pj] = scaled ? __builtin_amdgcn_rcpf(gl[eP0 + wave_p * 128 + pj * 32 + el32]) : 1.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ir8[e] = scaled ? __builtin_amdgcn_rcpf(gr[q0 + e]) : 1.0f;
+    const float inv_k = DGE ? 1.0f / g.dge_k : 1.0f;
+    const float pw = inv_k - 1.0f;
+    if constexpr (DGE) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) gw[e] = gamma_w[q0 + e];
+    }
+    {
+      // One body for both cases (two copies of it invite the optimizer to hoist what they share,
+      // the scaling of all four quarters, above the branch between them).  The loads of a pass
+      // are held in one set of registers: as soon as a pass of this quarter has taken its
+      // values, the same pass of the next quarter is requested into them, ahead of this pass's
+      // store.
+      const bool HAS = addend != nullptr;
+      [[maybe_unused]] f32x4 ad[NP][2];
+      [[maybe_unused]] u32x4 wl[NP];
+      auto issue = [&](int pj, int pass) {
+        const int64_t p = prow + pj * EPI_ROWS + pass * RPP;
+        if (HAS) {
+          const float* a = addend + p * g.ldo + q0;
+          ad[pass][0] = *reinterpret_cast<const f32x4*>(a);
+          ad[pass][1] = *reinterpret_cast<const f32x4*>(a + 4);
+        } else {   // defined on every path: an undefined value may be given a register for the whole tile loop
+          ad[pass][0] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+          ad[pass][1] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        }
+        if constexpr (DGE)
+          wl[pass] = *reinterpret_cast<const u32x4*>(reinterpret_cast<const uint16_t*>(Wp) + p * g.ldw + q0);
+      };
+#pragma unroll
+      for (int pass = 0; pass < NP; ++pass) issue(0, pass);
+      __builtin_amdgcn_sched_barrier(0);
+      static_for<4>([&](auto pc) {
+        constexpr int pj = decltype(pc)::value;
+        // the scheduler otherwise scales all four quarters up front, next to the raw accumulators
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<4 * QI>([&](auto ic) {
+          constexpr int qi = decltype(ic)::value / 4, g4 = decltype(ic)::value % 4;
+          const f32x16& a16 = acc[qi][pj];
+          f32x4 y;
+          y.x = a16[g4 * 4 + 0] * il4[pj];
+          y.y = a16[g4 * 4 + 1] * il4[pj];
+          y.z = a16[g4 * 4 + 2] * il4[pj];
+          y.w = a16[g4 * 4 + 3] * il4[pj];
+          *reinterpret_cast<f32x4*>(stage + el32 * EPI_LD + qi * 32 + g4 * 8 + elhi * 4) = y;
+        });
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<NP>([&](auto sc) {
+          constexpr int pass = decltype(sc)::value;
+          const int rloc = pass * RPP + ln / LPR;
+          const int64_t p = prow + pj * EPI_ROWS + pass * RPP;
+          const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + rloc * EPI_LD + bcol);
+          const f32x4 v1 = *reinterpret_cast<const f32x4*>(stage + rloc * EPI_LD + bcol + 4);
+          float y[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+          for (int e = 0; e < 8; ++e) y[e] = __fmul_rn(y[e], ir8[e]);
+          if (HAS) {
+            const f32x4 a0 = ad[pass][0], a1 = ad[pass][1];
+            y[0] += a0.x; y[1] += a0.y; y[2] += a0.z; y[3] += a0.w;
+            y[4] += a1.x; y[5] += a1.y; y[6] += a1.z; y[7] += a1.w;
+          }
+          [[maybe_unused]] float w[8];
+          if constexpr (DGE) {
+            const u32x4 r = wl[pass];
+            w[0] = u2f(r.x << 16); w[1] = u2f(r.x & 0xffff0000u); w[2] = u2f(r.y << 16); w[3] = u2f(r.y & 0xffff0000u);
+            w[4] = u2f(r.z << 16); w[5] = u2f(r.z & 0xffff0000u); w[6] = u2f(r.w << 16); w[7] = u2f(r.w & 0xffff0000u);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          if constexpr (pj + 1 < 4) issue(pj + 1, pass);
+          __builtin_amdgcn_sched_barrier(0);
+          if constexpr (DGE) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] *= dge_factor(w[e], gw[e], pw, inv_k, g.dge_cap);
+          }
+          if constexpr (OUT_BF16) {
+            u32x4 pk;
+            pk.x = pack_bf16x2(y[0], y[1]);
+            pk.y = pack_bf16x2(y[2], y[3]);
+            pk.z = pack_bf16x2(y[4], y[5]);
+            pk.w = pack_bf16x2(y[6], y[7]);
+            *reinterpret_cast<u32x4*>(reinterpret_cast<uint16_t*>(outp) + p * g.ldo + q0) = pk;
+          } else {
+            float* o = reinterpret_cast<float*>(outp) + p * g.ldo + q0;
+            const f32x4 o0 = {y[0], y[1], y[2], y[3]}, o1 = {y[4], y[5], y[6], y[7]};
+            *reinterpret_cast<f32x4*>(o) = o0;
+            *reinterpret_cast<f32x4*>(o + 4) = o1;
+          }
+        });
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+      });
+    }
+  } else {
   float ir[QI][4][4];
   if (scaled) {
 #pragma unroll
@@ -449,6 +568,7 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
   });
+  }  // edge tiles
   __syncthreads();   // the staging regions overlap stage 1 of the operands, which the next tile fills first thing
   if (!has_next) break;
   lid = next;
