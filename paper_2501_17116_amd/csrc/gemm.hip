@@ -332,6 +332,11 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
   constexpr int RPP = 64 / LPR;         // rows per pass
   static_assert(EPI_ROWS % RPP == 0, "passes per parked block");
   const bool scaled = gl != nullptr;
+  // lane-derived values are rebuilt here from a copy of the lane id the optimizer cannot see
+  // through: computed at kernel entry they would sit in registers across the main loop
+  int ln = lane;
+  asm volatile("" : "+v"(ln));
+  const int el32 = ln & 31, elhi = ln >> 5;
   // Tiles that lie wholly inside the matrix take a branch-free epilogue.  What a wave reads from
   // memory here (addend, W for the DGE factor) and what it writes count on the same in-order
   // counter, so a load issued after a store is only usable once that store has completed: pass
@@ -341,11 +346,6 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
   constexpr bool FAST_OK = !DGE || W_BF16;
   constexpr int NP = EPI_ROWS / RPP;   // passes per parked block
   if (FAST_OK && eP0 + BM <= g.P && eQ0 + BN <= g.Q) {
-    // lane-derived values are rebuilt here from a copy of the lane id the optimizer cannot see
-    // through: computed at kernel entry they would sit in registers across the main loop
-    int ln = lane;
-    asm volatile("" : "+v"(ln));
-    const int el32 = ln & 31, elhi = ln >> 5;
     const int bcol = (ln % LPR) * 8;
     const int64_t q0 = eQ0 + wave_q * WCOLS + bcol;
     const int64_t prow = eP0 + wave_p * 128 + ln / LPR;
@@ -457,7 +457,7 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
       for (int g4 = 0; g4 < 4; ++g4)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const int64_t q = min(eQ0 + wave_q * WCOLS + qi * 32 + g4 * 8 + lhi * 4 + e, g.Q - 1);
+          const int64_t q = min(eQ0 + wave_q * WCOLS + qi * 32 + g4 * 8 + elhi * 4 + e, g.Q - 1);
           ir[qi][g4][e] = __builtin_amdgcn_rcpf(gr[q]);
         }
   } else {
@@ -468,7 +468,7 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
 #pragma unroll
         for (int e = 0; e < 4; ++e) ir[qi][g4][e] = 1.0f;
   }
-  const int bcol = (lane % LPR) * 8;                    // phase B: this lane's 8 columns
+  const int bcol = (ln % LPR) * 8;                    // phase B: this ln's 8 columns
   const int64_t q0 = eQ0 + wave_q * WCOLS + bcol;
   const bool q_full = q0 + 7 < g.Q;
   float gw[8];
@@ -481,7 +481,7 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
   static_for<4>([&](auto pc) {
     constexpr int pj = decltype(pc)::value;
     {
-      const int64_t p = min(eP0 + wave_p * 128 + pj * 32 + l32, g.P - 1);
+      const int64_t p = min(eP0 + wave_p * 128 + pj * 32 + el32, g.P - 1);
       float il = 1.0f;
       if (scaled) il = __builtin_amdgcn_rcpf(gl[p]);
       static_for<4 * QI>([&](auto ic) {
@@ -492,14 +492,14 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
         y.y = a16[g4 * 4 + 1] * il * ir[qi][g4][1];
         y.z = a16[g4 * 4 + 2] * il * ir[qi][g4][2];
         y.w = a16[g4 * 4 + 3] * il * ir[qi][g4][3];
-        *reinterpret_cast<f32x4*>(stage + l32 * EPI_LD + qi * 32 + g4 * 8 + lhi * 4) = y;
+        *reinterpret_cast<f32x4*>(stage + el32 * EPI_LD + qi * 32 + g4 * 8 + elhi * 4) = y;
       });
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int pass = 0; pass < EPI_ROWS / RPP; ++pass) {
-      const int rloc = pass * RPP + lane / LPR;
+      const int rloc = pass * RPP + ln / LPR;
       const int64_t p = eP0 + wave_p * 128 + pj * EPI_ROWS + rloc;
       const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + rloc * EPI_LD + bcol);
       const f32x4 v1 = *reinterpret_cast<const f32x4*>(stage + rloc * EPI_LD + bcol + 4);
