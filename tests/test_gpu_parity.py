@@ -196,6 +196,35 @@ def test_gemm_scaled_and_addend(out_dtype):
     assert_close(y2, o.dequant_gemm(ca, ga, cw, gw) + add.numpy().astype(np.float64), out_dtype, "gemm+addend")
 
 
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
+def test_gemm_interior_and_edge_tiles_give_the_same_bits(out_dtype):
+    # The kernel finishes tiles that lie wholly inside the output with a branch-free epilogue and tiles on
+    # the edge with a masked one.  The same problem computed once with ragged edges and once padded (zero
+    # codes, unit scales, zero addend) to whole tiles must agree bit for bit where the two overlap.
+    P, Q, K, PP, QP = 288, 296, 384, 512, 512
+    g = torch.Generator().manual_seed(11)
+    A = torch.randn(P, K, generator=g)
+    W = torch.randn(K, Q, generator=g) * 0.02
+    ca, ga = o.quantize_rows(A.numpy())
+    cw, gw = o.quantize_cols(W.numpy())
+    add = torch.randn(P, Q, generator=g)
+    tdt = torch.bfloat16 if out_dtype == "bf16" else torch.float32
+    pa, pw = o.pack_codes(ca), o.pack_codes(cw)
+    small = b.fp4_gemm(torch.from_numpy(pa).cuda(), torch.from_numpy(ga).cuda(), torch.from_numpy(pw).cuda(),
+                       torch.from_numpy(gw).cuda(), out_dtype=tdt, addend=add.cuda())
+    pa_big = np.zeros((PP, pa.shape[1]), dtype=np.uint8); pa_big[:P] = pa
+    pw_big = np.zeros((QP, pw.shape[1]), dtype=np.uint8); pw_big[:Q] = pw
+    ga_big = np.ones(PP, dtype=np.float32); ga_big[:P] = ga
+    gw_big = np.ones(QP, dtype=np.float32); gw_big[:Q] = gw
+    add_big = torch.zeros(PP, QP); add_big[:P, :Q] = add
+    big = b.fp4_gemm(torch.from_numpy(pa_big).cuda(), torch.from_numpy(ga_big).cuda(), torch.from_numpy(pw_big).cuda(),
+                     torch.from_numpy(gw_big).cuda(), out_dtype=tdt, addend=add_big.cuda())
+    torch.cuda.synchronize()
+    view = torch.int16 if out_dtype == "bf16" else torch.int32
+    assert torch.equal(small.contiguous().view(view), big[:P, :Q].contiguous().view(view))
+    assert_close(big[:P, :Q], o.dequant_gemm(ca, ga, cw, gw) + add.numpy().astype(np.float64), out_dtype, "padded gemm+addend")
+
+
 # ------------------------------------------------------------------------------------------
 # OCC
 # ------------------------------------------------------------------------------------------
