@@ -352,7 +352,8 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
     float il4[4], ir8[8];
     [[maybe_unused]] float gw[8];
 #pragma unroll
-    for (int pj = 0; pj < 4; ++pj) il4[pj] = scaled ? __builtin_amdgcn_rcpf(gl[eP0 + wave_p * 128 + pj * 32 + el32]) : 1.0f;
+    for (int pj = 0; pj < 4; ++pj)
+      il4[pj] = scaled ? __builtin_amdgcn_rcpf(gl[eP0 + wave_p * 128 + pj * 32 + el32]) : 1.0f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) ir8[e] = scaled ? __builtin_amdgcn_rcpf(gr[q0 + e]) : 1.0f;
     const float inv_k = DGE ? 1.0f / g.dge_k : 1.0f;
@@ -420,8 +421,10 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
           [[maybe_unused]] float w[8];
           if constexpr (DGE) {
             const u32x4 r = wl[pass];
-            w[0] = u2f(r.x << 16); w[1] = u2f(r.x & 0xffff0000u); w[2] = u2f(r.y << 16); w[3] = u2f(r.y & 0xffff0000u);
-            w[4] = u2f(r.z << 16); w[5] = u2f(r.z & 0xffff0000u); w[6] = u2f(r.w << 16); w[7] = u2f(r.w & 0xffff0000u);
+            w[0] = u2f(r.x << 16); w[1] = u2f(r.x & 0xffff0000u);
+            w[2] = u2f(r.y << 16); w[3] = u2f(r.y & 0xffff0000u);
+            w[4] = u2f(r.z << 16); w[5] = u2f(r.z & 0xffff0000u);
+            w[6] = u2f(r.w << 16); w[7] = u2f(r.w & 0xffff0000u);
           }
           __builtin_amdgcn_sched_barrier(0);
           if constexpr (pj + 1 < 4) issue(pj + 1, pass);
@@ -449,125 +452,127 @@ __global__ __launch_bounds__(NTHREADS) void fp4_gemm_nt_kernel(
       });
     }
   } else {
-  float ir[QI][4][4];
-  if (scaled) {
+    float ir[QI][4][4];
+    if (scaled) {
 #pragma unroll
-    for (int qi = 0; qi < QI; ++qi)
+      for (int qi = 0; qi < QI; ++qi)
 #pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4)
+        for (int g4 = 0; g4 < 4; ++g4)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int64_t q = min(eQ0 + wave_q * WCOLS + qi * 32 + g4 * 8 + elhi * 4 + e, g.Q - 1);
-          ir[qi][g4][e] = __builtin_amdgcn_rcpf(gr[q]);
-        }
-  } else {
-#pragma unroll
-    for (int qi = 0; qi < QI; ++qi)
-#pragma unroll
-      for (int g4 = 0; g4 < 4; ++g4)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) ir[qi][g4][e] = 1.0f;
-  }
-  const int bcol = (ln % LPR) * 8;                    // phase B: this ln's 8 columns
-  const int64_t q0 = eQ0 + wave_q * WCOLS + bcol;
-  const bool q_full = q0 + 7 < g.Q;
-  float gw[8];
-  const float inv_k = DGE ? 1.0f / g.dge_k : 1.0f;
-  const float pw = inv_k - 1.0f;
-  if (DGE) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) gw[e] = gamma_w[min(q0 + e, g.Q - 1)];
-  }
-  static_for<4>([&](auto pc) {
-    constexpr int pj = decltype(pc)::value;
-    {
-      const int64_t p = min(eP0 + wave_p * 128 + pj * 32 + el32, g.P - 1);
-      float il = 1.0f;
-      if (scaled) il = __builtin_amdgcn_rcpf(gl[p]);
-      static_for<4 * QI>([&](auto ic) {
-        constexpr int qi = decltype(ic)::value / 4, g4 = decltype(ic)::value % 4;
-        f32x4 y;
-        const f32x16& a16 = acc[qi][pj];
-        y.x = a16[g4 * 4 + 0] * il * ir[qi][g4][0];
-        y.y = a16[g4 * 4 + 1] * il * ir[qi][g4][1];
-        y.z = a16[g4 * 4 + 2] * il * ir[qi][g4][2];
-        y.w = a16[g4 * 4 + 3] * il * ir[qi][g4][3];
-        *reinterpret_cast<f32x4*>(stage + el32 * EPI_LD + qi * 32 + g4 * 8 + elhi * 4) = y;
-      });
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int pass = 0; pass < EPI_ROWS / RPP; ++pass) {
-      const int rloc = pass * RPP + ln / LPR;
-      const int64_t p = eP0 + wave_p * 128 + pj * EPI_ROWS + rloc;
-      const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + rloc * EPI_LD + bcol);
-      const f32x4 v1 = *reinterpret_cast<const f32x4*>(stage + rloc * EPI_LD + bcol + 4);
-      float y[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-      if (p < g.P && q0 < g.Q) {
-        if (addend) {
-          const float* ad = addend + p * g.ldo + q0;
-          if (q_full) {
-            const f32x4 a0 = *reinterpret_cast<const f32x4*>(ad), a1 = *reinterpret_cast<const f32x4*>(ad + 4);
-            y[0] += a0.x; y[1] += a0.y; y[2] += a0.z; y[3] += a0.w;
-            y[4] += a1.x; y[5] += a1.y; y[6] += a1.z; y[7] += a1.w;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-              if (q0 + e < g.Q) y[e] += ad[e];
+          for (int e = 0; e < 4; ++e) {
+            const int64_t q = min(eQ0 + wave_q * WCOLS + qi * 32 + g4 * 8 + elhi * 4 + e, g.Q - 1);
+            ir[qi][g4][e] = __builtin_amdgcn_rcpf(gr[q]);
           }
-        }
-        if (DGE) {
-          float w[8];
-          if (W_BF16) {
-            const uint16_t* wp = reinterpret_cast<const uint16_t*>(Wp) + p * g.ldw + q0;
+    } else {
+#pragma unroll
+      for (int qi = 0; qi < QI; ++qi)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) ir[qi][g4][e] = 1.0f;
+    }
+    const int bcol = (ln % LPR) * 8;                    // phase B: this ln's 8 columns
+    const int64_t q0 = eQ0 + wave_q * WCOLS + bcol;
+    const bool q_full = q0 + 7 < g.Q;
+    float gw[8];
+    const float inv_k = DGE ? 1.0f / g.dge_k : 1.0f;
+    const float pw = inv_k - 1.0f;
+    if (DGE) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) gw[e] = gamma_w[min(q0 + e, g.Q - 1)];
+    }
+    static_for<4>([&](auto pc) {
+      constexpr int pj = decltype(pc)::value;
+      {
+        const int64_t p = min(eP0 + wave_p * 128 + pj * 32 + el32, g.P - 1);
+        float il = 1.0f;
+        if (scaled) il = __builtin_amdgcn_rcpf(gl[p]);
+        static_for<4 * QI>([&](auto ic) {
+          constexpr int qi = decltype(ic)::value / 4, g4 = decltype(ic)::value % 4;
+          f32x4 y;
+          const f32x16& a16 = acc[qi][pj];
+          y.x = a16[g4 * 4 + 0] * il * ir[qi][g4][0];
+          y.y = a16[g4 * 4 + 1] * il * ir[qi][g4][1];
+          y.z = a16[g4 * 4 + 2] * il * ir[qi][g4][2];
+          y.w = a16[g4 * 4 + 3] * il * ir[qi][g4][3];
+          *reinterpret_cast<f32x4*>(stage + el32 * EPI_LD + qi * 32 + g4 * 8 + elhi * 4) = y;
+        });
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int pass = 0; pass < EPI_ROWS / RPP; ++pass) {
+        const int rloc = pass * RPP + ln / LPR;
+        const int64_t p = eP0 + wave_p * 128 + pj * EPI_ROWS + rloc;
+        const f32x4 v0 = *reinterpret_cast<const f32x4*>(stage + rloc * EPI_LD + bcol);
+        const f32x4 v1 = *reinterpret_cast<const f32x4*>(stage + rloc * EPI_LD + bcol + 4);
+        float y[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+        if (p < g.P && q0 < g.Q) {
+          if (addend) {
+            const float* ad = addend + p * g.ldo + q0;
             if (q_full) {
-              const u32x4 r = *reinterpret_cast<const u32x4*>(wp);
-              w[0] = u2f(r.x << 16); w[1] = u2f(r.x & 0xffff0000u); w[2] = u2f(r.y << 16); w[3] = u2f(r.y & 0xffff0000u);
-              w[4] = u2f(r.z << 16); w[5] = u2f(r.z & 0xffff0000u); w[6] = u2f(r.w << 16); w[7] = u2f(r.w & 0xffff0000u);
+              const f32x4 a0 = *reinterpret_cast<const f32x4*>(ad), a1 = *reinterpret_cast<const f32x4*>(ad + 4);
+              y[0] += a0.x; y[1] += a0.y; y[2] += a0.z; y[3] += a0.w;
+              y[4] += a1.x; y[5] += a1.y; y[6] += a1.z; y[7] += a1.w;
             } else {
 #pragma unroll
-              for (int e = 0; e < 8; ++e) w[e] = q0 + e < g.Q ? bf16_bits_to_f32(wp[e]) : 0.0f;
+              for (int e = 0; e < 8; ++e)
+                if (q0 + e < g.Q) y[e] += ad[e];
+            }
+          }
+          if (DGE) {
+            float w[8];
+            if (W_BF16) {
+              const uint16_t* wp = reinterpret_cast<const uint16_t*>(Wp) + p * g.ldw + q0;
+              if (q_full) {
+                const u32x4 r = *reinterpret_cast<const u32x4*>(wp);
+                w[0] = u2f(r.x << 16); w[1] = u2f(r.x & 0xffff0000u);
+                w[2] = u2f(r.y << 16); w[3] = u2f(r.y & 0xffff0000u);
+                w[4] = u2f(r.z << 16); w[5] = u2f(r.z & 0xffff0000u);
+                w[6] = u2f(r.w << 16); w[7] = u2f(r.w & 0xffff0000u);
+              } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) w[e] = q0 + e < g.Q ? bf16_bits_to_f32(wp[e]) : 0.0f;
+              }
+            } else {
+              const float* wp = reinterpret_cast<const float*>(Wp) + p * g.ldw + q0;
+#pragma unroll
+              for (int e = 0; e < 8; ++e) w[e] = q0 + e < g.Q ? wp[e] : 0.0f;
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) y[e] *= dge_factor(w[e], gw[e], pw, inv_k, g.dge_cap);
+          }
+          if (OUT_BF16) {
+            uint16_t* o = reinterpret_cast<uint16_t*>(outp) + p * g.ldo + q0;
+            if (q_full) {
+              u32x4 pk;
+              pk.x = pack_bf16x2(y[0], y[1]);
+              pk.y = pack_bf16x2(y[2], y[3]);
+              pk.z = pack_bf16x2(y[4], y[5]);
+              pk.w = pack_bf16x2(y[6], y[7]);
+              *reinterpret_cast<u32x4*>(o) = pk;
+            } else {
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                if (q0 + e < g.Q) o[e] = (uint16_t)f32_to_bf16_bits(y[e]);
             }
           } else {
-            const float* wp = reinterpret_cast<const float*>(Wp) + p * g.ldw + q0;
+            float* o = reinterpret_cast<float*>(outp) + p * g.ldo + q0;
+            if (q_full) {
+              const f32x4 o0 = {y[0], y[1], y[2], y[3]}, o1 = {y[4], y[5], y[6], y[7]};
+              *reinterpret_cast<f32x4*>(o) = o0;
+              *reinterpret_cast<f32x4*>(o + 4) = o1;
+            } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) w[e] = q0 + e < g.Q ? wp[e] : 0.0f;
-          }
-#pragma unroll
-          for (int e = 0; e < 8; ++e) y[e] *= dge_factor(w[e], gw[e], pw, inv_k, g.dge_cap);
-        }
-        if (OUT_BF16) {
-          uint16_t* o = reinterpret_cast<uint16_t*>(outp) + p * g.ldo + q0;
-          if (q_full) {
-            u32x4 pk;
-            pk.x = pack_bf16x2(y[0], y[1]);
-            pk.y = pack_bf16x2(y[2], y[3]);
-            pk.z = pack_bf16x2(y[4], y[5]);
-            pk.w = pack_bf16x2(y[6], y[7]);
-            *reinterpret_cast<u32x4*>(o) = pk;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-              if (q0 + e < g.Q) o[e] = (uint16_t)f32_to_bf16_bits(y[e]);
-          }
-        } else {
-          float* o = reinterpret_cast<float*>(outp) + p * g.ldo + q0;
-          if (q_full) {
-            const f32x4 o0 = {y[0], y[1], y[2], y[3]}, o1 = {y[4], y[5], y[6], y[7]};
-            *reinterpret_cast<f32x4*>(o) = o0;
-            *reinterpret_cast<f32x4*>(o + 4) = o1;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-              if (q0 + e < g.Q) o[e] = y[e];
+              for (int e = 0; e < 8; ++e)
+                if (q0 + e < g.Q) o[e] = y[e];
+            }
           }
         }
       }
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-  });
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    });
   }  // edge tiles
   __syncthreads();   // the staging regions overlap stage 1 of the operands, which the next tile fills first thing
   if (!has_next) break;
